@@ -1,0 +1,231 @@
+"""ctypes front-end of the CPU oracle (test infrastructure, not the product).
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg import this.
+The HIP library never does, and this module imports nothing from it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "haq_oracle.cpp")
+_LIB = os.path.join(_DIR, "libhaq_oracle.so")
+
+CXXFLAGS = ["-O3", "-march=x86-64-v3", "-std=c++17", "-fno-fast-math", "-ffp-contract=off",
+            "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (a couple of seconds)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["g++", *CXXFLAGS, _SRC, "-o", tmp], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+    return _lib
+
+
+def _p(a: np.ndarray | None):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def half_to_float(h: np.ndarray) -> np.ndarray:
+    h = _c(h.view(np.uint16), np.uint16)
+    out = np.empty(h.shape, np.float32)
+    lib().oracle_half_to_float(_p(h), C.c_int64(h.size), _p(out))
+    return out
+
+
+def float_to_half(f: np.ndarray) -> np.ndarray:
+    f = _c(f, np.float32)
+    out = np.empty(f.shape, np.uint16)
+    lib().oracle_float_to_half(_p(f), C.c_int64(f.size), _p(out))
+    return out.view(np.float16)
+
+
+def exp_spec(t: np.ndarray) -> np.ndarray:
+    t = _c(t, np.float32)
+    out = np.empty(t.shape, np.float32)
+    lib().oracle_exp_spec(_p(t), C.c_int64(t.size), _p(out))
+    return out
+
+
+def col_absmax_f16(X: np.ndarray) -> np.ndarray:
+    X = _c(X, np.float16)
+    T, K = X.shape
+    ax = np.empty(K, np.float32)
+    lib().oracle_col_absmax_f16(_p(X), C.c_int64(K), T, K, _p(ax))
+    return ax
+
+
+def row_absmax_f32(W: np.ndarray, aw: np.ndarray | None = None) -> np.ndarray:
+    W = _c(W, np.float32)
+    K, N = W.shape
+    if aw is None:
+        aw = np.zeros(K, np.float32)
+    lib().oracle_row_absmax_f32(_p(W), K, N, _p(aw))
+    return aw
+
+
+def smoothing_vector(ax: np.ndarray, aw: np.ndarray | None, alpha: float = 0.5) -> np.ndarray:
+    ax = _c(ax, np.float32)
+    K = ax.size
+    s = np.empty(K, np.float32)
+    use_w = aw is not None
+    aw_ = _c(aw, np.float32) if use_w else None
+    lib().oracle_smoothing_vector(_p(ax), _p(aw_), K, C.c_double(alpha), int(use_w), _p(s))
+    return s
+
+
+def smooth_quant_act(X: np.ndarray, s: np.ndarray | None):
+    X = _c(X, np.float16)
+    T, K = X.shape
+    q = np.empty((T, K), np.int8)
+    sx = np.empty(T, np.float32)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_smooth_quant_act(_p(X), C.c_int64(K), _p(s_), T, K, _p(q), C.c_int64(K), _p(sx))
+    return q, sx
+
+
+def quant_weight(W: np.ndarray, s: np.ndarray | None):
+    W = _c(W, np.float32)
+    K, N = W.shape
+    Wq = np.empty((K, N), np.int8)
+    sw = np.empty(N, np.float32)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_quant_weight(_p(W), _p(s_), K, N, _p(Wq), _p(sw))
+    return Wq, sw
+
+
+def gemm_i8(q: np.ndarray, Wq: np.ndarray) -> np.ndarray:
+    q = _c(q, np.int8)
+    Wq = _c(Wq, np.int8)
+    T, K = q.shape
+    K2, N = Wq.shape
+    assert K == K2
+    acc = np.empty((T, N), np.int32)
+    lib().oracle_gemm_i8(_p(q), C.c_int64(K), _p(Wq), T, K, N, _p(acc))
+    return acc
+
+
+ACT = {"none": 0, "relu": 1}
+
+
+def epilogue(acc: np.ndarray, sx: np.ndarray, sw: np.ndarray, act: str = "none") -> np.ndarray:
+    acc = _c(acc, np.int32)
+    T, N = acc.shape
+    Y = np.empty((T, N), np.float16)
+    lib().oracle_epilogue(_p(acc), _p(_c(sx, np.float32)), _p(_c(sw, np.float32)), T, N, ACT[act],
+                          _p(Y), C.c_int64(N))
+    return Y
+
+
+def w8a8_linear(X, s, Wq, sw, act="none", full=False):
+    """The public linear: quantise activations, int8 GEMM, dequantise + activation."""
+    q, sx = smooth_quant_act(X, s)
+    acc = gemm_i8(q, Wq)
+    Y = epilogue(acc, sx, sw, act)
+    return (Y, acc, q, sx) if full else Y
+
+
+def route_top2(logits: np.ndarray):
+    logits = _c(logits, np.float16)
+    T, E = logits.shape
+    idx = np.empty((T, 2), np.int32)
+    gw = np.empty((T, 2), np.float32)
+    lib().oracle_route_top2(_p(logits), C.c_int64(E), T, E, _p(idx), _p(gw))
+    return idx, gw
+
+
+def permute(idx: np.ndarray, E: int):
+    idx = _c(idx, np.int32)
+    T = idx.shape[0]
+    counts = np.empty(E, np.int32)
+    offsets = np.empty(E + 1, np.int32)
+    perm = np.empty(2 * T, np.int32)
+    inv = np.empty(2 * T, np.int32)
+    lib().oracle_permute(_p(idx), T, E, _p(counts), _p(offsets), _p(perm), _p(inv))
+    return counts, offsets, perm, inv
+
+
+class _ExpertStruct(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w1", "w3", "w2", "sw1", "sw3", "sw2", "s_mid")]
+
+
+@dataclass
+class Expert:
+    """One expert's offline-quantised weights: int8 [H,I], [H,I], [I,H] + scales + s_mid."""
+    w1: np.ndarray
+    w3: np.ndarray
+    w2: np.ndarray
+    sw1: np.ndarray
+    sw3: np.ndarray
+    sw2: np.ndarray
+    s_mid: np.ndarray
+
+
+def _expert_array(experts: list[Expert]):
+    arr = (_ExpertStruct * len(experts))()
+    for i, e in enumerate(experts):
+        for n, dt in (("w1", np.int8), ("w3", np.int8), ("w2", np.int8), ("sw1", np.float32),
+                      ("sw3", np.float32), ("sw2", np.float32), ("s_mid", np.float32)):
+            a = getattr(e, n)
+            assert a.dtype == dt and a.flags.c_contiguous, n
+            setattr(arr[i], n, a.ctypes.data)
+    return arr
+
+
+def moe_ffn(X, idx, gw, s_in, experts: list[Expert], tokens=None, dumps=False):
+    X = _c(X, np.float16)
+    T, H = X.shape
+    I = experts[0].w1.shape[1]
+    idx = _c(idx, np.int32)
+    gw = _c(gw, np.float32)
+    tok = None if tokens is None else _c(tokens, np.int32)
+    n_tok = T if tok is None else tok.size
+    out = np.empty((n_tok, H), np.float16)
+    mid = hq = sh = y = None
+    if dumps:
+        mid = np.empty((2 * n_tok, I), np.float16)
+        hq = np.empty((2 * n_tok, I), np.int8)
+        sh = np.empty(2 * n_tok, np.float32)
+        y = np.empty((2 * n_tok, H), np.float16)
+    arr = _expert_array(experts)
+    lib().oracle_moe_ffn(_p(X), C.c_int64(H), _p(idx), _p(gw), _p(_c(s_in, np.float32)), arr, T, H, I,
+                         _p(tok), n_tok, _p(out), _p(mid), _p(hq), _p(sh), _p(y))
+    return (out, mid, hq, sh, y) if dumps else out
+
+
+def moe_mid_absmax(X, idx, s_in, experts: list[Expert]) -> np.ndarray:
+    X = _c(X, np.float16)
+    T, H = X.shape
+    I = experts[0].w1.shape[1]
+    E = len(experts)
+    ax = np.empty((E, I), np.float32)
+    arr = _expert_array(experts)
+    lib().oracle_moe_mid_absmax(_p(X), C.c_int64(H), _p(_c(idx, np.int32)), _p(_c(s_in, np.float32)), arr,
+                                T, H, I, E, _p(ax))
+    return ax

@@ -1,0 +1,437 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests calls the HIP library.  Each one is chosen so that a plausible
+mistake in the oracle (dropped term, wrong sign / axis / index, transposed operand,
+wrong rounding mode) fails it.  The paper prints no worked numerical example of the
+operator, so the pins are closed forms, invariants, brute force on tiny inputs,
+special cases that reduce to numpy routines and the a-priori quantisation error
+bound of Eq. 1's operator.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import haq_inputs as hi
+import oracle
+from tests import offline
+
+F32 = np.float32
+
+
+# ----------------------------------------------------------------- binary16 / exp
+def test_half_to_float_exhaustive():
+    h = np.arange(65536, dtype=np.uint16)
+    got = oracle.half_to_float(h)
+    ref = h.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got.view(np.uint32)[~nan], ref.view(np.uint32)[~nan])
+
+
+def test_float_to_half_rne_against_numpy():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(1_000_000).astype(F32) * F32(10.0) ** rng.integers(-9, 5, 1_000_000).astype(F32)
+    # exact halfway points between neighbouring halves, and the overflow boundary
+    h = np.arange(0, 0x7bff, dtype=np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi_ = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    mid = ((lo + hi_) / 2).astype(F32)
+    edge = np.array([65504, 65519.996, 65520, 65536, 1e30, 2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0001,
+                     2.0 ** -14, 2.0 ** -14 * 0.99999, 0.0, -0.0, np.inf, -np.inf], dtype=F32)
+    allx = np.concatenate([x, -x, mid, -mid, np.nextafter(mid, F32(0)), np.nextafter(mid, F32(1e9)), edge])
+    with np.errstate(over="ignore"):
+        ref = allx.astype(np.float16)
+    got = oracle.float_to_half(allx)
+    assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+
+
+def test_exp_spec_within_one_ulp_of_exp():
+    t = np.concatenate([np.linspace(-87, 88, 1_500_001), np.linspace(-1, 1, 500_001)]).astype(F32)
+    got = oracle.exp_spec(t).astype(np.float64)
+    ref = np.exp(t.astype(np.float64))
+    ulp = np.spacing(ref.astype(F32)).astype(np.float64)
+    assert np.max(np.abs(got - ref) / ulp) < 1.0
+    assert oracle.exp_spec(np.array([0.0], F32))[0] == 1.0
+    # clamped outside [-87, 88]
+    lo, hi_ = oracle.exp_spec(np.array([-87, 88], F32))
+    assert np.array_equal(oracle.exp_spec(np.array([-1e4, -np.inf, 1e4], F32)), np.array([lo, lo, hi_], F32))
+    # monotone on a coarse grid (catches a sign error in the reduction)
+    g = oracle.exp_spec(np.linspace(-80, 80, 1601).astype(F32))
+    assert np.all(np.diff(g) > 0)
+
+
+# ----------------------------------------------------------------- O1 activation quantisation
+def _acts(seed=0, T=33, K=200, **kw):
+    return hi.hidden_states(seed, T, K, **kw)[0]
+
+
+def test_act_quant_rounding_mode_and_scale():
+    # absmax 127 and s = 1 -> scale exactly 1 -> codes are rne(x): ties go to even
+    x = np.array([[127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5, 126.5, -126.5, 0.49, 0.51]], np.float16)
+    q, sx = oracle.smooth_quant_act(x, None)
+    assert sx[0] == 1.0
+    assert q[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 4, 126, -126, 0, 1]
+
+
+def test_act_quant_integer_identity_and_zero_row():
+    rng = np.random.default_rng(1)
+    X = rng.integers(-127, 128, size=(9, 64)).astype(np.float16)
+    X[:, 0] = 127
+    X[4] = 0
+    q, sx = oracle.smooth_quant_act(X, None)
+    keep = np.arange(9) != 4
+    assert np.array_equal(q[keep], X[keep].astype(np.int8)) and np.all(sx[keep] == 1.0)
+    assert np.all(q[4] == 0) and sx[4] == 0.0
+
+
+def test_act_quant_divides_by_s_per_channel():
+    # x/s = [127, 100] -> scale 1; a multiply, or s indexed by token, gives other codes
+    X = np.array([[254, 100], [-127, 200]], np.float16)
+    s = np.array([2, 1], F32)
+    q, sx = oracle.smooth_quant_act(X, s)
+    assert q.tolist() == [[127, 100], [-40, 127]]  # row 1: y = [-63.5, 200], scale 200/127
+    assert sx[0] == 1.0 and sx[1] == F32(200) / F32(127)
+    assert q[1, 0] == int(np.rint(F32(-63.5) / sx[1]))
+
+
+def test_act_quant_power_of_two_s_equals_prescaled_input():
+    X = _acts(2, 17, 96)
+    e = np.random.default_rng(2).integers(-3, 4, 96)
+    s = (2.0 ** e).astype(F32)
+    q1, sx1 = oracle.smooth_quant_act(X, s)
+    Xs = (X.astype(F32) / s).astype(np.float16)  # exact: power-of-two scaling, no overflow/underflow here
+    assert np.array_equal(Xs.astype(F32), X.astype(F32) / s)
+    q2, sx2 = oracle.smooth_quant_act(Xs, None)
+    assert np.array_equal(q1, q2) and np.array_equal(sx1, sx2)
+
+
+def test_act_quant_error_bound_and_range():
+    X = _acts(3, 64, 512, n_outlier=4)
+    s = np.exp(np.random.default_rng(3).normal(0, 1, 512)).astype(F32)
+    q, sx = oracle.smooth_quant_act(X, s)
+    y = (X.astype(F32) / s)  # numpy binary32 division is IEEE
+    assert q.min() >= -127 and q.max() <= 127
+    err = np.abs(y.astype(np.float64) - q.astype(np.float64) * sx[:, None].astype(np.float64))
+    assert np.all(err <= sx[:, None].astype(np.float64) / 2 * (1 + 2.0 ** -21))
+    # every non-zero row reaches +-127 at its absmax, and the scale is absmax/127 in binary32
+    a = np.abs(y).max(axis=1)
+    assert np.array_equal(sx, a / F32(127))
+    j = np.abs(y).argmax(axis=1)
+    assert np.all(np.abs(q[np.arange(64), j]) == 127)
+
+
+def test_act_quant_matches_numpy_binary32_recomputation():
+    X = _acts(4, 40, 300)
+    s = np.exp(np.random.default_rng(4).normal(0, 1, 300)).astype(F32)
+    q, sx = oracle.smooth_quant_act(X, s)
+    y = X.astype(F32) / s
+    sc = np.abs(y).max(axis=1) / F32(127)
+    ref = np.clip(np.rint(y / sc[:, None]), -127, 127).astype(np.int8)
+    assert np.array_equal(q, ref) and np.array_equal(sx, sc)
+
+
+# ----------------------------------------------------------------- O0 / O2 offline side
+def test_smoothing_vector_closed_forms():
+    ax = np.array([4, 16, 9, 0, 5, 1e12, 1e-12], F32)
+    aw = np.array([1, 4, 0.25, 3, 0, 1e-12, 1e12], F32)
+    s = oracle.smoothing_vector(ax, aw, 0.5)
+    assert s.tolist() == [2.0, 2.0, 6.0, 1.0, 1.0, F32(1e5), F32(1e-5)]
+    assert np.array_equal(oracle.smoothing_vector(ax[:3], aw[:3], 1.0), ax[:3])          # e = 1: s = s_X
+    assert np.array_equal(oracle.smoothing_vector(ax[:3], aw[:3], 0.0), 1 / aw[:3])      # e = 0: weight only
+    assert np.array_equal(oracle.smoothing_vector(ax[:3], None, 0.5), np.array([2, 4, 3], F32))  # Eq. 3 form
+    # general exponent against binary64 pow
+    rng = np.random.default_rng(5)
+    ax, aw = rng.uniform(0.1, 300, 100).astype(F32), rng.uniform(0.01, 1, 100).astype(F32)
+    ref = (ax.astype(np.float64) ** 0.3 / aw.astype(np.float64) ** 0.7).astype(F32)
+    assert np.array_equal(oracle.smoothing_vector(ax, aw, 0.3), ref)
+
+
+def test_absmax_reductions_axes():
+    X = np.array([[1, -7, 2], [-3, 4, 0.5]], np.float16)
+    assert oracle.col_absmax_f16(X).tolist() == [3, 7, 2]          # over tokens, per channel
+    W = np.array([[1, -9], [0.5, 0.25], [-2, 1]], F32)
+    assert oracle.row_absmax_f32(W).tolist() == [9, 0.5, 2]        # over outputs, per input channel
+    assert oracle.row_absmax_f32(W, np.array([1, 1, 1], F32)).tolist() == [9, 1, 2]  # folds into running max
+
+
+def test_weight_quant_scale_axis_and_smoothing_multiplies():
+    # column 0 has absmax 127 after smoothing, column 1 absmax 12.7: scales on the OUTPUT channel
+    W = np.array([[63.5, 1.0], [-100, 12.7]], F32)
+    s = np.array([2, 1], F32)  # W' = diag(s) W = [[127, 2], [-100, 12.7]]
+    Wq, sw = oracle.quant_weight(W, s)
+    assert sw[0] == 1.0 and sw[1] == F32(12.7) / F32(127)
+    assert Wq[:, 0].tolist() == [127, -100]
+    assert Wq[:, 1].tolist() == [20, 127]
+    # zero column
+    Wq, sw = oracle.quant_weight(np.array([[1, 0], [2, 0]], F32), None)
+    assert sw[1] == 0 and Wq[:, 1].tolist() == [0, 0] and Wq[:, 0].tolist() == [64, 127]
+
+
+def test_weight_quant_error_bound():
+    W = hi.gaussian_weight(6, 0, 300, 70)
+    s = np.exp(np.random.default_rng(6).normal(0, 1, 300)).astype(F32)
+    Wq, sw = oracle.quant_weight(W, s)
+    Ws = (s[:, None] * W)
+    err = np.abs(Ws.astype(np.float64) - Wq.astype(np.float64) * sw[None, :].astype(np.float64))
+    assert np.all(err <= sw[None, :].astype(np.float64) / 2 * (1 + 2.0 ** -21))
+    assert np.array_equal(sw, np.abs(Ws).max(axis=0) / F32(127))
+    assert np.all(np.abs(Wq).max(axis=0) == 127)
+
+
+def test_smoothing_invariance_fp64():
+    # X W = (X diag(s)^-1)(diag(s) W): the identity behind Eq. 1 / Algorithm 1 step 1
+    X = _acts(7, 20, 128).astype(np.float64)
+    W = hi.gaussian_weight(7, 0, 128, 48).astype(np.float64)
+    s = offline.quantize_linear(X.astype(np.float16), W.astype(F32))[0].astype(np.float64)
+    a, b = X @ W, (X / s[None, :]) @ (s[:, None] * W)
+    assert np.max(np.abs(a - b)) <= 1e-12 * np.max(np.abs(a))
+
+
+# ----------------------------------------------------------------- O3 GEMM
+def test_gemm_brute_force_tiny():
+    rng = np.random.default_rng(8)
+    for T, K, N in [(1, 1, 1), (2, 3, 5), (5, 8, 3), (8, 7, 8)]:
+        q = rng.integers(-127, 128, (T, K)).astype(np.int8)
+        W = rng.integers(-127, 128, (K, N)).astype(np.int8)
+        acc = oracle.gemm_i8(q, W)
+        for t, n in itertools.product(range(T), range(N)):
+            assert acc[t, n] == sum(int(q[t, k]) * int(W[k, n]) for k in range(K))
+
+
+def test_gemm_not_symmetric_inputs_vs_numpy_int64():
+    rng = np.random.default_rng(9)
+    q = rng.integers(-127, 128, (13, 257)).astype(np.int8)
+    W = rng.integers(-127, 128, (257, 31)).astype(np.int8)
+    assert np.array_equal(oracle.gemm_i8(q, W), (q.astype(np.int64) @ W.astype(np.int64)).astype(np.int32))
+
+
+def test_gemm_extreme_accumulators():
+    K = 16384
+    q = np.full((2, K), 127, np.int8)
+    q[1] = -127
+    W = np.full((K, 3), 127, np.int8)
+    W[:, 1] = -127
+    W[:, 2] = 1
+    acc = oracle.gemm_i8(q, W)
+    m = 127 * 127 * K
+    assert acc.tolist() == [[m, -m, 127 * K], [-m, m, -127 * K]]
+
+
+# ----------------------------------------------------------------- O4 epilogue, O1..O4 chain
+def test_epilogue_scale_orientation_relu_and_rounding():
+    acc = np.array([[1, -1, 3], [2, 5, -7]], np.int32)
+    sx = np.array([1, 2], F32)         # per token (row)
+    sw = np.array([1, 10, 100], F32)   # per output channel (column)
+    Y = oracle.epilogue(acc, sx, sw, "none").astype(F32)
+    assert Y.tolist() == [[1, -10, 300], [4, 100, -1400]]
+    Yr = oracle.epilogue(acc, sx, sw, "relu").astype(F32)
+    assert Yr.tolist() == [[1, 0, 300], [4, 100, 0]]
+    # binary16 rounding (2049 -> 2048, 2051 -> 2052: ties to even) and overflow to inf
+    Y = oracle.epilogue(np.array([[2049, 2051, 70000, -70000]], np.int32), np.ones(1, F32), np.ones(4, F32))
+    assert Y.astype(F32).tolist() == [[2048, 2052, np.inf, -np.inf]]
+
+
+def test_linear_integer_closed_form():
+    # integer X and W' with absmax 127 and s = 1: both scales are 1, Y = fp16(exact product)
+    rng = np.random.default_rng(10)
+    X = rng.integers(-5, 6, (6, 32)).astype(np.float16)
+    X[:, 0] = 127
+    W = rng.integers(-4, 5, (32, 10)).astype(F32)
+    W[0, :] = 127
+    Wq, sw = oracle.quant_weight(W, None)
+    assert np.all(sw == 1) and np.array_equal(Wq, W.astype(np.int8))
+    Y, acc, q, sx = oracle.w8a8_linear(X, None, Wq, sw, "none", full=True)
+    exact = X.astype(np.int64) @ W.astype(np.int64)
+    assert np.array_equal(acc, exact)
+    assert np.array_equal(Y, exact.astype(np.float16))
+
+
+def _apriori_bound(X, s, W, sx, sw):
+    """Per-output bound on |dequant(acc) - X W| from half-a-step errors of both operands."""
+    y = np.abs(X.astype(np.float64) / s[None, :])
+    w = np.abs(s[:, None].astype(np.float64) * W.astype(np.float64))
+    sx = sx.astype(np.float64)[:, None]
+    sw = sw.astype(np.float64)[None, :]
+    K = y.shape[1]
+    return y.sum(1, keepdims=True) * sw / 2 + sx / 2 * w.sum(0, keepdims=True) + K * sx * sw / 4
+
+
+def test_linear_within_apriori_bound_of_exact_product():
+    wl = hi.OPT125M_LINEAR
+    X, _, _ = hi.hidden_states(wl.seed, wl.T, wl.K, wl.n_outlier, wl.mult)
+    W = hi.gaussian_weight(wl.seed, 0, wl.K, 256)
+    s, Wq, sw = offline.quantize_linear(X, W)
+    Y, acc, q, sx = oracle.w8a8_linear(X, s, Wq, sw, "none", full=True)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    bound = _apriori_bound(X, s, W, sx, sw)
+    half_ulp = np.spacing(np.abs(Y).astype(np.float16)).astype(np.float64)
+    err = np.abs(Y.astype(np.float64) - exact)
+    assert np.all(err <= bound * (1 + 1e-5) + half_ulp)
+    # and it is a good approximation, not merely a bounded one
+    assert np.sqrt(np.mean(err ** 2)) < 0.02 * np.sqrt(np.mean(exact ** 2))
+
+
+def test_smoothing_reduces_joint_quantisation_error():
+    # Table I's ordering RTN > Smooth in proxy form: with outlier channels, alpha = 0.5 beats s = 1
+    X, _, _ = hi.hidden_states(11, 64, 512, 4, 50.0)
+    W = hi.gaussian_weight(11, 0, 512, 128)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    s, Wq, sw = offline.quantize_linear(X, W)
+    Wq1, sw1 = oracle.quant_weight(W, None)
+    mse_s = np.mean((oracle.w8a8_linear(X, s, Wq, sw).astype(np.float64) - exact) ** 2)
+    mse_1 = np.mean((oracle.w8a8_linear(X, None, Wq1, sw1).astype(np.float64) - exact) ** 2)
+    assert mse_s < 0.5 * mse_1
+
+
+# ----------------------------------------------------------------- O5 router
+def test_router_properties_and_closed_form():
+    rng = np.random.default_rng(12)
+    logits = (rng.standard_normal((500, 8)) * 3).astype(np.float16)
+    idx, gw = oracle.route_top2(logits)
+    l = logits.astype(np.float64)
+    order = np.argsort(-l, axis=1, kind="stable")
+    assert np.array_equal(idx, order[:, :2].astype(np.int32))
+    assert np.all(idx[:, 0] != idx[:, 1])
+    assert np.all(gw[:, 0] >= gw[:, 1]) and np.all(gw > 0)
+    assert np.max(np.abs(gw.sum(1) - 1)) <= 2 ** -22
+    l0 = np.take_along_axis(l, idx[:, :1].astype(np.int64), 1)[:, 0]
+    l1 = np.take_along_axis(l, idx[:, 1:].astype(np.int64), 1)[:, 0]
+    g0 = 1 / (1 + np.exp(l1 - l0))  # softmax renormalised over two = logistic of the logit gap
+    assert np.max(np.abs(gw[:, 0] - g0)) < 5e-7
+
+
+def test_router_ties_pick_lowest_index():
+    logits = np.array([[1, 1, 1, 1], [0, 2, 2, 1], [3, 0, 3, 3], [-1, -1, 5, -1], [0, 0, 0, 7]], np.float16)
+    idx, gw = oracle.route_top2(logits)
+    assert idx.tolist() == [[0, 1], [1, 2], [0, 2], [2, 0], [3, 0]]
+    assert gw[0].tolist() == [0.5, 0.5] and gw[1].tolist() == [0.5, 0.5]
+
+
+# ----------------------------------------------------------------- O6 permutation
+def test_permutation_properties():
+    rng = np.random.default_rng(13)
+    T, E = 301, 8
+    idx = np.stack([rng.permutation(E)[:2] for _ in range(T)]).astype(np.int32)
+    idx[idx == 5] = 4  # expert 5 gets nothing; duplicates in a token are still legal input here
+    counts, offsets, perm, inv = oracle.permute(idx, E)
+    flat = idx.ravel()
+    assert np.array_equal(counts, np.bincount(flat, minlength=E))
+    assert counts[5] == 0 and counts.sum() == 2 * T
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(counts)]))
+    assert np.array_equal(np.sort(perm), np.arange(2 * T))
+    assert np.array_equal(inv[perm], np.arange(2 * T)) and np.array_equal(perm[inv], np.arange(2 * T))
+    for e in range(E):
+        seg = perm[offsets[e]:offsets[e + 1]]
+        assert np.all(flat[seg] == e) and np.all(np.diff(seg) > 0)  # grouped by expert, stable inside
+    assert np.array_equal(perm, np.argsort(flat, kind="stable"))
+
+
+# ----------------------------------------------------------------- O7 / O8 routed expert FFN
+def _float_moe_reference(X, weights, idx, gw):
+    """Unquantised binary64 top-2 SwiGLU MoE."""
+    X = X.astype(np.float64)
+    out = np.zeros((X.shape[0], weights[0][2].shape[1]))
+    for t in range(X.shape[0]):
+        for k in range(2):
+            w1, w3, w2 = (w.astype(np.float64) for w in weights[idx[t, k]])
+            g, u = X[t] @ w1, X[t] @ w3
+            out[t] += gw[t, k] * ((g / (1 + np.exp(-g)) * u) @ w2)
+    return out
+
+
+def test_moe_close_to_float_reference():
+    m = offline.small_moe(seed=14, T=24, H=128, I=320, E=8)
+    out = oracle.moe_ffn(m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]).astype(np.float64)
+    ref = _float_moe_reference(m["X"], m["weights"], m["idx"], m["gw"].astype(np.float64))
+    rel = np.sqrt(np.mean((out - ref) ** 2) / np.mean(ref ** 2))
+    assert rel < 0.03, rel
+
+
+def _chain_from_pinned_pieces(X, idx, gw, s_in, experts):
+    """The same layer assembled in Python from the separately pinned pieces."""
+    T, H = X.shape
+    q, sx = oracle.smooth_quant_act(X, s_in)
+    out = np.zeros((T, H), np.float16)
+    for t in range(T):
+        ys = []
+        for k in range(2):
+            ex = experts[idx[t, k]]
+            a1, a3 = oracle.gemm_i8(q[t:t + 1], ex.w1)[0], oracle.gemm_i8(q[t:t + 1], ex.w3)[0]
+            g = (a1.astype(F32) * sx[t]) * ex.sw1
+            u = (a3.astype(F32) * sx[t]) * ex.sw3
+            silu = g / (F32(1) + oracle.exp_spec(-g))
+            h = oracle.float_to_half(silu * u)
+            y = oracle.w8a8_linear(h[None, :], ex.s_mid, ex.w2, ex.sw2)[0]
+            ys.append(y.astype(F32))
+        out[t] = oracle.float_to_half(gw[t, 0] * ys[0] + gw[t, 1] * ys[1])
+    return out
+
+
+def test_moe_equals_chain_of_pinned_pieces_and_token_subset():
+    m = offline.small_moe(seed=15, T=19, H=128, I=192, E=8)
+    X, idx, gw, s_in, ex = m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]
+    out, mid, hq, sh, y = oracle.moe_ffn(X, idx, gw, s_in, ex, dumps=True)
+    assert np.array_equal(out.view(np.uint16), _chain_from_pinned_pieces(X, idx, gw, s_in, ex).view(np.uint16))
+    tok = np.array([17, 3, 3, 0], np.int32)
+    sub, mid_s, hq_s, sh_s, y_s = oracle.moe_ffn(X, idx, gw, s_in, ex, tokens=tok, dumps=True)
+    assert np.array_equal(sub.view(np.uint16), out[tok].view(np.uint16))
+    rows = (2 * tok[:, None] + np.arange(2)[None, :]).ravel()
+    assert np.array_equal(mid_s.view(np.uint16), mid[rows].view(np.uint16))
+    assert np.array_equal(hq_s, hq[rows]) and np.array_equal(sh_s, sh[rows])
+    assert np.array_equal(y_s.view(np.uint16), y[rows].view(np.uint16))
+    # the requantised intermediate is O1 applied to the fp16 intermediate with the expert's s_mid
+    r = 5
+    e = idx.ravel()[r]
+    q_r, s_r = oracle.smooth_quant_act(mid[r:r + 1], ex[e].s_mid)
+    assert np.array_equal(q_r[0], hq[r]) and s_r[0] == sh[r]
+
+
+def test_moe_identical_experts_reduce_to_dense_ffn():
+    # with the same weights in every expert the gate weights (g0 + g1 = 1) drop out
+    m = offline.small_moe(seed=16, T=11, H=128, I=192, E=4)
+    ex0 = m["experts"][0]
+    same = [ex0] * 4
+    out, _, _, _, y = oracle.moe_ffn(m["X"], m["idx"], m["gw"], m["s_in"], same, dumps=True)
+    assert np.array_equal(y[0::2].view(np.uint16), y[1::2].view(np.uint16))
+    dense = y[0::2].astype(np.float64)
+    assert np.max(np.abs(out.astype(np.float64) - dense)) <= np.max(np.spacing(np.abs(y[0::2]))) * 1.01
+
+
+def test_moe_two_experts_every_token_visits_both():
+    m = offline.small_moe(seed=17, T=9, H=128, I=192, E=2)
+    assert np.all(np.sort(m["idx"], axis=1) == np.array([0, 1]))
+    out = oracle.moe_ffn(m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]).astype(np.float64)
+    ref = _float_moe_reference(m["X"], m["weights"], m["idx"], m["gw"].astype(np.float64))
+    assert np.sqrt(np.mean((out - ref) ** 2) / np.mean(ref ** 2)) < 0.03
+
+
+def test_mid_absmax_matches_dumped_intermediate():
+    m = offline.small_moe(seed=18, T=21, H=128, I=192, E=8)
+    _, mid, _, _, _ = oracle.moe_ffn(m["X"], m["idx"], m["gw"], m["s_in"], m["experts"], dumps=True)
+    ax = oracle.moe_mid_absmax(m["X"], m["idx"], m["s_in"], m["experts"])
+    flat = m["idx"].ravel()
+    for e in range(8):
+        rows = np.abs(mid[flat == e].astype(F32))
+        ref = rows.max(axis=0) if rows.size else np.zeros(192, F32)
+        assert np.array_equal(ax[e], ref)
+
+
+# ----------------------------------------------------------------- input recipe sanity
+def test_zipf_router_bias_reaches_target_popularity():
+    wl = hi.MoeWorkload("zipf_small", 19, 2048, 256, 64, 8, "zipf")
+    X, _, _ = hi.hidden_states(wl.seed, wl.T, wl.H)
+    idx, _ = oracle.route_top2(hi.moe_logits(wl, X))
+    share = np.bincount(idx.ravel(), minlength=8) / (2 * wl.T)
+    assert np.max(np.abs(share - hi.zipf_shares(8))) < 0.02
+    assert np.all(np.diff(share) < 0.01)
+
+
+def test_outlier_channels_are_fixed_and_large():
+    X, idx, mult = hi.hidden_states(1, 256, 4096)
+    assert idx.size == 21 or idx.size == 20
+    a = np.abs(X.astype(F32)).max(axis=0)
+    rest = np.delete(a, idx)
+    assert a[idx].min() > 3 * rest.max()
+    X2, idx2, _ = hi.hidden_states(1, 64, 4096)
+    assert np.array_equal(idx, idx2)
