@@ -48,20 +48,23 @@ def outlier_channels(seed: int, K: int, n_outlier: int) -> np.ndarray:
 
 
 def hidden_states(seed: int, T: int, K: int, n_outlier: int | None = None,
-                  mult: float | tuple[float, float] = (20.0, 80.0)
-                  ) -> tuple[np.ndarray, np.ndarray, np.ndarray]:
+                  mult: float | tuple[float, float] = (20.0, 80.0),
+                  channel_seed: int | None = None) -> tuple[np.ndarray, np.ndarray, np.ndarray]:
     """fp16 activations [T, K] ~ N(0,1) with fixed outlier channels scaled up.
 
     n_outlier defaults to ceil(0.5% of K).  `mult` is either one multiplier for
     every outlier channel or a (lo, hi) range from which one multiplier per
     outlier channel is drawn uniformly.  The multiplier is applied in fp32
     before the single rounding to fp16.  Returns (X, channel_idx, channel_mult).
+    The outlier channels and their multipliers belong to the layer, not to the
+    batch: `channel_seed` (default: `seed`) selects them, `seed` the token values.
     """
     if n_outlier is None:
         n_outlier = int(math.ceil(0.005 * K))
-    idx = outlier_channels(seed, K, n_outlier)
+    cs = seed if channel_seed is None else channel_seed
+    idx = outlier_channels(cs, K, n_outlier)
     if isinstance(mult, tuple):
-        m = _rng(seed, _S_OUTLIER_MUL).uniform(mult[0], mult[1], size=n_outlier).astype(np.float32)
+        m = _rng(cs, _S_OUTLIER_MUL).uniform(mult[0], mult[1], size=n_outlier).astype(np.float32)
     else:
         m = np.full(n_outlier, mult, dtype=np.float32)
     x = _rng(seed, _S_X).standard_normal(size=(T, K), dtype=np.float32)
@@ -165,13 +168,28 @@ class MoeWorkload:
     E: int = MIXTRAL_E
     routing: str = "gate"  # "gate" | "zipf" | "popularity"
     resident: tuple[int, ...] = field(default_factory=tuple)  # empty = all resident
+    layer_seed: int | None = None  # seed of the layer (weights, gate, outlier channels); default: seed
 
 
 OPT125M_LINEAR = LinearWorkload("opt125m_linear", 0, 16, 768, 3072, 4, 50.0, "relu")
 OPT67B_FFN = FfnWorkload("opt6.7b_ffn", 1, 2048, 4096, 16384, 20)
-MIXTRAL_DECODE = tuple(MoeWorkload(f"mixtral_decode_b{b}", 2, b) for b in (1, 8, 64))
-MIXTRAL_PREFILL = MoeWorkload("mixtral_prefill_zipf", 3, 4096, routing="zipf")
-MIXTRAL_OFFLOAD = MoeWorkload("mixtral_offload_b256", 4, 256, routing="popularity", resident=(0, 1, 2, 3))
+# One Mixtral-shaped layer (weights, router gate, outlier channels: seed 2) serves the
+# decode, prefill and offload workloads; each workload draws its own tokens.
+MIXTRAL_LAYER_SEED = 2
+MIXTRAL_DECODE = tuple(MoeWorkload(f"mixtral_decode_b{b}", 2, b, layer_seed=MIXTRAL_LAYER_SEED) for b in (1, 8, 64))
+MIXTRAL_PREFILL = MoeWorkload("mixtral_prefill_zipf", 3, 4096, routing="zipf", layer_seed=MIXTRAL_LAYER_SEED)
+MIXTRAL_OFFLOAD = MoeWorkload("mixtral_offload_b256", 4, 256, routing="popularity", resident=(0, 1, 2, 3),
+                              layer_seed=MIXTRAL_LAYER_SEED)
+MIXTRAL_CALIB = MoeWorkload("mixtral_calibration", 2, 256, layer_seed=MIXTRAL_LAYER_SEED)
+
+
+def _layer_seed(wl: MoeWorkload) -> int:
+    return wl.seed if wl.layer_seed is None else wl.layer_seed
+
+
+def moe_hidden_states(wl: MoeWorkload) -> np.ndarray:
+    """The workload's token batch: its own values, the layer's outlier channels."""
+    return hidden_states(wl.seed, wl.T, wl.H, channel_seed=_layer_seed(wl))[0]
 
 
 def moe_logits(wl: MoeWorkload, X: np.ndarray) -> np.ndarray:
@@ -179,7 +197,7 @@ def moe_logits(wl: MoeWorkload, X: np.ndarray) -> np.ndarray:
     if wl.routing == "popularity":
         assert wl.E == len(OFFLOAD_POPULARITY)
         return gumbel_logits(wl.seed, wl.T)
-    gate = router_gate(wl.seed, wl.H, wl.E)
+    gate = router_gate(_layer_seed(wl), wl.H, wl.E)
     if wl.routing == "zipf":
         bias = fit_router_bias(X, gate, zipf_shares(wl.E))
         return gate_logits(X, gate, bias)
@@ -190,5 +208,5 @@ def moe_weight(wl: MoeWorkload, e: int, which: str) -> np.ndarray:
     """fp32 weight of expert e; which in {"w1","w3"} -> [H, I], "w2" -> [I, H]."""
     j = {"w1": 0, "w3": 1, "w2": 2}[which]
     if which == "w2":
-        return gaussian_weight(wl.seed, 3 * e + j, wl.I, wl.H)
-    return gaussian_weight(wl.seed, 3 * e + j, wl.H, wl.I)
+        return gaussian_weight(_layer_seed(wl), 3 * e + j, wl.I, wl.H)
+    return gaussian_weight(_layer_seed(wl), 3 * e + j, wl.H, wl.I)

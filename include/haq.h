@@ -1,0 +1,194 @@
+/*
+ * haq.h - C ABI of the MI355X (gfx950) library for the smoothed W8A8 expert FFN
+ * of HAQ (arXiv 2508.07329, Section III.B).
+ *
+ * Operator (Section III.B.1, Eq. 1):  Y = Q(W s) Q(s^-1 X).  Here activations
+ * are X [T x K] (one token per row) and weights W [K x N] (input channel major),
+ * the transpose of the paper's W X.  Quantisation scales sit on the outer
+ * dimensions only (Section III.B.1, last paragraph): one scale per token for the
+ * activations, one per output channel for the weights.  Both operands are
+ * symmetric int8 in [-127, 127].
+ *
+ * Conventions for every entry point
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - Buffers are owned by the caller.  Work is enqueued on `stream` (a
+ *    hipStream_t passed as void*; NULL = the default stream) and the call
+ *    returns without synchronising; buffers must stay alive until the stream
+ *    has drained.  The library allocates nothing on these calls: scratch comes
+ *    from the caller's workspace, sized by the matching *_workspace_bytes query.
+ *  - Arguments are validated on the host before any HIP call.  Return value:
+ *    HAQ_OK or a negative HAQ_ERR_*; haq_last_error() gives a thread-local text.
+ *  - Device pointers must be 16-byte aligned; leading dimensions are in
+ *    elements; K (the contracted dimension) must be a multiple of 64.
+ *  - Arithmetic is IEEE binary32 with one rounding per operation, int32
+ *    accumulation, round-half-to-even; results do not depend on launch shape.
+ */
+#ifndef HAQ_H
+#define HAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HAQ_OK 0
+#define HAQ_ERR_INVALID_ARG (-1) /* null / negative / misaligned argument */
+#define HAQ_ERR_UNSUPPORTED (-2) /* shape or enum the kernels do not cover */
+#define HAQ_ERR_WORKSPACE (-3)   /* workspace missing or too small */
+#define HAQ_ERR_HIP (-4)         /* a HIP call failed */
+
+#define HAQ_ACT_NONE 0
+#define HAQ_ACT_RELU 1
+
+#define HAQ_LOC_DEVICE 0      /* expert weights live in HBM */
+#define HAQ_LOC_HOST_PINNED 1 /* expert weights live in pinned host memory and are streamed in */
+
+int32_t haq_version(void);
+const char* haq_last_error(void); /* host string, valid until the thread's next failing call */
+
+/* ------------------------------------------------------------------------
+ * Activation operand of Eq. 1, Q(s^-1 X), scale on the token dimension.
+ *   y = x / s_k (binary32 divide);  scale_t = max_k |y| / 127;
+ *   q = clamp(rne(y / scale_t), -127, 127).   A zero row gives scale 0, codes 0.
+ * x_fp16 [T x K] row-major (row stride ldx), s [K] (> 0, finite) or NULL for all
+ * ones.  Outputs q int8 [T x K] (row stride ldq) and row_scale [T].
+ * T >= 0 (T == 0 is a no-op), K % 64 == 0, K <= 65536.
+ */
+int32_t haq_smooth_quant_act(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K,
+                             int8_t* q, int64_t ldq, float* row_scale, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Offline side of Eq. 1 / Algorithm 1 step 1 for a fixed exponent (the values
+ * the hot path consumes are produced once, outside the timed path).
+ *
+ * haq_channel_absmax_f16: ax[k] = max(ax[k], max_t |X[t][k]|)  - the per-channel
+ *   activation magnitude s_X of Eq. 3.  Folds into ax (caller zeroes it first).
+ * haq_weight_row_absmax: aw[k] = max(aw[k], max_n |W[k][n]|), W fp32 [K x N].
+ * haq_smoothing_vector (HOST pointers): s_k = ax_k^alpha / aw_k^(1-alpha) in
+ *   binary64, rounded to binary32, clamped to [1e-5, 1e5]; 1 where ax_k or aw_k
+ *   is 0.  aw == NULL gives Eq. 3's activation-only form s_k = ax_k^alpha.
+ * haq_quant_weight: Q(W s) with one scale per output channel.  W fp32 [K x N],
+ *   s [K] or NULL; outputs wq int8 [K x N] (canonical layout) and w_scale [N].
+ */
+int32_t haq_channel_absmax_f16(const void* x_fp16, int64_t ldx, int32_t T, int32_t K, float* ax, void* stream);
+int32_t haq_weight_row_absmax(const float* w, int32_t K, int32_t N, float* aw, void* stream);
+int32_t haq_smoothing_vector(const float* ax_host, const float* aw_host, int32_t K, double alpha, float* s_host);
+int32_t haq_quant_weight(const float* w, const float* s, int32_t K, int32_t N, int8_t* wq, float* w_scale,
+                         void* stream);
+
+/* ------------------------------------------------------------------------
+ * Weight layout for the MFMA kernels (offline, Algorithm 1 step 3 keeps int8
+ * weights on the GPU in the form its kernels consume).
+ *
+ * Packed layout of a [K x N] int8 matrix: [K/16][Npad][16] - for each group of
+ * 16 consecutive input channels, all output channels side by side, each with its
+ * 16 bytes.  Npad = N rounded up to a multiple of 256; padding is zero.
+ * haq_packed_bytes(K, N) gives the size.  haq_pack_weight converts the canonical
+ * row-major [K x N] matrix.  haq_pack_gate_up interleaves the gate (w1) and up
+ * (w3) matrices of a SwiGLU expert, both [K x N], into one packed [K x 2N]
+ * matrix whose output channels alternate in blocks of 32: 32 of w1, the same 32
+ * of w3, and so on (N % 32 == 0).
+ */
+size_t haq_packed_bytes(int32_t K, int32_t N);
+int32_t haq_pack_weight(const int8_t* wq, int32_t K, int32_t N, int8_t* packed, void* stream);
+int32_t haq_pack_gate_up(const int8_t* w1q, const int8_t* w3q, int32_t K, int32_t N, int8_t* packed, void* stream);
+
+/* ------------------------------------------------------------------------
+ * One smoothed W8A8 linear layer (Eq. 1 evaluated at run time):
+ *   q, sx = Q(s^-1 X);  acc = q Wq (int32);  r = (float(acc) * sx_t) * sw_n;
+ *   act;  Y = fp16(r).
+ * x_fp16 [T x K], s [K] or NULL, w_packed from haq_pack_weight, w_scale [N].
+ * Y fp16 [T x N] (row stride ldy).  Optional outputs (NULL to skip): acc_dbg
+ * int32 [T x N] dense, q_dbg int8 [T x K] dense, sx_dbg [T].
+ * T >= 0, K % 64 == 0, N % 16 == 0.
+ */
+size_t haq_linear_workspace_bytes(int32_t T, int32_t K, int32_t N);
+
+/* The two stages of haq_w8a8_linear as calls of their own (same kernels, same
+ * results), for callers that keep activations in int8 between layers or time the
+ * stages separately.  The packed activation layout is that of the weights:
+ * [K/16][R][16] with R = haq_packed_act_rows(T) rows (T rounded up to 16, plus
+ * one 256-row tile of slack that the GEMM may read but never uses); its size is
+ * haq_packed_act_bytes(T, K) = K * R.
+ * haq_quant_act_packed: Q(s^-1 X) as in haq_smooth_quant_act, codes written in
+ *   the packed layout.  haq_gemm_w8a8_packed: int8 GEMM + dequantise + activation
+ *   on such codes; row_scale [T], y fp16 [T x N]; acc_dbg optional.            */
+int64_t haq_packed_act_rows(int32_t T);
+size_t haq_packed_act_bytes(int32_t T, int32_t K);
+int32_t haq_quant_act_packed(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K,
+                             int8_t* q_packed, float* row_scale, void* stream);
+int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, const int8_t* w_packed,
+                             const float* w_scale, int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16,
+                             int64_t ldy, int32_t* acc_dbg, void* stream);
+int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const int8_t* w_packed,
+                        const float* w_scale, int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16,
+                        int64_t ldy, int32_t* acc_dbg, int8_t* q_dbg, float* sx_dbg, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Top-2 routed SwiGLU expert FFN with W8A8 experts.
+ *
+ * Per token t: top-2 experts by router logit (lowest index wins ties); gate
+ * weights = softmax over all E logits, renormalised over the two.  The token is
+ * quantised once with s_in (shared by the gate/up projections of all experts,
+ * which all see the same X).  Per (token, expert) pair:
+ *   g = deq(q w1), u = deq(q w3), h = fp16(silu(g) * u);
+ *   hq, sh = Q(s_mid^-1 h);  y = fp16(deq(hq w2));
+ * out[t] = fp16(g0 * y0 + g1 * y1).  silu(g) = g / (1 + e^-g) with e^t evaluated
+ * by a fixed binary32 sequence (two-part ln 2 reduction, degree-7 Horner with
+ * FMAs), so that codes and outputs are reproducible bit for bit.
+ *
+ * Pairs are processed grouped by expert: pair id r = 2t + k, sorted by
+ * (expert, r) (stable), which is what the debug arrays expose.
+ */
+typedef struct haq_expert_desc {
+    const int8_t* w13;  /* packed gate/up [H x 2I] from haq_pack_gate_up; device, or pinned HOST if location says so */
+    const int8_t* w2;   /* packed down [I x H] from haq_pack_weight; same location as w13 */
+    const float* sw1;   /* [I] device */
+    const float* sw3;   /* [I] device */
+    const float* sw2;   /* [H] device */
+    const float* s_mid; /* [I] device, smoothing vector of the down projection */
+    int32_t location;   /* HAQ_LOC_DEVICE or HAQ_LOC_HOST_PINNED */
+    int32_t reserved;
+} haq_expert_desc;
+
+typedef struct haq_moe_debug { /* every field optional (NULL to skip); all device pointers */
+    int32_t* topk_idx; /* [T x 2] */
+    float* topk_w;     /* [T x 2] */
+    int32_t* counts;   /* [E] */
+    int32_t* offsets;  /* [E + 1] */
+    int32_t* perm;     /* [2T] pair id at each sorted position */
+    int32_t* inv;      /* [2T] sorted position of each pair id */
+    int8_t* q;         /* [T x H] dense, codes of the tokens */
+    float* sx;         /* [T] */
+    void* mid_fp16;    /* [2T x I] dense, sorted order */
+    int8_t* hq;        /* [2T x I] dense, sorted order */
+    float* sh;         /* [2T] sorted order */
+    void* y_fp16;      /* [2T x H] dense, sorted order */
+} haq_moe_debug;
+
+/* Context for layers with host-resident experts: owns a side stream, events and
+ * `n_slots` HBM staging slots, each large enough for one expert of the given
+ * geometry.  Creating and destroying it allocates / frees; the FFN call does not. */
+typedef struct haq_ctx haq_ctx;
+int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out_host);
+int32_t haq_ctx_destroy(haq_ctx* ctx);
+
+size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
+
+/* experts: HOST array of E descriptors (read during the call only).  ctx may be
+ * NULL when every expert is device resident.  2 <= E <= 32, top_k must be 2,
+ * H % 64 == 0, I % 64 == 0.  Host-resident experts are copied into the
+ * context's staging slots with hipMemcpyAsync on its side stream while resident
+ * experts compute; results are identical to the all-resident call.           */
+int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl,
+                         const float* s_in, const haq_expert_desc* experts_host, int32_t T, int32_t H, int32_t I,
+                         int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg_host,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAQ_H */

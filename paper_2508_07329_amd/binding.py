@@ -1,0 +1,279 @@
+"""ctypes binding of libhaq.so: argument marshalling only.
+
+Function names are those of include/haq.h.  Tensors are torch tensors on the GPU
+(they own the memory); work is enqueued on torch's current stream.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+__all__ = [
+    "HaqError", "lib", "haq_version", "haq_smooth_quant_act", "haq_channel_absmax_f16", "haq_weight_row_absmax",
+    "haq_smoothing_vector", "haq_quant_weight", "haq_packed_bytes", "haq_pack_weight", "haq_pack_gate_up",
+    "haq_linear_workspace_bytes", "haq_w8a8_linear", "haq_packed_act_rows", "haq_packed_act_bytes",
+    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
+    "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
+    "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
+]
+
+HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
+HAQ_LOC_DEVICE, HAQ_LOC_HOST_PINNED = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libhaq.so")
+
+EXPORTED_SYMBOLS = [
+    "haq_version", "haq_last_error", "haq_smooth_quant_act", "haq_channel_absmax_f16", "haq_weight_row_absmax",
+    "haq_smoothing_vector", "haq_quant_weight", "haq_packed_bytes", "haq_pack_weight", "haq_pack_gate_up",
+    "haq_linear_workspace_bytes", "haq_w8a8_linear", "haq_packed_act_rows", "haq_packed_act_bytes",
+    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ctx_create", "haq_ctx_destroy",
+    "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
+]
+
+
+class HaqError(RuntimeError):
+    pass
+
+
+class _ExpertDesc(C.Structure):
+    _fields_ = [("w13", C.c_void_p), ("w2", C.c_void_p), ("sw1", C.c_void_p), ("sw3", C.c_void_p),
+                ("sw2", C.c_void_p), ("s_mid", C.c_void_p), ("location", C.c_int32), ("reserved", C.c_int32)]
+
+
+_DBG_FIELDS = ("topk_idx", "topk_w", "counts", "offsets", "perm", "inv", "q", "sx", "mid_fp16", "hq", "sh", "y_fp16")
+
+
+class _MoeDebug(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _DBG_FIELDS]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libhaq.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from .build import build
+            build()
+        L = C.CDLL(LIB_PATH)
+        L.haq_last_error.restype = C.c_char_p
+        for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes"):
+            getattr(L, n).restype = C.c_size_t
+        L.haq_packed_act_rows.restype = C.c_int64
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise HaqError(f"libhaq error {rc}: {lib().haq_last_error().decode()}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def haq_version() -> int:
+    return int(lib().haq_version())
+
+
+def haq_smooth_quant_act(x: torch.Tensor, s: torch.Tensor | None):
+    """x fp16 [T,K], s fp32 [K] or None -> (q int8 [T,K], row_scale fp32 [T])."""
+    T, K = x.shape
+    q = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    sx = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _check(lib().haq_smooth_quant_act(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), T, K, _ptr(q), C.c_int64(K),
+                                      _ptr(sx), _stream()))
+    return q, sx
+
+
+def haq_channel_absmax_f16(x: torch.Tensor, ax: torch.Tensor | None = None) -> torch.Tensor:
+    T, K = x.shape
+    if ax is None:
+        ax = torch.zeros((K,), dtype=torch.float32, device=x.device)
+    _check(lib().haq_channel_absmax_f16(_ptr(x), C.c_int64(x.stride(0)), T, K, _ptr(ax), _stream()))
+    return ax
+
+
+def haq_weight_row_absmax(w: torch.Tensor, aw: torch.Tensor | None = None) -> torch.Tensor:
+    K, N = w.shape
+    if aw is None:
+        aw = torch.zeros((K,), dtype=torch.float32, device=w.device)
+    _check(lib().haq_weight_row_absmax(_ptr(w), K, N, _ptr(aw), _stream()))
+    return aw
+
+
+def haq_smoothing_vector(ax: torch.Tensor, aw: torch.Tensor | None, alpha: float = 0.5) -> torch.Tensor:
+    """Host-side formula on host copies of the magnitudes; returns s on ax's device."""
+    ax_h = ax.detach().to("cpu", torch.float32).contiguous()
+    aw_h = None if aw is None else aw.detach().to("cpu", torch.float32).contiguous()
+    s_h = torch.empty_like(ax_h)
+    _check(lib().haq_smoothing_vector(_ptr(ax_h), _ptr(aw_h), ax_h.numel(), C.c_double(alpha), _ptr(s_h)))
+    return s_h.to(ax.device)
+
+
+def haq_quant_weight(w: torch.Tensor, s: torch.Tensor | None):
+    """w fp32 [K,N] -> (wq int8 [K,N] canonical, w_scale fp32 [N])."""
+    K, N = w.shape
+    wq = torch.empty((K, N), dtype=torch.int8, device=w.device)
+    sw = torch.empty((N,), dtype=torch.float32, device=w.device)
+    _check(lib().haq_quant_weight(_ptr(w), _ptr(s), K, N, _ptr(wq), _ptr(sw), _stream()))
+    return wq, sw
+
+
+def haq_packed_bytes(K: int, N: int) -> int:
+    return int(lib().haq_packed_bytes(K, N))
+
+
+def haq_pack_weight(wq: torch.Tensor) -> torch.Tensor:
+    K, N = wq.shape
+    out = torch.empty((haq_packed_bytes(K, N),), dtype=torch.int8, device=wq.device)
+    _check(lib().haq_pack_weight(_ptr(wq), K, N, _ptr(out), _stream()))
+    return out
+
+
+def haq_pack_gate_up(w1q: torch.Tensor, w3q: torch.Tensor) -> torch.Tensor:
+    K, N = w1q.shape
+    out = torch.empty((haq_packed_bytes(K, 2 * N),), dtype=torch.int8, device=w1q.device)
+    _check(lib().haq_pack_gate_up(_ptr(w1q), _ptr(w3q), K, N, _ptr(out), _stream()))
+    return out
+
+
+def haq_linear_workspace_bytes(T: int, K: int, N: int) -> int:
+    return int(lib().haq_linear_workspace_bytes(T, K, N))
+
+
+def haq_w8a8_linear(x, s, w_packed, w_scale, N: int, act: int = HAQ_ACT_NONE, *, out=None, workspace=None,
+                    debug: bool = False):
+    """x fp16 [T,K] -> y fp16 [T,N]; with debug=True also (acc int32 [T,N], q int8 [T,K], sx [T])."""
+    T, K = x.shape
+    dev = x.device
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=dev)
+    if workspace is None:
+        workspace = _ws(haq_linear_workspace_bytes(T, K, N), dev)
+    acc = q = sx = None
+    if debug:
+        acc = torch.empty((T, N), dtype=torch.int32, device=dev)
+        q = torch.empty((T, K), dtype=torch.int8, device=dev)
+        sx = torch.empty((T,), dtype=torch.float32, device=dev)
+    _check(lib().haq_w8a8_linear(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), _ptr(w_packed), _ptr(w_scale), T, K, N, act,
+                                 _ptr(y), C.c_int64(y.stride(0)), _ptr(acc), _ptr(q), _ptr(sx), _ptr(workspace),
+                                 C.c_size_t(workspace.numel()), _stream()))
+    return (y, acc, q, sx) if debug else y
+
+
+def haq_packed_act_rows(T: int) -> int:
+    return int(lib().haq_packed_act_rows(T))
+
+
+def haq_packed_act_bytes(T: int, K: int) -> int:
+    return int(lib().haq_packed_act_bytes(T, K))
+
+
+def haq_quant_act_packed(x, s, *, q_packed=None, row_scale=None):
+    """x fp16 [T,K] -> (codes in the packed MFMA operand layout (flat int8), row_scale [T])."""
+    T, K = x.shape
+    if q_packed is None:
+        q_packed = torch.empty((haq_packed_act_bytes(T, K),), dtype=torch.int8, device=x.device)
+    if row_scale is None:
+        row_scale = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _check(lib().haq_quant_act_packed(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), T, K, _ptr(q_packed), _ptr(row_scale),
+                                      _stream()))
+    return q_packed, row_scale
+
+
+def haq_gemm_w8a8_packed(q_packed, row_scale, w_packed, w_scale, T: int, K: int, N: int, act: int = HAQ_ACT_NONE, *,
+                         out=None):
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=q_packed.device)
+    _check(lib().haq_gemm_w8a8_packed(_ptr(q_packed), _ptr(row_scale), _ptr(w_packed), _ptr(w_scale), T, K, N, act,
+                                      _ptr(y), C.c_int64(y.stride(0)), None, _stream()))
+    return y
+
+
+@dataclass
+class ExpertWeights:
+    """Device (or pinned host, for w13/w2) tensors of one expert, as haq_expert_desc wants them."""
+    w13: torch.Tensor
+    w2: torch.Tensor
+    sw1: torch.Tensor
+    sw3: torch.Tensor
+    sw2: torch.Tensor
+    s_mid: torch.Tensor
+    location: int = HAQ_LOC_DEVICE
+
+
+@dataclass
+class MoeDebug:
+    topk_idx: torch.Tensor
+    topk_w: torch.Tensor
+    counts: torch.Tensor
+    offsets: torch.Tensor
+    perm: torch.Tensor
+    inv: torch.Tensor
+    q: torch.Tensor
+    sx: torch.Tensor
+    mid_fp16: torch.Tensor
+    hq: torch.Tensor
+    sh: torch.Tensor
+    y_fp16: torch.Tensor
+
+
+def haq_moe_workspace_bytes(T: int, H: int, I: int, E: int) -> int:
+    return int(lib().haq_moe_workspace_bytes(T, H, I, E))
+
+
+def haq_ctx_create(H: int, I: int, n_slots: int):
+    ctx = C.c_void_p()
+    _check(lib().haq_ctx_create(H, I, n_slots, C.byref(ctx)))
+    return ctx
+
+
+def haq_ctx_destroy(ctx) -> None:
+    _check(lib().haq_ctx_destroy(ctx))
+
+
+def haq_moe_w8a8_ffn(x, logits, s_in, experts: list[ExpertWeights], I: int, *, ctx=None, out=None, workspace=None,
+                     debug: bool = False):
+    """x fp16 [T,H], logits fp16 [T,E] -> out fp16 [T,H] (and a MoeDebug when debug=True)."""
+    T, H = x.shape
+    E = len(experts)
+    dev = x.device
+    y = out if out is not None else torch.empty((T, H), dtype=torch.float16, device=dev)
+    if workspace is None:
+        workspace = _ws(haq_moe_workspace_bytes(T, H, I, E), dev)
+    descs = (_ExpertDesc * E)()
+    for i, e in enumerate(experts):
+        descs[i].w13, descs[i].w2 = e.w13.data_ptr(), e.w2.data_ptr()
+        descs[i].sw1, descs[i].sw3, descs[i].sw2 = e.sw1.data_ptr(), e.sw3.data_ptr(), e.sw2.data_ptr()
+        descs[i].s_mid, descs[i].location = e.s_mid.data_ptr(), e.location
+    dbg = None
+    dbg_c = None
+    if debug:
+        P = 2 * T
+        i32, f32, f16, i8 = torch.int32, torch.float32, torch.float16, torch.int8
+        mk = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        dbg = MoeDebug(mk((T, 2), i32), mk((T, 2), f32), mk((E,), i32), mk((E + 1,), i32), mk((P,), i32), mk((P,), i32),
+                       mk((T, H), i8), mk((T,), f32), mk((P, I), f16), mk((P, I), i8), mk((P,), f32), mk((P, H), f16))
+        dbg_c = _MoeDebug(*[getattr(dbg, n).data_ptr() for n in _DBG_FIELDS])
+    _check(lib().haq_moe_w8a8_ffn(ctx, _ptr(x), C.c_int64(x.stride(0)), _ptr(logits), C.c_int64(logits.stride(0)),
+                                  _ptr(s_in), descs, T, H, I, E, 2, _ptr(y), C.c_int64(y.stride(0)),
+                                  C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),
+                                  C.c_size_t(workspace.numel()), _stream()))
+    return (y, dbg) if debug else y

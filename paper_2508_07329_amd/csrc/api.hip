@@ -1,0 +1,343 @@
+// C ABI entry points: argument validation on the host, workspace carving and the
+// launch sequence of the linear layer and of the routed expert FFN.
+#include <cmath>
+#include <cstdarg>
+
+#include "haq_common.h"
+#include "moe.h"
+
+namespace haq {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+// Bump allocator over the caller's workspace (256-byte granules).
+struct Carver {
+    uint8_t* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base((uint8_t*)p) {}
+    template <typename T>
+    T* take(size_t n) {
+        T* r = base ? (T*)(base + off) : nullptr;
+        off += (size_t)round_up((int64_t)(n * sizeof(T)), 256);
+        return r;
+    }
+};
+
+constexpr int TILE_M = 256;  // largest row tile of the GEMM: operands are padded by this many rows
+
+inline int64_t padded_rows(int64_t rows) { return round_up(rows, 16) + TILE_M; }
+
+struct LinearWs {
+    int8_t* q_cm;
+    float* sx;
+    int64_t R;
+    size_t bytes;
+};
+LinearWs carve_linear(void* ws, int T, int K) {
+    Carver c(ws);
+    LinearWs w;
+    w.R = padded_rows(T);
+    w.q_cm = c.take<int8_t>((size_t)K * w.R);
+    w.sx = c.take<float>((size_t)T);
+    w.bytes = c.off;
+    return w;
+}
+
+struct MoeWs {
+    int32_t *idx, *counts, *offsets, *perm, *inv;
+    float *gw, *sx, *sx_sorted, *sh;
+    ExpertTab* tab;
+    int8_t *q_cm, *hq_cm;
+    __half *mid, *y;
+    int64_t R;
+    size_t bytes;
+};
+MoeWs carve_moe(void* ws, int T, int H, int I, int E) {
+    Carver c(ws);
+    MoeWs w;
+    const size_t P = 2 * (size_t)T;
+    w.R = padded_rows((int64_t)P);
+    w.idx = c.take<int32_t>(P);
+    w.gw = c.take<float>(P);
+    w.counts = c.take<int32_t>(E);
+    w.offsets = c.take<int32_t>(E + 1);
+    w.perm = c.take<int32_t>(P);
+    w.inv = c.take<int32_t>(P);
+    w.sx = c.take<float>(T);
+    w.sx_sorted = c.take<float>(P);
+    w.sh = c.take<float>(P);
+    w.tab = c.take<ExpertTab>(E);
+    w.q_cm = c.take<int8_t>((size_t)H * w.R);
+    w.hq_cm = c.take<int8_t>((size_t)I * w.R);
+    w.mid = c.take<__half>(P * (size_t)I);
+    w.y = c.take<__half>(P * (size_t)H);
+    w.bytes = c.off;
+    return w;
+}
+
+int quant_packed(const void* x_fp16, int64_t ldx, const float* s, int T, int K, int8_t* q_cm, float* sx, int8_t* q_rm,
+                 hipStream_t st) {
+    QuantArgs qa{};
+    qa.x = (const __half*)x_fp16;
+    qa.ldx = ldx;
+    qa.s = s;
+    qa.T = T;
+    qa.K = K;
+    qa.q_rm = q_rm;
+    qa.ldq = K;
+    qa.q_cm = q_cm;
+    qa.R = padded_rows(T);
+    qa.scale = sx;
+    return launch_quant(qa, st);
+}
+
+int gemm_packed(const int8_t* q_cm, const float* sx, const int8_t* w_packed, const float* w_scale, int T, int K, int N,
+                int act, void* y_fp16, int64_t ldy, int32_t* acc_dbg, hipStream_t st) {
+    GemmArgs ga{};
+    ga.A = q_cm;
+    ga.R = padded_rows(T);
+    ga.sx = sx;
+    ga.K = K;
+    ga.N = N;
+    ga.Npad = round_up(N, NPAD);
+    ga.M = T;
+    ga.B = w_packed;
+    ga.sw = w_scale;
+    ga.act = act;
+    ga.Y = (__half*)y_fp16;
+    ga.ldy = ldy;
+    ga.acc_dbg = acc_dbg;
+    return launch_gemm(ga, EPI_LINEAR, st);
+}
+
+}  // namespace
+}  // namespace haq
+
+using namespace haq;
+
+extern "C" {
+
+int32_t haq_version(void) { return 1; }
+const char* haq_last_error(void) { return g_err; }
+
+int32_t haq_smoothing_vector(const float* ax, const float* aw, int32_t K, double alpha, float* s) {
+    if (K <= 0 || !ax || !s) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_smoothing_vector: K=%d or null buffer", K);
+    if (!(alpha >= 0.0 && alpha <= 1.0)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_smoothing_vector: alpha=%g outside [0,1]", alpha);
+    for (int k = 0; k < K; ++k) {
+        const double a = ax[k], w = aw ? (double)aw[k] : 1.0;
+        double v = 1.0;
+        if (a != 0.0 && w != 0.0) {
+            v = std::pow(a, alpha) / std::pow(w, 1.0 - alpha);
+            v = v < 1e-5 ? 1e-5 : (v > 1e5 ? 1e5 : v);
+        }
+        s[k] = (float)v;
+    }
+    return HAQ_OK;
+}
+
+size_t haq_linear_workspace_bytes(int32_t T, int32_t K, int32_t N) {
+    (void)N;
+    if (T < 0 || K <= 0) return 0;
+    return carve_linear(nullptr, T, K).bytes;
+}
+
+int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const int8_t* w_packed, const float* w_scale,
+                        int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg,
+                        int8_t* q_dbg, float* sx_dbg, void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: T=%d K=%d N=%d", T, K, N);
+    if (K % 64 != 0 || K > 65536 || N % 16 != 0)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: K=%d must be a multiple of 64 (<= 65536), N=%d of 16", K, N);
+    if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: act=%d", act);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: null buffer");
+    if (ldx < K || ldx % 8 != 0 || ldy < N) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: ldx=%lld ldy=%lld", (long long)ldx, (long long)ldy);
+    if (!aligned16(x_fp16) || !aligned16(w_packed) || (s && !aligned16(s)) || (q_dbg && !aligned16(q_dbg)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: pointers must be 16-byte aligned");
+    const size_t need = carve_linear(nullptr, T, K).bytes;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_w8a8_linear: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const LinearWs w = carve_linear(workspace, T, K);
+    int rc = quant_packed(x_fp16, ldx, s, T, K, w.q_cm, w.sx, q_dbg, st);
+    if (rc != HAQ_OK) return rc;
+    if (sx_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(sx_dbg, w.sx, (size_t)T * sizeof(float), hipMemcpyDeviceToDevice, st));
+    return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, st);
+}
+
+int64_t haq_packed_act_rows(int32_t T) { return T < 0 ? 0 : padded_rows(T); }
+size_t haq_packed_act_bytes(int32_t T, int32_t K) { return (T < 0 || K <= 0) ? 0 : (size_t)K * (size_t)padded_rows(T); }
+
+int32_t haq_quant_act_packed(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K, int8_t* q_packed,
+                             float* row_scale, void* stream) {
+    if (T < 0 || K <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: T=%d K=%d", T, K);
+    if (K % 64 != 0 || K > 65536) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_quant_act_packed: K=%d must be a multiple of 64, <= 65536", K);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !q_packed || !row_scale) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: null buffer");
+    if (ldx < K || ldx % 8 != 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: ldx=%lld", (long long)ldx);
+    if (!aligned16(x_fp16) || !aligned16(q_packed) || (s && !aligned16(s)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: pointers must be 16-byte aligned");
+    return quant_packed(x_fp16, ldx, s, T, K, q_packed, row_scale, nullptr, (hipStream_t)stream);
+}
+
+int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, const int8_t* w_packed, const float* w_scale,
+                             int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg,
+                             void* stream) {
+    if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: T=%d K=%d N=%d", T, K, N);
+    if (K % 64 != 0 || N % 16 != 0) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: K=%d must be a multiple of 64, N=%d of 16", K, N);
+    if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: act=%d", act);
+    if (T == 0) return HAQ_OK;
+    if (!q_packed || !row_scale || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: null buffer");
+    if (ldy < N) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: ldy=%lld", (long long)ldy);
+    if (!aligned16(q_packed) || !aligned16(w_packed)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: pointers must be 16-byte aligned");
+    return gemm_packed(q_packed, row_scale, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, (hipStream_t)stream);
+}
+
+int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out) {
+    (void)H;
+    (void)I;
+    (void)n_slots;
+    if (out) *out = nullptr;
+    HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_ctx_create: host-resident experts are not available yet");
+}
+int32_t haq_ctx_destroy(haq_ctx* ctx) {
+    (void)ctx;
+    return HAQ_OK;
+}
+
+size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E) {
+    if (T < 0 || H <= 0 || I <= 0 || E <= 0) return 0;
+    return carve_moe(nullptr, T, H, I, E).bytes;
+}
+
+int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl,
+                         const float* s_in, const haq_expert_desc* experts, int32_t T, int32_t H, int32_t I, int32_t E,
+                         int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    (void)ctx;
+    if (T < 0 || H <= 0 || I <= 0 || E <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: T=%d H=%d I=%d E=%d", T, H, I, E);
+    if (top_k != 2) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: top_k=%d (only 2)", top_k);
+    if (E < 2 || E > 32) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: E=%d outside [2, 32]", E);
+    if (H % 64 != 0 || I % 64 != 0 || H > 65536 || I > 65536)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: H=%d and I=%d must be multiples of 64 (both <= 65536)", H, I);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !logits_fp16 || !experts || !out_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: null buffer");
+    if (ldx < H || ldx % 8 != 0 || ldl < E || ldo < H || ldo % 8 != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: ldx=%lld ldl=%lld ldo=%lld", (long long)ldx, (long long)ldl, (long long)ldo);
+    if (!aligned16(x_fp16) || !aligned16(out_fp16) || (s_in && !aligned16(s_in)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: pointers must be 16-byte aligned");
+    ExpertTab tab[32];
+    for (int e = 0; e < E; ++e) {
+        const haq_expert_desc& d = experts[e];
+        if (!d.w13 || !d.w2 || !d.sw1 || !d.sw3 || !d.sw2 || !d.s_mid)
+            HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d has a null pointer", e);
+        if (!aligned16(d.w13) || !aligned16(d.w2) || !aligned16(d.s_mid))
+            HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d pointers must be 16-byte aligned", e);
+        if (d.location != HAQ_LOC_DEVICE) {
+            if (d.location != HAQ_LOC_HOST_PINNED) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d location=%d", e, d.location);
+            HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: expert %d is host resident: not available yet", e);
+        }
+        tab[e] = ExpertTab{d.w13, d.w2, d.sw1, d.sw3, d.sw2, d.s_mid};
+    }
+    const size_t need = carve_moe(nullptr, T, H, I, E).bytes;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_moe_w8a8_ffn: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+
+    hipStream_t st = (hipStream_t)stream;
+    MoeWs w = carve_moe(workspace, T, H, I, E);
+    const int P = 2 * T;
+    haq_moe_debug d{};
+    if (dbg) d = *dbg;
+    // debug buffers with the same shape as a workspace buffer simply take its place
+    int32_t* idx = d.topk_idx ? d.topk_idx : w.idx;
+    float* gw = d.topk_w ? d.topk_w : w.gw;
+    int32_t* counts = d.counts ? d.counts : w.counts;
+    int32_t* offsets = d.offsets ? d.offsets : w.offsets;
+    int32_t* perm = d.perm ? d.perm : w.perm;
+    int32_t* inv = d.inv ? d.inv : w.inv;
+    __half* mid = d.mid_fp16 ? (__half*)d.mid_fp16 : w.mid;
+    __half* y = d.y_fp16 ? (__half*)d.y_fp16 : w.y;
+    float* sh = d.sh ? d.sh : w.sh;
+
+    int rc;
+    if ((rc = upload_tab(tab, E, w.tab, st)) != HAQ_OK) return rc;
+    if ((rc = launch_route((const __half*)logits_fp16, ldl, T, E, idx, gw, st)) != HAQ_OK) return rc;
+    if ((rc = launch_permute(idx, P, E, counts, offsets, perm, inv, st)) != HAQ_OK) return rc;
+
+    QuantArgs qa{};
+    qa.x = (const __half*)x_fp16;
+    qa.ldx = ldx;
+    qa.s = s_in;
+    qa.T = T;
+    qa.K = H;
+    qa.q_rm = d.q;
+    qa.ldq = H;
+    qa.q_cm = w.q_cm;
+    qa.R = w.R;
+    qa.dest = inv;
+    qa.scale = d.sx;
+    qa.scale_dest = w.sx_sorted;
+    if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
+
+    GemmArgs g1{};
+    g1.A = w.q_cm;
+    g1.R = w.R;
+    g1.sx = w.sx_sorted;
+    g1.K = H;
+    g1.N = 2 * I;
+    g1.Npad = round_up(2 * (int64_t)I, NPAD);
+    g1.offsets = offsets;
+    g1.tab = w.tab;
+    g1.which = 0;
+    g1.n_sel = E;
+    for (int e = 0; e < E; ++e) g1.sel[e] = e;
+    g1.max_rows = P;
+    g1.Y = mid;
+    g1.ldy = I;
+    if ((rc = launch_gemm(g1, EPI_SWIGLU, st)) != HAQ_OK) return rc;
+
+    QuantArgs qb{};
+    qb.x = mid;
+    qb.ldx = I;
+    qb.tab = w.tab;
+    qb.offsets = offsets;
+    qb.E = E;
+    qb.T = P;
+    qb.K = I;
+    qb.q_rm = d.hq;
+    qb.ldq = I;
+    qb.q_cm = w.hq_cm;
+    qb.R = w.R;
+    qb.scale = sh;
+    if ((rc = launch_quant(qb, st)) != HAQ_OK) return rc;
+
+    GemmArgs g2{};
+    g2.A = w.hq_cm;
+    g2.R = w.R;
+    g2.sx = sh;
+    g2.K = I;
+    g2.N = H;
+    g2.Npad = round_up(H, NPAD);
+    g2.offsets = offsets;
+    g2.tab = w.tab;
+    g2.which = 1;
+    g2.n_sel = E;
+    for (int e = 0; e < E; ++e) g2.sel[e] = e;
+    g2.max_rows = P;
+    g2.act = HAQ_ACT_NONE;
+    g2.Y = y;
+    g2.ldy = H;
+    if ((rc = launch_gemm(g2, EPI_LINEAR, st)) != HAQ_OK) return rc;
+
+    return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Shared host/device helpers of the HAQ W8A8 library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "haq.h"
+
+namespace haq {
+
+// ---- error reporting -------------------------------------------------------
+void set_error(const char* fmt, ...);  // thread-local text behind haq_last_error()
+
+#define HAQ_FAIL(code, ...)        \
+    do {                           \
+        haq::set_error(__VA_ARGS__); \
+        return (code);             \
+    } while (0)
+
+#define HAQ_CHECK_HIP(expr)                                                                 \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) HAQ_FAIL(HAQ_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---- layouts ---------------------------------------------------------------
+// "Chunk-major" int8 operand layout shared by activations and packed weights:
+// [K/16][R][16] - for each group of 16 consecutive k, all R rows side by side.
+// A tile of BM rows x 64 k is then four contiguous segments of BM*16 bytes and
+// lands in LDS in the order the MFMA fragments are read, without bank conflicts.
+constexpr int KCHUNK = 16;
+constexpr int NPAD = 256;  // packed weights pad the output-channel count to this
+
+// ---- device arithmetic (every operation rounds once; no contraction) --------
+#ifdef __HIPCC__
+__device__ __forceinline__ float h2f(__half h) { return __half2float(h); }
+__device__ __forceinline__ __half f2h(float f) { return __float2half_rn(f); }
+
+// e^t as a fixed binary32 sequence: clamp to [-87, 88], n = rne(t*log2 e),
+// r = t - n*ln2 (two-part), degree-7 Taylor/Horner with FMAs, times 2^n.
+__device__ __forceinline__ float exp_spec(float t) {
+    t = fminf(fmaxf(t, -87.0f), 88.0f);
+    const float n = rintf(t * 1.44269502162933349609375f);
+    float r = __builtin_fmaf(n, -0.693145751953125f, t);
+    r = __builtin_fmaf(n, -1.42860682030941723212e-6f, r);
+    float p = 1.0f / 5040.0f;
+    p = __builtin_fmaf(p, r, 1.0f / 720.0f);
+    p = __builtin_fmaf(p, r, 1.0f / 120.0f);
+    p = __builtin_fmaf(p, r, 1.0f / 24.0f);
+    p = __builtin_fmaf(p, r, 1.0f / 6.0f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    const float scale = __int_as_float(((int)n + 127) << 23);
+    return p * scale;
+}
+__device__ __forceinline__ float silu(float g) { return g / (1.0f + exp_spec(-g)); }
+__device__ __forceinline__ float dequant(int acc, float sx, float sw) { return ((float)acc * sx) * sw; }
+__device__ __forceinline__ int code_of(float y, float scale) {
+    float c = rintf(y / scale);
+    c = fminf(fmaxf(c, -127.0f), 127.0f);
+    return (int)c;
+}
+#endif
+
+// ---- internal launchers (host) ----------------------------------------------
+struct ExpertTab {  // device-side table entry
+    const int8_t* w13;
+    const int8_t* w2;
+    const float* sw1;
+    const float* sw3;
+    const float* sw2;
+    const float* s_mid;
+};
+
+struct QuantArgs {
+    const __half* x;   // [T x K], row stride ldx
+    int64_t ldx;
+    const float* s;    // [K] or null (all ones); ignored when tab is set
+    const struct ExpertTab* tab;  // null, or per-expert table: row r uses tab[e(r)].s_mid, e(r) from offsets
+    const int32_t* offsets;       // [E+1] sorted-row offsets (with tab)
+    int E;
+    int T, K;
+    int8_t* q_rm;      // optional row-major output, row stride ldq
+    int64_t ldq;
+    int8_t* q_cm;      // optional chunk-major output [K/16][R][16]
+    int64_t R;
+    const int32_t* dest;  // null: row t goes to chunk-major row t; else rows dest[2t], dest[2t+1]
+    float* scale;      // optional [T]
+    float* scale_dest; // optional: scale scattered to dest rows (used with dest)
+};
+int launch_quant(const QuantArgs& a, hipStream_t st);
+
+enum { EPI_LINEAR = 0, EPI_SWIGLU = 1 };
+
+struct GemmArgs {
+    const int8_t* A;   // chunk-major [K/16][R][16]
+    int64_t R;
+    const float* sx;   // [rows] per A row
+    int K;
+    int N;             // packed output channels (before SwiGLU halving)
+    int64_t Npad;
+    // single group (offsets == null): rows [0, M), weights B, scales sw
+    int M;
+    const int8_t* B;
+    const float* sw;
+    // grouped: offsets [E+1] on device, experts tab on device, selected experts
+    const int32_t* offsets;
+    const ExpertTab* tab;
+    int which;         // 0: gate/up (w13, sw1/sw3), 1: down (w2, sw2)
+    int n_sel;
+    int sel[64];
+    int max_rows;      // upper bound of rows over the selected groups (grid sizing)
+    int act;
+    __half* Y;
+    int64_t ldy;
+    int32_t* acc_dbg;  // optional dense [rows x N]
+};
+int launch_gemm(const GemmArgs& a, int epi, hipStream_t st);
+
+}  // namespace haq

@@ -1,0 +1,82 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/haq.h
+declares, and rejects bad arguments on the host before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+
+import oracle
+import paper_2508_07329_amd as haq
+from paper_2508_07329_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "haq.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(haq_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = haq.lib()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert haq.haq_version() == 1
+
+
+def test_sizes_and_layout_queries():
+    assert haq.haq_packed_bytes(768, 3072) == 768 * 3072
+    assert haq.haq_packed_bytes(64, 48) == 64 * 256          # output channels padded to 256
+    assert haq.haq_packed_bytes(0, 5) == 0
+    assert haq.haq_linear_workspace_bytes(2048, 4096, 16384) >= 2048 * 4096
+    assert haq.haq_moe_workspace_bytes(64, 4096, 14336, 8) >= 128 * 14336 * 3
+
+
+def test_argument_errors_are_reported_on_the_host():
+    L = haq.lib()
+    err = lambda: L.haq_last_error().decode()
+    one = C.c_void_p(16)  # never dereferenced: validation fails first
+    assert L.haq_smooth_quant_act(one, C.c_int64(64), None, -1, 64, one, C.c_int64(64), one, None) == -1
+    assert "T=-1" in err()
+    assert L.haq_smooth_quant_act(one, C.c_int64(100), None, 4, 100, one, C.c_int64(100), one, None) == -2
+    assert L.haq_smooth_quant_act(None, C.c_int64(64), None, 4, 64, one, C.c_int64(64), one, None) == -1
+    assert L.haq_smooth_quant_act(C.c_void_p(8), C.c_int64(64), None, 4, 64, one, C.c_int64(64), one, None) == -1
+    assert "aligned" in err()
+    assert L.haq_smooth_quant_act(one, C.c_int64(32), None, 4, 64, one, C.c_int64(64), one, None) == -1
+    # T == 0 is a no-op that needs no buffers
+    assert L.haq_smooth_quant_act(None, C.c_int64(64), None, 0, 64, None, C.c_int64(64), None, None) == 0
+    z = C.c_size_t(0)
+    assert L.haq_w8a8_linear(one, C.c_int64(64), None, one, one, 4, 64, 16, 7, one, C.c_int64(16), None, None, None,
+                             None, z, None) == -2
+    assert L.haq_w8a8_linear(one, C.c_int64(64), None, one, one, 4, 64, 16, 0, one, C.c_int64(16), None, None, None,
+                             None, z, None) == -3
+    assert "workspace" in err()
+    assert L.haq_w8a8_linear(one, C.c_int64(64), None, one, one, 4, 64, 24, 0, one, C.c_int64(24), None, None, None,
+                             None, z, None) == -2
+    assert L.haq_moe_w8a8_ffn(None, one, C.c_int64(64), one, C.c_int64(8), None, one, 4, 64, 64, 8, 3, one,
+                              C.c_int64(64), None, None, z, None) == -2
+    assert "top_k" in err()
+    assert L.haq_moe_w8a8_ffn(None, one, C.c_int64(64), one, C.c_int64(8), None, one, 4, 64, 64, 1, 2, one,
+                              C.c_int64(64), None, None, z, None) == -2
+    assert L.haq_pack_weight(one, 100, 16, one, None) == -2
+    assert L.haq_quant_weight(None, None, 4, 4, one, one, None) == -1
+
+
+def test_smoothing_vector_host_function_matches_oracle():
+    rng = np.random.default_rng(0)
+    ax = rng.uniform(0, 300, 257).astype(np.float32)
+    aw = rng.uniform(0, 1, 257).astype(np.float32)
+    ax[3] = 0
+    aw[9] = 0
+    L = haq.lib()
+    for alpha, use_w in [(0.5, True), (0.3, True), (1.0, True), (0.0, True), (0.5, False)]:
+        s = np.empty(257, np.float32)
+        rc = L.haq_smoothing_vector(ax.ctypes.data_as(C.c_void_p), aw.ctypes.data_as(C.c_void_p) if use_w else None,
+                                    257, C.c_double(alpha), s.ctypes.data_as(C.c_void_p))
+        assert rc == 0
+        assert np.array_equal(s, oracle.smoothing_vector(ax, aw if use_w else None, alpha))
+    assert L.haq_smoothing_vector(ax.ctypes.data_as(C.c_void_p), None, 257, C.c_double(1.5), s.ctypes.data_as(C.c_void_p)) == -1

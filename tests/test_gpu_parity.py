@@ -1,0 +1,225 @@
+"""GPU-vs-oracle parity through the C ABI (ctypes binding), element by element.
+
+Bars: bit-exact for int8 codes, scales derived by IEEE operations, int32
+accumulators, routing indices and permutations; fp16 outputs within
+|gpu - cpu| <= 1e-3 |cpu| + 1e-3 rms(cpu row) (they are in fact expected to be
+bit-identical, because both sides round every binary32 operation once and use the
+same defined e^t sequence; the tests report that too).
+"""
+import numpy as np
+import pytest
+import torch
+
+import haq_inputs as hi
+import oracle
+import paper_2508_07329_amd as haq
+from tests import offline
+from tests.gpu_util import bits_equal, dev, fp16_close, host, mixtral_layer, upload_experts
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    haq.lib()
+
+
+# ------------------------------------------------------------------ A1
+@pytest.mark.parametrize("T,K,with_s", [(16, 768, True), (2048, 4096, True), (37, 14336, True), (1, 64, False),
+                                         (9, 16384, True), (300, 832, False)])
+def test_smooth_quant_act_bit_exact(T, K, with_s):
+    X, _, _ = hi.hidden_states(100 + T, T, K, n_outlier=max(1, K // 200))
+    if T > 4:
+        X[3] = 0  # a zero row
+    s = np.exp(np.random.default_rng(T).normal(0, 1, K)).astype(F32) if with_s else None
+    q_ref, sx_ref = oracle.smooth_quant_act(X, s)
+    q, sx = haq.haq_smooth_quant_act(dev(X), None if s is None else dev(s))
+    assert bits_equal(host(sx), sx_ref)
+    assert bits_equal(host(q), q_ref)
+
+
+def test_smooth_quant_act_strided_input_and_empty():
+    X, _, _ = hi.hidden_states(5, 20, 256)
+    big = torch.zeros((20, 512), dtype=torch.float16, device="cuda:0")
+    big[:, :256] = dev(X)
+    q, sx = haq.haq_smooth_quant_act(big[:, :256], None)
+    q_ref, sx_ref = oracle.smooth_quant_act(X, None)
+    assert bits_equal(host(q), q_ref) and bits_equal(host(sx), sx_ref)
+    q0, sx0 = haq.haq_smooth_quant_act(torch.empty((0, 256), dtype=torch.float16, device="cuda:0"), None)
+    assert q0.shape == (0, 256) and sx0.shape == (0,)
+
+
+# ------------------------------------------------------------------ offline side
+def test_offline_quantiser_bit_exact():
+    X, _, _ = hi.hidden_states(6, 70, 320, 4, 50.0)
+    W = hi.gaussian_weight(6, 0, 320, 200)
+    W[:, 7] = 0  # a zero output channel
+    ax = host(haq.haq_channel_absmax_f16(dev(X)))
+    aw = host(haq.haq_weight_row_absmax(dev(W)))
+    assert bits_equal(ax, oracle.col_absmax_f16(X)) and bits_equal(aw, oracle.row_absmax_f32(W))
+    s = haq.haq_smoothing_vector(dev(ax), dev(aw), 0.5)
+    s_ref = oracle.smoothing_vector(ax, aw, 0.5)
+    assert bits_equal(host(s), s_ref)
+    wq, sw = haq.haq_quant_weight(dev(W), s)
+    wq_ref, sw_ref = oracle.quant_weight(W, s_ref)
+    assert bits_equal(host(sw), sw_ref) and bits_equal(host(wq), wq_ref)
+    wq1, sw1 = haq.haq_quant_weight(dev(W), None)
+    wq1_ref, sw1_ref = oracle.quant_weight(W, None)
+    assert bits_equal(host(sw1), sw1_ref) and bits_equal(host(wq1), wq1_ref)
+
+
+def test_pack_layouts():
+    rng = np.random.default_rng(7)
+    K, N = 128, 96
+    w1 = rng.integers(-127, 128, (K, N)).astype(np.int8)
+    w3 = rng.integers(-127, 128, (K, N)).astype(np.int8)
+    p = host(haq.haq_pack_weight(dev(w1))).reshape(K // 16, 256, 16)
+    ref = np.zeros((K // 16, 256, 16), np.int8)
+    ref[:, :N, :] = w1.reshape(K // 16, 16, N).transpose(0, 2, 1)
+    assert np.array_equal(p, ref)
+    g = host(haq.haq_pack_gate_up(dev(w1), dev(w3))).reshape(K // 16, 256, 16)
+    inter = np.zeros((K, 2 * N), np.int8)
+    for b in range(N // 32):
+        inter[:, 64 * b:64 * b + 32] = w1[:, 32 * b:32 * b + 32]
+        inter[:, 64 * b + 32:64 * b + 64] = w3[:, 32 * b:32 * b + 32]
+    ref = np.zeros((K // 16, 256, 16), np.int8)
+    ref[:, :2 * N, :] = inter.reshape(K // 16, 16, 2 * N).transpose(0, 2, 1)
+    assert np.array_equal(g, ref)
+
+
+# ------------------------------------------------------------------ A1+A2+A3 linear
+def _linear_case(X, W, act):
+    s, Wq, sw = offline.quantize_linear(X, W)
+    Y_ref, acc_ref, q_ref, sx_ref = oracle.w8a8_linear(X, s, Wq, sw, act, full=True)
+    wp = haq.haq_pack_weight(dev(Wq))
+    y, acc, q, sx = haq.haq_w8a8_linear(dev(X), dev(s), wp, dev(sw), W.shape[1], oracle.ACT[act], debug=True)
+    assert bits_equal(host(q), q_ref) and bits_equal(host(sx), sx_ref)
+    assert bits_equal(host(acc), acc_ref)
+    assert fp16_close(host(y), Y_ref)
+    assert bits_equal(host(y), Y_ref)
+    y2 = haq.haq_w8a8_linear(dev(X), dev(s), wp, dev(sw), W.shape[1], oracle.ACT[act])
+    assert bits_equal(host(y2), Y_ref)
+
+
+def test_linear_opt125m_config():
+    wl = hi.OPT125M_LINEAR
+    X, _, _ = hi.hidden_states(wl.seed, wl.T, wl.K, wl.n_outlier, wl.mult)
+    _linear_case(X, hi.gaussian_weight(wl.seed, 0, wl.K, wl.N), wl.act)
+
+
+@pytest.mark.parametrize("T,K,N,act", [(300, 832, 1040, "relu"), (1, 64, 16, "none"), (257, 1024, 272, "none"),
+                                        (513, 2048, 768, "relu")])
+def test_linear_ragged_shapes(T, K, N, act):
+    X, _, _ = hi.hidden_states(T + K, T, K, n_outlier=3)
+    _linear_case(X, hi.gaussian_weight(T + K, 0, K, N), act)
+
+
+def test_linear_extreme_accumulators():
+    K = 16384
+    X = np.full((3, K), 127, np.float16)
+    X[1] = -127
+    X[2, ::2] = -127
+    Wq = np.full((K, 16), 127, np.int8)
+    Wq[:, 1] = -127
+    sw = np.full(16, 1e-6, F32)
+    y, acc, q, sx = haq.haq_w8a8_linear(dev(X), None, haq.haq_pack_weight(dev(Wq)), dev(sw), 16, debug=True)
+    Y_ref, acc_ref, _, _ = oracle.w8a8_linear(X, None, Wq, sw, "none", full=True)
+    assert acc_ref[0, 0] == 127 * 127 * K
+    assert bits_equal(host(acc), acc_ref) and bits_equal(host(y), Y_ref)
+
+
+def test_ffn_opt67b_full_size_sampled_rows():
+    """OPT-6.7B FFN block at full size; the oracle checks 40 sampled token rows end to end."""
+    wl = hi.OPT67B_FFN
+    X, _, _ = hi.hidden_states(wl.seed, wl.T, wl.H, wl.n_outlier, wl.mult)
+    W1 = hi.gaussian_weight(wl.seed, 0, wl.H, wl.F)
+    W2 = hi.gaussian_weight(wl.seed, 1, wl.F, wl.H)
+    rows = np.sort(np.random.default_rng(1).permutation(wl.T)[:40])
+    rows[0], rows[-1] = 0, wl.T - 1
+    # offline quantisation calibrated on the sampled rows only (keeps the oracle's share small)
+    (s1, W1q, sw1), (s2, W2q, sw2) = offline.quantize_ffn(X[rows], W1, W2)
+    del W1, W2
+    w1p, w2p = haq.haq_pack_weight(dev(W1q)), haq.haq_pack_weight(dev(W2q))
+    h = haq.haq_w8a8_linear(dev(X), dev(s1), w1p, dev(sw1), wl.F, haq.HAQ_ACT_RELU)
+    y = haq.haq_w8a8_linear(h, dev(s2), w2p, dev(sw2), wl.H, haq.HAQ_ACT_NONE)
+    h_ref = oracle.w8a8_linear(X[rows], s1, W1q, sw1, "relu")
+    y_ref = oracle.w8a8_linear(h_ref, s2, W2q, sw2, "none")
+    assert bits_equal(host(h)[rows], h_ref)
+    assert fp16_close(host(y)[rows], y_ref)
+    assert bits_equal(host(y)[rows], y_ref)
+
+
+# ------------------------------------------------------------------ MoE, small shapes, everything compared
+def _check_moe(m, dev_experts=None, tokens=None, ctx=None):
+    X, logits, s_in, experts = m["X"], m["logits"], m["s_in"], m["experts"]
+    T, H = X.shape
+    I = experts[0].w1.shape[1]
+    E = len(experts)
+    if dev_experts is None:
+        dev_experts = upload_experts(experts)
+    out, d = haq.haq_moe_w8a8_ffn(dev(X), dev(logits), dev(s_in), dev_experts, I, ctx=ctx, debug=True)
+    torch.cuda.synchronize()
+    idx_ref, gw_ref = oracle.route_top2(logits)
+    counts, offsets, perm, inv = oracle.permute(idx_ref, E)
+    assert bits_equal(host(d.topk_idx), idx_ref)
+    assert bits_equal(host(d.topk_w), gw_ref)
+    assert bits_equal(host(d.counts), counts) and bits_equal(host(d.offsets), offsets)
+    assert bits_equal(host(d.perm), perm) and bits_equal(host(d.inv), inv)
+    q_ref, sx_ref = oracle.smooth_quant_act(X, s_in)
+    assert bits_equal(host(d.q), q_ref) and bits_equal(host(d.sx), sx_ref)
+    tok = np.arange(T, dtype=np.int32) if tokens is None else np.asarray(tokens, np.int32)
+    out_ref, mid_ref, hq_ref, sh_ref, y_ref = oracle.moe_ffn(X, idx_ref, gw_ref, s_in, experts, tokens=tok, dumps=True)
+    pos = inv[(2 * tok[:, None] + np.arange(2)[None, :]).ravel()]  # sorted positions of the sampled pairs
+    assert fp16_close(host(d.mid_fp16)[pos], mid_ref)
+    assert fp16_close(host(d.y_fp16)[pos], y_ref)
+    assert fp16_close(host(out)[tok], out_ref)
+    exact = dict(mid=bits_equal(host(d.mid_fp16)[pos], mid_ref), hq=bits_equal(host(d.hq)[pos], hq_ref),
+                 sh=bits_equal(host(d.sh)[pos], sh_ref), y=bits_equal(host(d.y_fp16)[pos], y_ref),
+                 out=bits_equal(host(out)[tok], out_ref))
+    assert all(exact.values()), exact
+    out2 = haq.haq_moe_w8a8_ffn(dev(X), dev(logits), dev(s_in), dev_experts, I, ctx=ctx)
+    assert bits_equal(host(out2), host(out))
+    return counts
+
+
+@pytest.mark.parametrize("T,H,I,E", [(37, 128, 320, 8), (1, 128, 192, 8), (300, 256, 576, 8), (9, 128, 192, 2),
+                                      (530, 192, 448, 4)])
+def test_moe_small_everything_bit_exact(T, H, I, E):
+    _check_moe(offline.small_moe(seed=20 + T, T=T, H=H, I=I, E=E))
+
+
+def test_moe_small_skewed_routing_and_empty_expert():
+    m = offline.small_moe(seed=31, T=64, H=128, I=192, E=8, routing="popularity")
+    m["logits"][:, 5] = -100  # nobody picks expert 5
+    counts = _check_moe(m)
+    assert counts[5] == 0 and counts.max() > 2 * np.median(counts)
+
+
+# ------------------------------------------------------------------ MoE at the Mixtral shape (sampled tokens)
+@pytest.fixture(scope="module")
+def layer():
+    return mixtral_layer()
+
+
+def _mixtral_case(wl, layer):
+    X = hi.moe_hidden_states(wl)
+    logits = hi.moe_logits(wl, X)
+    return dict(X=X, logits=logits, s_in=layer["s_in"], experts=layer["experts"])
+
+
+@pytest.mark.parametrize("b", [1, 8, 64])
+def test_moe_mixtral_decode(layer, b):
+    wl = {w.T: w for w in hi.MIXTRAL_DECODE}[b]
+    tokens = np.arange(b) if b <= 8 else np.sort(np.random.default_rng(b).permutation(b)[:12])
+    _check_moe(_mixtral_case(wl, layer), layer["dev_experts"], tokens)
+
+
+def test_moe_mixtral_prefill_zipf(layer):
+    wl = hi.MIXTRAL_PREFILL
+    tokens = np.sort(np.random.default_rng(3).permutation(wl.T)[:20])
+    tokens[0], tokens[-1] = 0, wl.T - 1
+    counts = _check_moe(_mixtral_case(wl, layer), layer["dev_experts"], tokens)
+    share = counts / counts.sum()
+    assert np.max(np.abs(share - hi.zipf_shares(8))) < 0.02
