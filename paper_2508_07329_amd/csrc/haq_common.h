@@ -40,7 +40,14 @@ constexpr int NPAD = 256;  // packed weights pad the output-channel count to thi
 // ---- device arithmetic (every operation rounds once; no contraction) --------
 #ifdef __HIPCC__
 __device__ __forceinline__ float h2f(__half h) { return __half2float(h); }
-__device__ __forceinline__ __half f2h(float f) { return __float2half_rn(f); }
+// binary32 -> binary16, round to nearest even.  The empty asm keeps the compiler
+// from folding the producing multiply/add into a mixed-precision instruction that
+// rounds only once (v_fma_mixlo_f16): every binary32 result is rounded to binary32
+// first, then to binary16.
+__device__ __forceinline__ __half f2h(float f) {
+    asm("" : "+v"(f));
+    return __float2half_rn(f);
+}
 
 // e^t as a fixed binary32 sequence: clamp to [-87, 88], n = rne(t*log2 e),
 // r = t - n*ln2 (two-part), degree-7 Taylor/Horner with FMAs, times 2^n.

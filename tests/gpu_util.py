@@ -28,6 +28,20 @@ def bits_equal(a: np.ndarray, b: np.ndarray) -> bool:
     return np.array_equal(a.view(np.uint8), b.view(np.uint8))
 
 
+def diff_report(gpu: np.ndarray, cpu: np.ndarray, n: int = 6) -> str:
+    """Where and how two arrays differ bitwise (for assertion messages)."""
+    g, c = np.ascontiguousarray(gpu), np.ascontiguousarray(cpu)
+    if g.shape != c.shape or g.dtype != c.dtype:
+        return f"shape/dtype {g.shape}{g.dtype} vs {c.shape}{c.dtype}"
+    w = {1: np.uint8, 2: np.uint16, 4: np.uint32}[g.dtype.itemsize]
+    bad = np.argwhere(g.view(w) != c.view(w))
+    lines = [f"{len(bad)} of {g.size} differ"]
+    for ix in bad[:n]:
+        ix = tuple(int(i) for i in ix)
+        lines.append(f"  {ix}: gpu {g[ix]!r} ({int(g.view(w)[ix]):#x}) cpu {c[ix]!r} ({int(c.view(w)[ix]):#x})")
+    return "\n".join(lines)
+
+
 def fp16_close(gpu: np.ndarray, cpu: np.ndarray) -> bool:
     """The stated floating-point bar: |gpu - cpu| <= 1e-3 |cpu| + 1e-3 rms(cpu row)."""
     g, c = gpu.astype(np.float64), cpu.astype(np.float64)

@@ -14,7 +14,7 @@ import haq_inputs as hi
 import oracle
 import paper_2508_07329_amd as haq
 from tests import offline
-from tests.gpu_util import bits_equal, dev, fp16_close, host, mixtral_layer, upload_experts
+from tests.gpu_util import bits_equal, dev, diff_report, fp16_close, host, mixtral_layer, upload_experts
 
 pytestmark = pytest.mark.gpu
 F32 = np.float32
@@ -175,10 +175,9 @@ def _check_moe(m, dev_experts=None, tokens=None, ctx=None):
     assert fp16_close(host(d.mid_fp16)[pos], mid_ref)
     assert fp16_close(host(d.y_fp16)[pos], y_ref)
     assert fp16_close(host(out)[tok], out_ref)
-    exact = dict(mid=bits_equal(host(d.mid_fp16)[pos], mid_ref), hq=bits_equal(host(d.hq)[pos], hq_ref),
-                 sh=bits_equal(host(d.sh)[pos], sh_ref), y=bits_equal(host(d.y_fp16)[pos], y_ref),
-                 out=bits_equal(host(out)[tok], out_ref))
-    assert all(exact.values()), exact
+    for name, g, c in (("mid", host(d.mid_fp16)[pos], mid_ref), ("hq", host(d.hq)[pos], hq_ref),
+                       ("sh", host(d.sh)[pos], sh_ref), ("y", host(d.y_fp16)[pos], y_ref), ("out", host(out)[tok], out_ref)):
+        assert bits_equal(g, c), f"{name}: {diff_report(g, c)}"
     out2 = haq.haq_moe_w8a8_ffn(dev(X), dev(logits), dev(s_in), dev_experts, I, ctx=ctx)
     assert bits_equal(host(out2), host(out))
     return counts
