@@ -159,8 +159,9 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: null buffer");
-    if (ldx < K || ldx % 8 != 0 || ldy < N) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: ldx=%lld ldy=%lld", (long long)ldx, (long long)ldy);
-    if (!aligned16(x_fp16) || !aligned16(w_packed) || (s && !aligned16(s)) || (q_dbg && !aligned16(q_dbg)))
+    if (ldx < K || ldx % 8 != 0 || ldy < N || ldy % 8 != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: ldx=%lld ldy=%lld (multiples of 8)", (long long)ldx, (long long)ldy);
+    if (!aligned16(x_fp16) || !aligned16(w_packed) || !aligned16(y_fp16) || (s && !aligned16(s)) || (q_dbg && !aligned16(q_dbg)))
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: pointers must be 16-byte aligned");
     const size_t need = carve_linear(nullptr, T, K).bytes;
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
@@ -196,8 +197,8 @@ int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, con
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!q_packed || !row_scale || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: null buffer");
-    if (ldy < N) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: ldy=%lld", (long long)ldy);
-    if (!aligned16(q_packed) || !aligned16(w_packed)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: pointers must be 16-byte aligned");
+    if (ldy < N || ldy % 8 != 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: ldy=%lld (multiple of 8)", (long long)ldy);
+    if (!aligned16(q_packed) || !aligned16(w_packed) || !aligned16(y_fp16)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: pointers must be 16-byte aligned");
     return gemm_packed(q_packed, row_scale, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, (hipStream_t)stream);
 }
 

@@ -122,7 +122,7 @@ struct GemmArgs {
     const ExpertTab* tab;
     int which;         // 0: gate/up (w13, sw1/sw3), 1: down (w2, sw2)
     int n_sel;
-    int sel[64];
+    int sel[32];
     int max_rows;      // upper bound of rows over the selected groups (grid sizing)
     int act;
     __half* Y;
