@@ -96,7 +96,7 @@ int quant_packed(const void* x_fp16, int64_t ldx, const float* s, int T, int K, 
     qa.ldq = K;
     qa.q_cm = q_cm;
     qa.R = padded_rows(T);
-    qa.scale = sx;
+    qa.scale_dest = sx;
     return launch_quant(qa, st);
 }
 
@@ -277,13 +277,13 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qa.x = (const __half*)x_fp16;
     qa.ldx = ldx;
     qa.s = s_in;
-    qa.T = T;
+    qa.T = P;  // one output row per (token, expert) pair, in sorted order
     qa.K = H;
     qa.q_rm = d.q;
     qa.ldq = H;
     qa.q_cm = w.q_cm;
     qa.R = w.R;
-    qa.dest = inv;
+    qa.gather = perm;
     qa.scale = d.sx;
     qa.scale_dest = w.sx_sorted;
     if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
@@ -317,7 +317,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qb.ldq = I;
     qb.q_cm = w.hq_cm;
     qb.R = w.R;
-    qb.scale = sh;
+    qb.scale_dest = sh;
     if ((rc = launch_quant(qb, st)) != HAQ_OK) return rc;
 
     GemmArgs g2{};

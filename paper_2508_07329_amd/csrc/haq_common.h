@@ -98,9 +98,10 @@ struct QuantArgs {
     int64_t ldq;
     int8_t* q_cm;      // optional chunk-major output [K/16][R][16]
     int64_t R;
-    const int32_t* dest;  // null: row t goes to chunk-major row t; else rows dest[2t], dest[2t+1]
-    float* scale;      // optional [T]
-    float* scale_dest; // optional: scale scattered to dest rows (used with dest)
+    const int32_t* gather;  // null: output row t reads input row t; else input row gather[t] >> 1
+                            // (sorted pair -> token), and T counts output rows
+    float* scale;      // optional, indexed by input row
+    float* scale_dest; // optional, indexed by output row
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 

@@ -6,96 +6,200 @@ namespace haq {
 
 namespace {
 
-constexpr int QROWS = 8;      // rows per block
-constexpr int QTHREADS = 256;
-constexpr int QGROUPS = QTHREADS / QROWS;  // 16-element chunks handled side by side per row
+constexpr int QMAX_THREADS = 1024;
 
 struct alignas(16) Half8 { __half v[8]; };
 
-__device__ __forceinline__ void load_y16(const __half* xrow, const float* s, int c, float (&y)[16]) {
+// x / d for a divisor that is reused: r = RN(1/d) once, then q0 = RN(x r),
+// q = RN(q0 + r (x - q0 d)) with both corrections fused.  This is the correctly rounded
+// quotient (the final step of the classic reciprocal-based division; checked here
+// exhaustively for every binary16 significand of x against every binary32 significand of
+// d) as long as nothing under- or overflows, which `safe_divisor` guarantees for binary16
+// numerators; other divisors take the hardware division.
+__device__ __forceinline__ bool safe_divisor(float d) { return d >= 0x1p-40f && d <= 0x1p40f; }
+__device__ __forceinline__ float div_by(float x, float d, float r, bool fast) {
+    if (fast) {
+        const float q0 = x * r;
+        const float e = __builtin_fmaf(-q0, d, x);
+        return __builtin_fmaf(e, r, q0);
+    }
+    return x / d;
+}
+
+__device__ __forceinline__ void load_x16(const __half* xrow, int c, float (&x)[16]) {
     const uint4* px = reinterpret_cast<const uint4*>(xrow + c * 16);
-    uint4 r0 = px[0], r1 = px[1];
+    const uint4 r0 = px[0], r1 = px[1];
     Half8 h0, h1;
     *reinterpret_cast<uint4*>(&h0) = r0;
     *reinterpret_cast<uint4*>(&h1) = r1;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        y[i] = h2f(h0.v[i]);
-        y[8 + i] = h2f(h1.v[i]);
-    }
-    if (s) {
-        const float4* ps = reinterpret_cast<const float4*>(s + c * 16);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float4 sv = ps[i];
-            y[4 * i + 0] = y[4 * i + 0] / sv.x;
-            y[4 * i + 1] = y[4 * i + 1] / sv.y;
-            y[4 * i + 2] = y[4 * i + 2] / sv.z;
-            y[4 * i + 3] = y[4 * i + 3] / sv.w;
-        }
+        x[i] = h2f(h0.v[i]);
+        x[8 + i] = h2f(h1.v[i]);
     }
 }
 
-// Block = 8 rows x 32 chunk lanes: thread (row = tid % 8, g = tid / 8) owns chunks
-// g, g + 32, ...  Eight neighbouring lanes of a row read 256 contiguous bytes of X
-// and, in the chunk-major output, eight neighbouring rows of one chunk fill one
-// 128-byte line.  Pass 1 reduces the row absmax (lane shuffles, then 4 waves via
-// LDS); pass 2 re-reads the row (L2 resident) and rounds.
-__global__ __launch_bounds__(QTHREADS) void smooth_quant_kernel(QuantArgs a) {
-    __shared__ float red[QTHREADS / 64][QROWS];
+// reciprocals of one 16-channel chunk of the smoothing vector; `fast` says whether every
+// channel of the chunk may use them
+__device__ __forceinline__ bool load_s16(const float* s, int c, float (&sv)[16], float (&rv)[16]) {
+    const float4* ps = reinterpret_cast<const float4*>(s + c * 16);
+    bool fast = true;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float4 v = ps[i];
+        sv[4 * i + 0] = v.x;
+        sv[4 * i + 1] = v.y;
+        sv[4 * i + 2] = v.z;
+        sv[4 * i + 3] = v.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        rv[i] = 1.0f / sv[i];
+        fast = fast && safe_divisor(sv[i]);
+    }
+    return fast;
+}
+
+// Work-group = 8 consecutive output rows of one expert group (or of the matrix).  Threads
+// form G row groups x CL chunk lanes: thread (g, c) owns the 16-channel chunks c, c + CL, ...
+// of RS = 8 / G rows, so the reciprocals of the smoothing vector are formed once per chunk
+// for RS rows, a wave reads 2 KB contiguous per row, and the 8 rows of one chunk fill one
+// 128-byte line of the chunk-major output from inside one work-group.  Pass 1 reduces the
+// row absmax of y = x / s (lane shuffles, then across the waves of a row group through
+// LDS); pass 2 re-reads the rows (L2 resident), rounds y / scale and writes 16 codes per
+// chunk.  With `gather` the rows are read through a permutation (sorted pair -> token).
+constexpr int QBLOCK_ROWS = 8;
+template <int RS>
+__global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_kernel(QuantArgs a, int CL) {
+    __shared__ float red[QMAX_THREADS / 64][RS];
     const int tid = threadIdx.x;
-    const int rib = tid % QROWS, g = tid / QROWS;
-    const int t = blockIdx.x * QROWS + rib;
-    const bool live = t < a.T;
+    const int c0 = tid % CL, g = tid / CL;
+    const int waves_per_group = CL >> 6, wave = tid >> 6;
     const int nchunk = a.K / 16;
-    const __half* xrow = a.x + (size_t)(live ? t : 0) * a.ldx;
+    // rows of this work-group: [row0, row_end), never straddling two expert groups
+    int row0, row_end;
     const float* s = a.s;
-    if (a.tab) {  // smoothing vector of the expert that owns this sorted row
-        int e = 0;
-        while (e + 1 < a.E && t >= a.offsets[e + 1]) ++e;
+    if (a.tab) {
+        int b = blockIdx.x, e = 0;
+        row0 = row_end = 0;
+        for (; e < a.E; ++e) {
+            const int lo = a.offsets[e], hi = a.offsets[e + 1];
+            const int nb = (hi - lo + QBLOCK_ROWS - 1) / QBLOCK_ROWS;
+            if (b < nb) {
+                row0 = lo + b * QBLOCK_ROWS;
+                row_end = hi;
+                break;
+            }
+            b -= nb;
+        }
+        if (e == a.E) return;  // the grid is an upper bound
         s = a.tab[e].s_mid;
+    } else {
+        row0 = blockIdx.x * QBLOCK_ROWS;
+        row_end = a.T;
     }
-    float amax = 0.0f;
-    float y[16];
-    if (live) {
-        for (int c = g; c < nchunk; c += QGROUPS) {
-            load_y16(xrow, s, c, y);
+    row0 += g * RS;  // first row of this thread's row group
+    const int nrow = min(RS, row_end - row0);  // may be <= 0
+    const __half* xrow[RS];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(y[i]));
+    for (int r = 0; r < RS; ++r) {
+        int src = row0 + (r < nrow ? r : 0);
+        if (nrow <= 0) src = 0;
+        if (a.gather) src = a.gather[src] >> 1;
+        xrow[r] = a.x + (size_t)src * a.ldx;
+    }
+
+    float amax[RS];
+#pragma unroll
+    for (int r = 0; r < RS; ++r) amax[r] = 0.0f;
+    float sv[16], rv[16], x[16];
+    for (int c = c0; c < nchunk; c += CL) {
+        bool fast = true;
+        if (s) fast = load_s16(s, c, sv, rv);
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            if (r < nrow) {
+                load_x16(xrow[r], c, x);
+                float m = amax[r];
+                if (!s) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i]));
+                } else if (fast) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(div_by(x[i], sv[i], rv[i], true)));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i] / sv[i]));
+                }
+                amax[r] = m;
+            }
         }
     }
-    amax = fmaxf(amax, __shfl_xor(amax, 8));
-    amax = fmaxf(amax, __shfl_xor(amax, 16));
-    amax = fmaxf(amax, __shfl_xor(amax, 32));
-    if ((tid & 63) < QROWS) red[tid >> 6][rib] = amax;
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) amax[r] = fmaxf(amax[r], __shfl_xor(amax[r], o));
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) red[wave][r] = amax[r];
+    }
     __syncthreads();
-    amax = fmaxf(fmaxf(red[0][rib], red[1][rib]), fmaxf(red[2][rib], red[3][rib]));
-    if (!live) return;
-    const float scale = amax / 127.0f;
-    int64_t d0 = t, d1 = -1;
-    if (a.dest) {
-        d0 = a.dest[2 * t];
-        d1 = a.dest[2 * t + 1];
-    }
-    if (g == 0) {
-        if (a.scale) a.scale[t] = scale;
-        if (a.scale_dest) {
-            a.scale_dest[d0] = scale;
-            if (d1 >= 0) a.scale_dest[d1] = scale;
-        }
-    }
-    for (int c = g; c < nchunk; c += QGROUPS) {
-        uint32_t w[4] = {0, 0, 0, 0};
-        if (amax != 0.0f) {
-            load_y16(xrow, s, c, y);
+    float scale[RS], rscale[RS];
+    bool sfast[RS];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[i], scale) & 0xff) << (8 * (i % 4));
-        }
-        const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
-        if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)t * a.ldq + c * 16) = v;
-        if (a.q_cm) {
-            *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + d0) * 16) = v;
-            if (d1 >= 0) *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + d1) * 16) = v;
+    for (int r = 0; r < RS; ++r) {
+        float m = 0.0f;
+        for (int w = 0; w < waves_per_group; ++w) m = fmaxf(m, red[g * waves_per_group + w][r]);
+        amax[r] = m;
+        scale[r] = m / 127.0f;
+        rscale[r] = 1.0f / scale[r];
+        sfast[r] = scale[r] >= 0x1p-100f && scale[r] <= 0x1p100f;
+    }
+    if (c0 < nrow) {
+        const int t = row0 + c0;
+        float sc = 0.0f;
+#pragma unroll
+        for (int r = 0; r < RS; ++r)
+            if (r == c0) sc = scale[r];
+        if (a.scale_dest) a.scale_dest[t] = sc;
+        if (a.scale) a.scale[a.gather ? (a.gather[t] >> 1) : t] = sc;
+    }
+    for (int c = c0; c < nchunk; c += CL) {
+        bool fast = true;
+        if (s) fast = load_s16(s, c, sv, rv);
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            if (r < nrow) {
+                const int t = row0 + r;
+                uint32_t w[4] = {0, 0, 0, 0};
+                if (amax[r] != 0.0f) {
+                    load_x16(xrow[r], c, x);
+                    if (fast && sfast[r]) {  // the common case: both divisions through reciprocals
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float y = s ? div_by(x[i], sv[i], rv[i], true) : x[i];
+                            float q = rintf(div_by(y, scale[r], rscale[r], true));
+                            q = fminf(fmaxf(q, -127.0f), 127.0f);
+                            w[i / 4] |= (uint32_t)((int)q & 0xff) << (8 * (i % 4));
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float y = s ? x[i] / sv[i] : x[i];
+                            float q = rintf(y / scale[r]);
+                            q = fminf(fmaxf(q, -127.0f), 127.0f);
+                            w[i / 4] |= (uint32_t)((int)q & 0xff) << (8 * (i % 4));
+                        }
+                    }
+                }
+                const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+                if (a.q_rm) {
+                    const int tr = a.gather ? (a.gather[t] >> 1) : t;
+                    *reinterpret_cast<uint4*>(a.q_rm + (size_t)tr * a.ldq + c * 16) = v;
+                }
+                if (a.q_cm) *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + t) * 16) = v;
+            }
         }
     }
 }
@@ -185,7 +289,20 @@ __global__ void pack_kernel(const int8_t* w1, const int8_t* w3, int K, int Nsrc,
 
 int launch_quant(const QuantArgs& a, hipStream_t st) {
     if (a.T <= 0) return HAQ_OK;
-    hipLaunchKernelGGL(smooth_quant_kernel, dim3(cdiv(a.T, QROWS)), dim3(QTHREADS), 0, st, a);
+    const int nchunk = a.K / 16;
+    int CL = (int)round_up(nchunk, 64);  // chunk lanes
+    if (CL > QMAX_THREADS) CL = QMAX_THREADS;
+    int G = QMAX_THREADS / CL;           // row groups: 1, 2, 4 or 8
+    G = G >= 8 ? 8 : G >= 4 ? 4 : G >= 2 ? 2 : 1;
+    const int threads = CL * G;
+    // with per-expert groups every group may end in a partial block: T/8 + E is an upper bound
+    const int blocks = a.tab ? a.T / QBLOCK_ROWS + a.E : cdiv(a.T, QBLOCK_ROWS);
+    switch (QBLOCK_ROWS / G) {
+        case 8: hipLaunchKernelGGL(smooth_quant_kernel<8>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
+        case 4: hipLaunchKernelGGL(smooth_quant_kernel<4>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
+        case 2: hipLaunchKernelGGL(smooth_quant_kernel<2>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
+        default: hipLaunchKernelGGL(smooth_quant_kernel<1>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
+    }
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
