@@ -58,6 +58,7 @@ struct MoeWs {
     ExpertTab* tab;
     int8_t *q_cm, *hq_cm;
     __half *mid, *y;
+    float* pmax;
     int64_t R;
     size_t bytes;
 };
@@ -80,6 +81,7 @@ MoeWs carve_moe(void* ws, int T, int H, int I, int E) {
     w.hq_cm = c.take<int8_t>((size_t)I * w.R);
     w.mid = c.take<__half>(P * (size_t)I);
     w.y = c.take<__half>(P * (size_t)H);
+    w.pmax = c.take<float>(P * (size_t)(I / 32 + 1));
     w.bytes = c.off;
     return w;
 }
@@ -240,7 +242,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         const haq_expert_desc& d = experts[e];
         if (!d.w13 || !d.w2 || !d.sw1 || !d.sw3 || !d.sw2 || !d.s_mid)
             HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d has a null pointer", e);
-        if (!aligned16(d.w13) || !aligned16(d.w2) || !aligned16(d.s_mid))
+        if (!aligned16(d.w13) || !aligned16(d.w2) || !aligned16(d.s_mid) || !aligned16(d.sw1) || !aligned16(d.sw3) || !aligned16(d.sw2))
             HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d pointers must be 16-byte aligned", e);
         if (d.location != HAQ_LOC_DEVICE) {
             if (d.location != HAQ_LOC_HOST_PINNED) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d location=%d", e, d.location);
@@ -269,9 +271,9 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     float* sh = d.sh ? d.sh : w.sh;
 
     int rc;
-    if ((rc = upload_tab(tab, E, w.tab, st)) != HAQ_OK) return rc;
-    if ((rc = launch_route((const __half*)logits_fp16, ldl, T, E, idx, gw, st)) != HAQ_OK) return rc;
-    if ((rc = launch_permute(idx, P, E, counts, offsets, perm, inv, st)) != HAQ_OK) return rc;
+    if ((rc = launch_route_permute((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv,
+                                   st)) != HAQ_OK)
+        return rc;
 
     QuantArgs qa{};
     qa.x = (const __half*)x_fp16;
@@ -287,6 +289,29 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qa.scale = d.sx;
     qa.scale_dest = w.sx_sorted;
     if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
+
+    if (decode_supported(T, H, I)) {
+        // few rows per expert: stream every activated expert's weights once
+        DecodeArgs da{};
+        da.q_cm = w.q_cm;
+        da.sx = w.sx_sorted;
+        da.R = w.R;
+        da.offsets = offsets;
+        da.tab = w.tab;
+        da.E = E;
+        da.H = H;
+        da.I = I;
+        da.Npad13 = round_up(2 * (int64_t)I, NPAD);
+        da.Npad2 = round_up(H, NPAD);
+        da.mid = mid;
+        da.pmax = w.pmax;
+        da.hq_cm = w.hq_cm;
+        da.hq_rm = d.hq;
+        da.sh = sh;
+        da.y = y;
+        if ((rc = launch_decode(da, T, st)) != HAQ_OK) return rc;
+        return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+    }
 
     GemmArgs g1{};
     g1.A = w.q_cm;

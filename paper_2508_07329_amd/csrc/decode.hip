@@ -1,0 +1,258 @@
+// Decode path of the routed expert FFN: at most 64 rows per expert, so every
+// activated expert's int8 weights are streamed from HBM exactly once and the
+// work is bound by that stream (Section III.B.3: experts stay int8 on the GPU to
+// relieve memory bandwidth).
+//
+// Weight fragments go straight from global memory into MFMA operand registers
+// (no LDS: nothing is reused): with the chunk-major layout a lane's 16 bytes are
+// one output channel's 16 consecutive k, lanes 0-31 cover 32 neighbouring
+// channels (512 contiguous bytes) and lanes 32-63 the next k chunk.  The weights
+// are the first MFMA operand, the (few) token rows the second, so a lane ends up
+// with 16 output channels of one token.  The K range of a unit of output
+// channels is split across the waves of a work-group and the exact int32
+// partial sums are added through LDS.
+#include "haq_common.h"
+#include "moe.h"
+
+namespace haq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef const __attribute__((address_space(1))) v4i* gptr_v4i;
+__device__ __forceinline__ v4i gload16(const int8_t* p) { return *(gptr_v4i)(uintptr_t)p; }
+
+constexpr int GU_WAVES = 4;    // gate/up: 64 packed channels (32 gate + 32 up) per work-group
+constexpr int DN_WAVES = 8;    // down: 32 channels per work-group, K split 8 ways
+constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave (two operands each)
+constexpr int DN_DEPTH = 14;
+
+// ---- gate / up projections + SwiGLU + per-unit row maxima of h / s_mid ---------------
+// Rows [32*rb, 32*rb + 32) of every expert; experts with fewer rows leave at once.
+__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a, int rb) {
+    __shared__ int part[GU_WAVES][2][16][64];
+    __shared__ float wmax[GU_WAVES][32];
+    const int e = blockIdx.y, unit = blockIdx.x;
+    const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
+    if (m <= 0) return;
+    const ExpertTab& t = a.tab[e];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int nchunk = a.H / 16;
+    const int cpw = nchunk / GU_WAVES;  // chunks per wave (even)
+    const int c0 = wave * cpw + hi;     // this lane's first chunk; it advances by 2 per MFMA
+    const int64_t npad = a.Npad13;
+    // running pointers to the next k-step to fetch (gate fragment; the up fragment is 512 bytes further)
+    const int8_t* pw = t.w13 + ((size_t)c0 * npad + unit * 64 + l32) * 16;
+    const size_t wstep = (size_t)2 * npad * 16;
+    const int8_t* px = a.q_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    const size_t xstep = (size_t)2 * a.R * 16;
+
+    v16i accg, accu;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accg[r] = accu[r] = 0;
+
+    // rolling prefetch: GU_DEPTH k-steps of fragments are always in flight.  Straight-line groups of
+    // GU_DEPTH steps (fill, steady state, drain), then a plain loop for what is left.
+    const int nks = cpw / 2;
+    const int ngroups = nks / GU_DEPTH;
+    auto fetch = [&](v4i& g, v4i& u, v4i& x) {
+        g = gload16(pw);
+        u = gload16(pw + 512);
+        x = gload16(px);
+        pw += wstep;
+        px += xstep;
+    };
+    if (ngroups > 0) {
+        v4i fg[GU_DEPTH], fu[GU_DEPTH], fx[GU_DEPTH];
+#pragma unroll
+        for (int i = 0; i < GU_DEPTH; ++i) fetch(fg[i], fu[i], fx[i]);
+        for (int grp = 0; grp + 1 < ngroups; ++grp) {
+#pragma unroll
+            for (int i = 0; i < GU_DEPTH; ++i) {
+                const v4i g = fg[i], u = fu[i], x = fx[i];
+                fetch(fg[i], fu[i], fx[i]);
+                accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(g, x, accg, 0, 0, 0);
+                accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(u, x, accu, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < GU_DEPTH; ++i) {
+            accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(fg[i], fx[i], accg, 0, 0, 0);
+            accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(fu[i], fx[i], accu, 0, 0, 0);
+        }
+    }
+    for (int k = ngroups * GU_DEPTH; k < nks; ++k) {
+        v4i g, u, x;
+        fetch(g, u, x);
+        accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(g, x, accg, 0, 0, 0);
+        accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(u, x, accu, 0, 0, 0);
+    }
+    // exact int32 reduction over the K split
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        part[wave][0][r][lane] = accg[r];
+        part[wave][1][r][lane] = accu[r];
+    }
+    __syncthreads();
+    // wave w finishes registers 4w..4w+3: channels 8w + 4*hi + 0..3 of the unit, token row l32
+    const int ch = unit * 32 + 8 * wave + 4 * hi;
+    const float4 s1 = *reinterpret_cast<const float4*>(t.sw1 + ch);
+    const float4 s3 = *reinterpret_cast<const float4*>(t.sw3 + ch);
+    const float4 sm = *reinterpret_cast<const float4*>(t.s_mid + ch);
+    const float s1v[4] = {s1.x, s1.y, s1.z, s1.w}, s3v[4] = {s3.x, s3.y, s3.z, s3.w}, smv[4] = {sm.x, sm.y, sm.z, sm.w};
+    const bool live = l32 < m;
+    const float sx = live ? a.sx[lo + l32] : 0.0f;
+    __half hv[4];
+    float ymax = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int g = 0, u = 0;
+#pragma unroll
+        for (int w = 0; w < GU_WAVES; ++w) {
+            g += part[w][0][4 * wave + q][lane];
+            u += part[w][1][4 * wave + q][lane];
+        }
+        const float gf = dequant(g, sx, s1v[q]), uf = dequant(u, sx, s3v[q]);
+        hv[q] = f2h(silu(gf) * uf);
+        ymax = fmaxf(ymax, fabsf(h2f(hv[q]) / smv[q]));
+    }
+    if (live) *reinterpret_cast<uint2*>(a.mid + (size_t)(lo + l32) * a.I + ch) = *reinterpret_cast<const uint2*>(hv);
+    ymax = fmaxf(ymax, __shfl_xor(ymax, 32));
+    if (hi == 0) wmax[wave][l32] = ymax;
+    __syncthreads();
+    // one partial row maximum of |h / s_mid| per (row, unit): reduced by the requantisation kernel
+    if (tid < 32 && tid < m) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < GU_WAVES; ++w) v = fmaxf(v, wmax[w][tid]);
+        a.pmax[(size_t)(lo + tid) * (a.I / 32) + unit] = v;
+    }
+}
+
+// ---- requantisation of the intermediate with known partial maxima ------------------------
+// One work-group per sorted row: reduce the row's partial maxima, then round h / s_mid / scale.
+__global__ __launch_bounds__(256) void decode_requant_kernel(DecodeArgs a) {
+    __shared__ float red[4];
+    const int pos = blockIdx.x;
+    int e = 0;
+    while (e + 1 < a.E && pos >= a.offsets[e + 1]) ++e;
+    const float* s = a.tab[e].s_mid;
+    const int tid = threadIdx.x, nu = a.I / 32;
+    float m = 0.0f;
+    for (int i = tid; i < nu; i += 256) m = fmaxf(m, a.pmax[(size_t)pos * nu + i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((tid & 63) == 0) red[tid >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float scale = m / 127.0f;
+    if (tid == 0) a.sh[pos] = scale;
+    const __half* hrow = a.mid + (size_t)pos * a.I;
+    for (int c = tid; c < a.I / 16; c += 256) {
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (m != 0.0f) {
+            const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
+            const uint4 r0 = px[0], r1 = px[1];
+            const __half* h0 = reinterpret_cast<const __half*>(&r0);
+            const __half* h1 = reinterpret_cast<const __half*>(&r1);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float x = h2f(i < 8 ? h0[i] : h1[i - 8]);
+                const float y = x / s[c * 16 + i];
+                w[i / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (i % 4));
+            }
+        }
+        const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4*>(a.hq_cm + ((size_t)c * a.R + pos) * 16) = v;
+        if (a.hq_rm) *reinterpret_cast<uint4*>(a.hq_rm + (size_t)pos * a.I + c * 16) = v;
+    }
+}
+
+// ---- down projection ---------------------------------------------------------------------
+__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a, int rb) {
+    __shared__ int part[DN_WAVES][16][64];
+    const int e = blockIdx.y, unit = blockIdx.x;
+    const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
+    if (m <= 0) return;
+    const ExpertTab& t = a.tab[e];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int nchunk = a.I / 16;
+    const int cpw = nchunk / DN_WAVES;
+    const int c0 = wave * cpw + hi;
+    const int64_t npad = a.Npad2;
+    const int8_t* pw = t.w2 + ((size_t)c0 * npad + unit * 32 + l32) * 16;  // next k-step to fetch
+    const size_t wstep = (size_t)2 * npad * 16;
+    const int8_t* px = a.hq_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    const size_t xstep = (size_t)2 * a.R * 16;
+
+    v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+
+    const int nks = cpw / 2;
+    const int ngroups = nks / DN_DEPTH;
+    auto fetch = [&](v4i& w, v4i& x) {
+        w = gload16(pw);
+        x = gload16(px);
+        pw += wstep;
+        px += xstep;
+    };
+    if (ngroups > 0) {
+        v4i fw[DN_DEPTH], fx[DN_DEPTH];
+#pragma unroll
+        for (int i = 0; i < DN_DEPTH; ++i) fetch(fw[i], fx[i]);
+        for (int grp = 0; grp + 1 < ngroups; ++grp) {
+#pragma unroll
+            for (int i = 0; i < DN_DEPTH; ++i) {
+                const v4i w = fw[i], x = fx[i];
+                fetch(fw[i], fx[i]);
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < DN_DEPTH; ++i) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fx[i], acc, 0, 0, 0);
+    }
+    for (int k = ngroups * DN_DEPTH; k < nks; ++k) {
+        v4i w, x;
+        fetch(w, x);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[r];
+    __syncthreads();
+    // wave w finishes registers 2w, 2w+1: channels 8*(r/4) + 4*hi + r%4 of the unit
+    const bool live = l32 < m;
+    const float sh = live ? a.sh[lo + l32] : 0.0f;
+    const int r0 = 2 * wave;
+    const int ch = unit * 32 + 8 * (r0 / 4) + 4 * hi + (r0 % 4);
+    __half hv[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        int v = 0;
+#pragma unroll
+        for (int w = 0; w < DN_WAVES; ++w) v += part[w][r0 + q][lane];
+        hv[q] = f2h(dequant(v, sh, t.sw2[ch + q]));
+    }
+    if (live) *reinterpret_cast<uint32_t*>(a.y + (size_t)(lo + l32) * a.H + ch) = *reinterpret_cast<const uint32_t*>(hv);
+}
+
+}  // namespace
+
+bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 32) == 0 && I % (DN_WAVES * 32) == 0; }
+
+int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
+    const int P = 2 * T;
+    const dim3 g1(a.I / 32, a.E), g2(a.H / 32, a.E);
+    // an expert holds at most T rows: one launch per block of 32 rows (experts with fewer leave at once)
+    const int nrb = cdiv(T, 32);
+    for (int rb = 0; rb < nrb; ++rb) hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a, rb);
+    hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(256), 0, st, a);
+    for (int rb = 0; rb < nrb; ++rb) hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a, rb);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+}  // namespace haq

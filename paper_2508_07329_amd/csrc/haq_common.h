@@ -132,4 +132,23 @@ struct GemmArgs {
 };
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st);
 
+// Decode path (at most 64 rows per expert): weight-streaming kernels.
+struct DecodeArgs {
+    const int8_t* q_cm;   // token codes, chunk-major [H/16][R][16], sorted-pair rows
+    const float* sx;      // [P] sorted
+    int64_t R;
+    const int32_t* offsets;
+    const ExpertTab* tab;
+    int E, H, I;
+    int64_t Npad13, Npad2;
+    __half* mid;          // [P x I] sorted
+    float* pmax;          // [P x I/32] partial row maxima of |h / s_mid|
+    int8_t* hq_cm;        // [I/16][R][16]
+    int8_t* hq_rm;        // optional dense [P x I]
+    float* sh;            // [P]
+    __half* y;            // [P x H] sorted
+};
+bool decode_supported(int T, int H, int I);
+int launch_decode(const DecodeArgs& a, int T, hipStream_t st);
+
 }  // namespace haq

@@ -3,10 +3,9 @@
 #include "haq_common.h"
 
 namespace haq {
-int launch_route(const __half* logits, int64_t ldl, int T, int E, int32_t* idx, float* gw, hipStream_t st);
-int launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                   hipStream_t st);
+int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
+                         int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                         hipStream_t st);
 int launch_combine(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H, __half* out,
                    int64_t ldo, hipStream_t st);
-int upload_tab(const ExpertTab* host, int E, ExpertTab* dev, hipStream_t st);
 }  // namespace haq

@@ -8,13 +8,10 @@ namespace haq {
 
 namespace {
 
-// One thread per token.  Top-2 by logit (lowest index wins ties); gate weights are
-// the softmax over all experts, renormalised over the two.  The sum runs over the
-// experts in index order so that every implementation rounds alike.
-__global__ void route_top2_kernel(const __half* logits, int64_t ldl, int T, int E, int32_t* idx, float* gw) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= T) return;
-    const __half* l = logits + (size_t)t * ldl;
+// Top-2 by logit (lowest index wins ties); gate weights are the softmax over all experts,
+// renormalised over the two.  The sum runs over the experts in index order so that every
+// implementation rounds alike.
+__device__ __forceinline__ void route_token(const __half* l, int E, int32_t* idx, float* gw) {
     int i0 = 0;
     float l0 = h2f(l[0]);
     for (int e = 1; e < E; ++e) {
@@ -38,36 +35,62 @@ __global__ void route_top2_kernel(const __half* logits, int64_t ldl, int T, int 
     const float p0 = exp_spec(l0 - l0) / z;
     const float p1 = exp_spec(l1 - l0) / z;
     const float d = p0 + p1;
-    idx[2 * t] = i0;
-    idx[2 * t + 1] = i1;
-    gw[2 * t] = p0 / d;
-    gw[2 * t + 1] = p1 / d;
+    idx[0] = i0;
+    idx[1] = i1;
+    gw[0] = p0 / d;
+    gw[1] = p1 / d;
 }
 
-// Stable counting sort of the P = 2T pairs by expert, one work-group.  Thread i
-// owns a contiguous run of pair ids, so ranks inside an expert follow pair id.
+struct TabAll {
+    ExpertTab e[32];
+};
+
+// One work-group does the whole routing side: router top-2 for every token, then a stable
+// counting sort of the P = 2T pairs by expert (thread i owns a contiguous run of pair ids, so
+// ranks inside an expert follow pair id), and it drops the expert table into device memory
+// for the kernels that follow.
 constexpr int PERM_THREADS = 256;
-__global__ __launch_bounds__(PERM_THREADS) void permute_kernel(const int32_t* idx, int P, int E, int32_t* counts,
-                                                                int32_t* offsets, int32_t* perm, int32_t* inv) {
+__global__ __launch_bounds__(PERM_THREADS) void route_permute_kernel(const __half* logits, int64_t ldl, int T, int E,
+                                                                     TabAll tab, ExpertTab* tab_dev, int32_t* idx,
+                                                                     float* gw, int32_t* counts, int32_t* offsets,
+                                                                     int32_t* perm, int32_t* inv) {
     extern __shared__ int32_t sm[];  // cnt[E][PERM_THREADS], then off[E + 1]
     int32_t* cnt = sm;
     int32_t* off = sm + E * PERM_THREADS;
     const int tid = threadIdx.x;
+    const int P = 2 * T;
+    if (tid < E) tab_dev[tid] = tab.e[tid];
+    for (int t = tid; t < T; t += PERM_THREADS) route_token(logits + (size_t)t * ldl, E, idx + 2 * t, gw + 2 * t);
+    __syncthreads();  // idx is re-read below by other threads (global memory, same work-group)
     const int seg = (P + PERM_THREADS - 1) / PERM_THREADS;
     const int lo = min(P, tid * seg), hi = min(P, lo + seg);
     for (int e = 0; e < E; ++e) cnt[e * PERM_THREADS + tid] = 0;
     for (int r = lo; r < hi; ++r) cnt[idx[r] * PERM_THREADS + tid] += 1;
     __syncthreads();
-    // exclusive scan over the threads, one expert per thread
-    for (int e = tid; e < E; e += PERM_THREADS) {
-        int run = 0;
-        for (int i = 0; i < PERM_THREADS; ++i) {
-            const int c = cnt[e * PERM_THREADS + i];
-            cnt[e * PERM_THREADS + i] = run;
-            run += c;
+    // exclusive scan over the 256 per-thread counts of each expert: one wave per expert at a
+    // time, four counts per lane, lane sums scanned with shuffles
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+        for (int e = wave; e < E; e += PERM_THREADS / 64) {
+            int32_t* row = cnt + e * PERM_THREADS + 4 * lane;
+            const int c0 = row[0], c1 = row[1], c2 = row[2], c3 = row[3];
+            const int sum = c0 + c1 + c2 + c3;
+            int incl = sum;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(incl, o);
+                if (lane >= o) incl += v;
+            }
+            const int excl = incl - sum;
+            row[0] = excl;
+            row[1] = excl + c0;
+            row[2] = excl + c0 + c1;
+            row[3] = excl + c0 + c1 + c2;
+            if (lane == 63) {
+                counts[e] = incl;
+                off[e] = incl;  // count for now
+            }
         }
-        counts[e] = run;
-        off[e] = run;  // count for now
     }
     __syncthreads();
     if (tid == 0) {
@@ -114,26 +137,16 @@ __global__ void combine_kernel(const __half* y, int64_t ldy, const int32_t* inv,
     }
 }
 
-struct TabChunk {
-    ExpertTab e[8];
-};
-__global__ void write_tab_kernel(TabChunk c, ExpertTab* dst, int base, int n) {
-    const int i = threadIdx.x;
-    if (i < n) dst[base + i] = c.e[i];
-}
-
 }  // namespace
 
-int launch_route(const __half* logits, int64_t ldl, int T, int E, int32_t* idx, float* gw, hipStream_t st) {
-    hipLaunchKernelGGL(route_top2_kernel, dim3(cdiv(T, 64)), dim3(64), 0, st, logits, ldl, T, E, idx, gw);
-    HAQ_CHECK_HIP(hipGetLastError());
-    return HAQ_OK;
-}
-
-int launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                   hipStream_t st) {
+int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
+                         int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                         hipStream_t st) {
+    TabAll tab{};
+    for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
     const size_t sm = ((size_t)E * PERM_THREADS + E + 1) * sizeof(int32_t);
-    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, idx, P, E, counts, offsets, perm, inv);
+    hipLaunchKernelGGL(route_permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, logits, ldl, T, E, tab, tab_dev, idx, gw,
+                       counts, offsets, perm, inv);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
@@ -141,17 +154,6 @@ int launch_permute(const int32_t* idx, int P, int E, int32_t* counts, int32_t* o
 int launch_combine(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H, __half* out,
                    int64_t ldo, hipStream_t st) {
     hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, st, y, ldy, inv, gw, T, H, out, ldo);
-    HAQ_CHECK_HIP(hipGetLastError());
-    return HAQ_OK;
-}
-
-int upload_tab(const ExpertTab* host, int E, ExpertTab* dev, hipStream_t st) {
-    for (int base = 0; base < E; base += 8) {
-        TabChunk c{};
-        const int n = (E - base < 8) ? E - base : 8;
-        for (int i = 0; i < n; ++i) c.e[i] = host[base + i];
-        hipLaunchKernelGGL(write_tab_kernel, dim3(1), dim3(8), 0, st, c, dev, base, n);
-    }
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -189,6 +189,13 @@ def test_moe_small_everything_bit_exact(T, H, I, E):
     _check_moe(offline.small_moe(seed=20 + T, T=T, H=H, I=I, E=E))
 
 
+@pytest.mark.parametrize("T,H,I,E", [(37, 128, 512, 8), (1, 128, 512, 8), (64, 256, 1024, 4), (33, 384, 512, 8),
+                                      (5, 128, 512, 2)])
+def test_moe_small_decode_path_bit_exact(T, H, I, E):
+    """Shapes that take the weight-streaming (at most 64 tokens) kernels."""
+    _check_moe(offline.small_moe(seed=40 + T, T=T, H=H, I=I, E=E))
+
+
 def test_moe_small_skewed_routing_and_empty_expert():
     m = offline.small_moe(seed=31, T=64, H=128, I=192, E=8, routing="popularity")
     m["logits"][:, 5] = -100  # nobody picks expert 5
