@@ -2,6 +2,7 @@
 // launch sequence of the linear layer and of the routed expert FFN.
 #include <cmath>
 #include <cstdarg>
+#include <new>
 
 #include "haq_common.h"
 #include "moe.h"
@@ -126,6 +127,19 @@ int gemm_packed(const int8_t* q_cm, const float* sx, const int8_t* w_packed, con
 
 using namespace haq;
 
+// Context of layers with host-resident experts: staging slots in HBM, the copy stream and the
+// events that order copies against the GEMMs that read (and later overwrite) a slot.
+struct haq_ctx {
+    int H = 0, I = 0, n_slots = 0;
+    size_t w13_bytes = 0, w2_bytes = 0;
+    hipStream_t copy_stream = nullptr;
+    int8_t* slot[32] = {};
+    hipEvent_t copied[32] = {}, done[32] = {};
+    hipEvent_t routed = nullptr, call_done = nullptr;
+    bool used = false;
+    int32_t* counts_host = nullptr;  // pinned
+};
+
 extern "C" {
 
 int32_t haq_version(void) { return 1; }
@@ -205,14 +219,47 @@ int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, con
 }
 
 int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out) {
-    (void)H;
-    (void)I;
-    (void)n_slots;
-    if (out) *out = nullptr;
-    HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_ctx_create: host-resident experts are not available yet");
+    if (!out) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_create: null output");
+    *out = nullptr;
+    if (H <= 0 || I <= 0 || n_slots < 1 || n_slots > 32) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_create: H=%d I=%d n_slots=%d", H, I, n_slots);
+    haq_ctx* c = new (std::nothrow) haq_ctx();
+    if (!c) HAQ_FAIL(HAQ_ERR_HIP, "haq_ctx_create: out of host memory");
+    c->H = H;
+    c->I = I;
+    c->n_slots = n_slots;
+    c->w13_bytes = haq_packed_bytes(H, 2 * I);
+    c->w2_bytes = haq_packed_bytes(I, H);
+    hipError_t e = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking);  // default priority
+    for (int i = 0; e == hipSuccess && i < n_slots; ++i) e = hipMalloc((void**)&c->slot[i], c->w13_bytes + c->w2_bytes);
+    for (int i = 0; e == hipSuccess && i < 32; ++i) {
+        e = hipEventCreateWithFlags(&c->copied[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->routed, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->call_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->counts_host, 32 * sizeof(int32_t), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        set_error("haq_ctx_create: %s", hipGetErrorString(e));
+        haq_ctx_destroy(c);
+        return HAQ_ERR_HIP;
+    }
+    *out = c;
+    return HAQ_OK;
 }
-int32_t haq_ctx_destroy(haq_ctx* ctx) {
-    (void)ctx;
+
+int32_t haq_ctx_destroy(haq_ctx* c) {
+    if (!c) return HAQ_OK;
+    if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+    for (int i = 0; i < 32; ++i) {
+        if (c->slot[i]) (void)hipFree(c->slot[i]);
+        if (c->copied[i]) (void)hipEventDestroy(c->copied[i]);
+        if (c->done[i]) (void)hipEventDestroy(c->done[i]);
+    }
+    if (c->routed) (void)hipEventDestroy(c->routed);
+    if (c->call_done) (void)hipEventDestroy(c->call_done);
+    if (c->counts_host) (void)hipHostFree(c->counts_host);
+    if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+    delete c;
     return HAQ_OK;
 }
 
@@ -225,7 +272,6 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
                          const float* s_in, const haq_expert_desc* experts, int32_t T, int32_t H, int32_t I, int32_t E,
                          int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg, void* workspace,
                          size_t workspace_bytes, void* stream) {
-    (void)ctx;
     if (T < 0 || H <= 0 || I <= 0 || E <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: T=%d H=%d I=%d E=%d", T, H, I, E);
     if (top_k != 2) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: top_k=%d (only 2)", top_k);
     if (E < 2 || E > 32) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: E=%d outside [2, 32]", E);
@@ -238,17 +284,24 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     if (!aligned16(x_fp16) || !aligned16(out_fp16) || (s_in && !aligned16(s_in)))
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: pointers must be 16-byte aligned");
     ExpertTab tab[32];
+    int host_expert[32], n_host = 0;
     for (int e = 0; e < E; ++e) {
         const haq_expert_desc& d = experts[e];
         if (!d.w13 || !d.w2 || !d.sw1 || !d.sw3 || !d.sw2 || !d.s_mid)
             HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d has a null pointer", e);
         if (!aligned16(d.w13) || !aligned16(d.w2) || !aligned16(d.s_mid) || !aligned16(d.sw1) || !aligned16(d.sw3) || !aligned16(d.sw2))
             HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d pointers must be 16-byte aligned", e);
+        tab[e] = ExpertTab{d.w13, d.w2, d.sw1, d.sw3, d.sw2, d.s_mid};
         if (d.location != HAQ_LOC_DEVICE) {
             if (d.location != HAQ_LOC_HOST_PINNED) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d location=%d", e, d.location);
-            HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn: expert %d is host resident: not available yet", e);
+            if (!ctx) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d is host resident but no context was given", e);
+            if (ctx->H != H || ctx->I != I) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: context was created for H=%d I=%d", ctx->H, ctx->I);
+            // the i-th host-resident expert is staged in slot i mod n_slots
+            int8_t* slot = ctx->slot[n_host % ctx->n_slots];
+            tab[e].w13 = slot;
+            tab[e].w2 = slot + ctx->w13_bytes;
+            host_expert[n_host++] = e;
         }
-        tab[e] = ExpertTab{d.w13, d.w2, d.sw1, d.sw3, d.sw2, d.s_mid};
     }
     const size_t need = carve_moe(nullptr, T, H, I, E).bytes;
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
@@ -290,7 +343,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qa.scale_dest = w.sx_sorted;
     if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
 
-    if (decode_supported(T, H, I)) {
+    if (n_host == 0 && decode_supported(T, H, I)) {
         // few rows per expert: stream every activated expert's weights once
         DecodeArgs da{};
         da.q_cm = w.q_cm;
@@ -313,57 +366,131 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
     }
 
-    GemmArgs g1{};
-    g1.A = w.q_cm;
-    g1.R = w.R;
-    g1.sx = w.sx_sorted;
-    g1.K = H;
-    g1.N = 2 * I;
-    g1.Npad = round_up(2 * (int64_t)I, NPAD);
-    g1.offsets = offsets;
-    g1.tab = w.tab;
-    g1.which = 0;
-    g1.n_sel = E;
-    for (int e = 0; e < E; ++e) g1.sel[e] = e;
-    g1.max_rows = P;
-    g1.Y = mid;
-    g1.ldy = I;
-    if ((rc = launch_gemm(g1, EPI_SWIGLU, st)) != HAQ_OK) return rc;
+    // gate/up GEMM + SwiGLU, requantisation and down GEMM for a set of experts (rows of the others untouched)
+    auto run_experts = [&](const int* sel, int n_sel, int max_rows) -> int {
+        GemmArgs g1{};
+        g1.A = w.q_cm;
+        g1.R = w.R;
+        g1.sx = w.sx_sorted;
+        g1.K = H;
+        g1.N = 2 * I;
+        g1.Npad = round_up(2 * (int64_t)I, NPAD);
+        g1.offsets = offsets;
+        g1.tab = w.tab;
+        g1.which = 0;
+        g1.n_sel = n_sel;
+        for (int i = 0; i < n_sel; ++i) g1.sel[i] = sel[i];
+        g1.max_rows = max_rows;
+        g1.Y = mid;
+        g1.ldy = I;
+        int r = launch_gemm(g1, EPI_SWIGLU, st);
+        if (r != HAQ_OK) return r;
 
-    QuantArgs qb{};
-    qb.x = mid;
-    qb.ldx = I;
-    qb.tab = w.tab;
-    qb.offsets = offsets;
-    qb.E = E;
-    qb.T = P;
-    qb.K = I;
-    qb.q_rm = d.hq;
-    qb.ldq = I;
-    qb.q_cm = w.hq_cm;
-    qb.R = w.R;
-    qb.scale_dest = sh;
-    if ((rc = launch_quant(qb, st)) != HAQ_OK) return rc;
+        QuantArgs qb{};
+        qb.x = mid;
+        qb.ldx = I;
+        qb.tab = w.tab;
+        qb.offsets = offsets;
+        qb.E = E;
+        qb.T = P;
+        qb.K = I;
+        qb.q_rm = d.hq;
+        qb.ldq = I;
+        qb.q_cm = w.hq_cm;
+        qb.R = w.R;
+        qb.scale_dest = sh;
+        qb.n_sel = n_sel;
+        for (int i = 0; i < n_sel; ++i) qb.sel[i] = sel[i];
+        qb.max_rows = max_rows;
+        if ((r = launch_quant(qb, st)) != HAQ_OK) return r;
 
-    GemmArgs g2{};
-    g2.A = w.hq_cm;
-    g2.R = w.R;
-    g2.sx = sh;
-    g2.K = I;
-    g2.N = H;
-    g2.Npad = round_up(H, NPAD);
-    g2.offsets = offsets;
-    g2.tab = w.tab;
-    g2.which = 1;
-    g2.n_sel = E;
-    for (int e = 0; e < E; ++e) g2.sel[e] = e;
-    g2.max_rows = P;
-    g2.act = HAQ_ACT_NONE;
-    g2.Y = y;
-    g2.ldy = H;
-    if ((rc = launch_gemm(g2, EPI_LINEAR, st)) != HAQ_OK) return rc;
+        GemmArgs g2{};
+        g2.A = w.hq_cm;
+        g2.R = w.R;
+        g2.sx = sh;
+        g2.K = I;
+        g2.N = H;
+        g2.Npad = round_up(H, NPAD);
+        g2.offsets = offsets;
+        g2.tab = w.tab;
+        g2.which = 1;
+        g2.n_sel = n_sel;
+        for (int i = 0; i < n_sel; ++i) g2.sel[i] = sel[i];
+        g2.max_rows = max_rows;
+        g2.act = HAQ_ACT_NONE;
+        g2.Y = y;
+        g2.ldy = H;
+        return launch_gemm(g2, EPI_LINEAR, st);
+    };
 
-    return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+    if (n_host == 0) {
+        int all[32];
+        for (int e = 0; e < E; ++e) all[e] = e;
+        if ((rc = run_experts(all, E, P)) != HAQ_OK) return rc;
+        return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+    }
+
+    // ---- some experts live in pinned host memory (Section III.C: experts are moved in their
+    // low-bit form).  The routing result comes back to the host (one small blocking copy), the
+    // activated host experts are copied into the staging slots on the copy stream, and the
+    // device-resident experts compute meanwhile; each streamed expert computes as soon as its
+    // copy has landed and frees its slot for the expert n_slots further down the list.
+    HAQ_CHECK_HIP(hipMemcpyAsync(ctx->counts_host, counts, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HAQ_CHECK_HIP(hipEventRecord(ctx->routed, st));
+    HAQ_CHECK_HIP(hipEventSynchronize(ctx->routed));
+    // slots may still be read by the previous call on another stream
+    if (ctx->used) HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->call_done, 0));
+    int resident[32], n_res = 0, res_rows = 0;
+    bool is_host[32] = {};
+    for (int i = 0; i < n_host; ++i) is_host[host_expert[i]] = true;
+    for (int e = 0; e < E; ++e)
+        if (!is_host[e] && ctx->counts_host[e] > 0) {
+            resident[n_res++] = e;
+            res_rows += ctx->counts_host[e];
+        }
+    // activated host experts, in list order; entry i of the host list is staged in slot i mod n_slots
+    int order[32], n_order = 0;
+    for (int i = 0; i < n_host; ++i)
+        if (ctx->counts_host[host_expert[i]] > 0) order[n_order++] = i;
+    bool issued[32] = {}, slot_taken[32] = {};
+    auto issue_copy = [&](int i) -> int {
+        const int e = host_expert[i];
+        int8_t* slot = ctx->slot[i % ctx->n_slots];
+        HAQ_CHECK_HIP(hipMemcpyAsync(slot, experts[e].w13, ctx->w13_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
+        HAQ_CHECK_HIP(hipMemcpyAsync(slot + ctx->w13_bytes, experts[e].w2, ctx->w2_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
+        HAQ_CHECK_HIP(hipEventRecord(ctx->copied[i], ctx->copy_stream));
+        issued[i] = true;
+        return HAQ_OK;
+    };
+    // the first user of every slot is copied right away
+    for (int k = 0; k < n_order; ++k) {
+        const int i = order[k], sl = i % ctx->n_slots;
+        if (slot_taken[sl]) continue;
+        slot_taken[sl] = true;
+        if ((rc = issue_copy(i)) != HAQ_OK) return rc;
+    }
+    // device-resident experts compute while the first copies are in flight
+    if (n_res > 0 && (rc = run_experts(resident, n_res, res_rows)) != HAQ_OK) return rc;
+    for (int k = 0; k < n_order; ++k) {
+        const int i = order[k], e = host_expert[i];
+        HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[i], 0));  // issued: either above or when its slot's previous user finished
+        if ((rc = run_experts(&e, 1, ctx->counts_host[e])) != HAQ_OK) return rc;
+        HAQ_CHECK_HIP(hipEventRecord(ctx->done[i], st));
+        // this expert's slot is free after its GEMMs: hand it to the next activated expert of the same slot
+        for (int k2 = k + 1; k2 < n_order; ++k2) {
+            const int j = order[k2];
+            if (j % ctx->n_slots != i % ctx->n_slots) continue;
+            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->done[i], 0));
+            if ((rc = issue_copy(j)) != HAQ_OK) return rc;
+            break;
+        }
+    }
+    for (int k = 0; k < n_order; ++k)
+        if (!issued[order[k]]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
+    rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+    HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
+    ctx->used = true;
+    return rc;
 }
 
 }  // extern "C"

@@ -102,6 +102,9 @@ struct QuantArgs {
                             // (sorted pair -> token), and T counts output rows
     float* scale;      // optional, indexed by input row
     float* scale_dest; // optional, indexed by output row
+    int n_sel;         // with tab: the experts whose row groups this launch covers
+    int sel[32];
+    int max_rows;      // with tab: upper bound of the rows of the selected groups (grid sizing)
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 

@@ -80,9 +80,10 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_kernel(QuantArgs a,
     int row0, row_end;
     const float* s = a.s;
     if (a.tab) {
-        int b = blockIdx.x, e = 0;
+        int b = blockIdx.x, i = 0, e = 0;
         row0 = row_end = 0;
-        for (; e < a.E; ++e) {
+        for (; i < a.n_sel; ++i) {
+            e = a.sel[i];
             const int lo = a.offsets[e], hi = a.offsets[e + 1];
             const int nb = (hi - lo + QBLOCK_ROWS - 1) / QBLOCK_ROWS;
             if (b < nb) {
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_kernel(QuantArgs a,
             }
             b -= nb;
         }
-        if (e == a.E) return;  // the grid is an upper bound
+        if (i == a.n_sel) return;  // the grid is an upper bound
         s = a.tab[e].s_mid;
     } else {
         row0 = blockIdx.x * QBLOCK_ROWS;
@@ -296,7 +297,7 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     G = G >= 8 ? 8 : G >= 4 ? 4 : G >= 2 ? 2 : 1;
     const int threads = CL * G;
     // with per-expert groups every group may end in a partial block: T/8 + E is an upper bound
-    const int blocks = a.tab ? a.T / QBLOCK_ROWS + a.E : cdiv(a.T, QBLOCK_ROWS);
+    const int blocks = a.tab ? a.max_rows / QBLOCK_ROWS + a.n_sel : cdiv(a.T, QBLOCK_ROWS);
     switch (QBLOCK_ROWS / G) {
         case 8: hipLaunchKernelGGL(smooth_quant_kernel<8>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
         case 4: hipLaunchKernelGGL(smooth_quant_kernel<4>, dim3(blocks), dim3(threads), 0, st, a, CL); break;

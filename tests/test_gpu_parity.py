@@ -203,6 +203,48 @@ def test_moe_small_skewed_routing_and_empty_expert():
     assert counts[5] == 0 and counts.max() > 2 * np.median(counts)
 
 
+# ------------------------------------------------------------------ experts streamed from pinned host memory
+def _offload(dev_experts, host_ids):
+    """Copies of the experts in `host_ids` moved to pinned host memory (the others stay as they are)."""
+    out = []
+    for e, ex in enumerate(dev_experts):
+        if e in host_ids:
+            w13 = torch.empty(ex.w13.shape, dtype=torch.int8, pin_memory=True).copy_(ex.w13)
+            w2 = torch.empty(ex.w2.shape, dtype=torch.int8, pin_memory=True).copy_(ex.w2)
+            out.append(haq.ExpertWeights(w13, w2, ex.sw1, ex.sw3, ex.sw2, ex.s_mid, haq.HAQ_LOC_HOST_PINNED))
+        else:
+            out.append(ex)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("n_slots,host_ids", [(2, (4, 5, 6, 7)), (1, (0, 3, 5)), (3, (1, 2, 3, 4, 5, 6, 7))])
+def test_moe_offload_small_matches_resident_and_oracle(n_slots, host_ids):
+    m = offline.small_moe(seed=50 + n_slots, T=90, H=128, I=320, E=8, routing="popularity")
+    if n_slots == 1:
+        m["logits"][:, 3] = -100  # a host-resident expert nobody selects: never copied
+    dev_experts = upload_experts(m["experts"])
+    X, logits, s_in = dev(m["X"]), dev(m["logits"]), dev(m["s_in"])
+    ref = haq.haq_moe_w8a8_ffn(X, logits, s_in, dev_experts, 320)
+    ctx = haq.haq_ctx_create(128, 320, n_slots)
+    try:
+        mixed = _offload(dev_experts, host_ids)
+        _check_moe(m, mixed, ctx=ctx)
+        for _ in range(2):  # slots are reused across calls
+            out = haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, 320, ctx=ctx)
+            assert bits_equal(host(out), host(ref))
+    finally:
+        torch.cuda.synchronize()
+        haq.haq_ctx_destroy(ctx)
+
+
+def test_moe_offload_needs_context():
+    m = offline.small_moe(seed=53, T=8, H=128, I=320, E=8)
+    mixed = _offload(upload_experts(m["experts"]), (2,))
+    with pytest.raises(haq.HaqError):
+        haq.haq_moe_w8a8_ffn(dev(m["X"]), dev(m["logits"]), dev(m["s_in"]), mixed, 320)
+
+
 # ------------------------------------------------------------------ MoE at the Mixtral shape (sampled tokens)
 @pytest.fixture(scope="module")
 def layer():
@@ -220,6 +262,24 @@ def test_moe_mixtral_decode(layer, b):
     wl = {w.T: w for w in hi.MIXTRAL_DECODE}[b]
     tokens = np.arange(b) if b <= 8 else np.sort(np.random.default_rng(b).permutation(b)[:12])
     _check_moe(_mixtral_case(wl, layer), layer["dev_experts"], tokens)
+
+
+def test_moe_mixtral_offload_four_of_eight_resident(layer):
+    """256 tokens, experts 4-7 in pinned host memory and streamed through 2 staging slots."""
+    wl = hi.MIXTRAL_OFFLOAD
+    case = _mixtral_case(wl, layer)
+    mixed = _offload(layer["dev_experts"], set(range(wl.E)) - set(wl.resident))
+    ctx = haq.haq_ctx_create(wl.H, wl.I, 2)
+    try:
+        tokens = np.sort(np.random.default_rng(4).permutation(wl.T)[:16])
+        counts = _check_moe(case, mixed, tokens, ctx=ctx)
+        assert np.all(counts > 0)
+        ref = haq.haq_moe_w8a8_ffn(dev(case["X"]), dev(case["logits"]), layer["dev_s_in"], layer["dev_experts"], wl.I)
+        out = haq.haq_moe_w8a8_ffn(dev(case["X"]), dev(case["logits"]), layer["dev_s_in"], mixed, wl.I, ctx=ctx)
+        assert bits_equal(host(out), host(ref))
+    finally:
+        torch.cuda.synchronize()
+        haq.haq_ctx_destroy(ctx)
 
 
 def test_moe_mixtral_prefill_zipf(layer):
