@@ -80,10 +80,14 @@ def bench_ffn(args, torch, haq, hi):
         ws2 = torch.empty(haq.haq_linear_workspace_bytes(T, F, K), dtype=torch.uint8, device=dev)
         y = torch.empty((T, K), dtype=torch.float16, device=dev)
 
+    if two:
+        wsf = torch.empty(haq.haq_ffn_workspace_bytes(T, K, F, K), dtype=torch.uint8, device=dev)
+
     def step():
-        haq.haq_w8a8_linear(X, s1, w1p, sw1, F, haq.HAQ_ACT_RELU, out=h, workspace=ws1)
-        if two:
-            haq.haq_w8a8_linear(h, s2, w2p, sw2, K, haq.HAQ_ACT_NONE, out=y, workspace=ws2)
+        if two:  # the whole block in one call: quantise, fc1 + ReLU, requantise, fc2
+            haq.haq_w8a8_ffn(X, s1, w1p, sw1, F, haq.HAQ_ACT_RELU, s2, w2p, sw2, K, out=y, workspace=wsf)
+        else:
+            haq.haq_w8a8_linear(X, s1, w1p, sw1, F, haq.HAQ_ACT_RELU, out=h, workspace=ws1)
 
     sec = _time_steps(torch, step, args.steps, args.warmup)
     ops_per_gemm = 2.0 * T * K * F

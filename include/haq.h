@@ -128,6 +128,19 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
                         size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Two chained smoothed W8A8 linears (a dense FFN block, e.g. OPT: fc1, ReLU, fc2):
+ *   H = fp16(act(deq(Q(s1^-1 X) W1q)));   Y = fp16(deq(Q(s2^-1 H) W2q)).
+ * Results are identical to two haq_w8a8_linear calls; the block call keeps H and
+ * both sets of int8 codes in one workspace.  X [T x K], W1 packed
+ * [K x F], W2 packed [F x N]; h_dbg optional fp16 [T x F] dense copy of H.
+ * K % 64 == 0, F % 64 == 0, N % 16 == 0.                                     */
+size_t haq_ffn_workspace_bytes(int32_t T, int32_t K, int32_t F, int32_t N);
+int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int8_t* w1_packed, const float* w1_scale,
+                     int32_t act, const float* s2, const int8_t* w2_packed, const float* w2_scale, int32_t T,
+                     int32_t K, int32_t F, int32_t N, void* y_fp16, int64_t ldy, void* h_dbg_fp16, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Top-2 routed SwiGLU expert FFN with W8A8 experts.
  *
  * Per token t: top-2 experts by router logit (lowest index wins ties); gate

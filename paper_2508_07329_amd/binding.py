@@ -16,7 +16,8 @@ __all__ = [
     "HaqError", "lib", "haq_version", "haq_smooth_quant_act", "haq_channel_absmax_f16", "haq_weight_row_absmax",
     "haq_smoothing_vector", "haq_quant_weight", "haq_packed_bytes", "haq_pack_weight", "haq_pack_gate_up",
     "haq_linear_workspace_bytes", "haq_w8a8_linear", "haq_packed_act_rows", "haq_packed_act_bytes",
-    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
+    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ffn_workspace_bytes", "haq_w8a8_ffn",
+    "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
 ]
@@ -31,7 +32,8 @@ EXPORTED_SYMBOLS = [
     "haq_version", "haq_last_error", "haq_smooth_quant_act", "haq_channel_absmax_f16", "haq_weight_row_absmax",
     "haq_smoothing_vector", "haq_quant_weight", "haq_packed_bytes", "haq_pack_weight", "haq_pack_gate_up",
     "haq_linear_workspace_bytes", "haq_w8a8_linear", "haq_packed_act_rows", "haq_packed_act_bytes",
-    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ctx_create", "haq_ctx_destroy",
+    "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ffn_workspace_bytes", "haq_w8a8_ffn", "haq_ctx_create",
+    "haq_ctx_destroy",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
 ]
 
@@ -64,7 +66,8 @@ def lib() -> C.CDLL:
             build()
         L = C.CDLL(LIB_PATH)
         L.haq_last_error.restype = C.c_char_p
-        for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes"):
+        for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
+                  "haq_ffn_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -205,6 +208,25 @@ def haq_gemm_w8a8_packed(q_packed, row_scale, w_packed, w_scale, T: int, K: int,
     _check(lib().haq_gemm_w8a8_packed(_ptr(q_packed), _ptr(row_scale), _ptr(w_packed), _ptr(w_scale), T, K, N, act,
                                       _ptr(y), C.c_int64(y.stride(0)), None, _stream()))
     return y
+
+
+def haq_ffn_workspace_bytes(T: int, K: int, F: int, N: int) -> int:
+    return int(lib().haq_ffn_workspace_bytes(T, K, F, N))
+
+
+def haq_w8a8_ffn(x, s1, w1_packed, w1_scale, F: int, act: int, s2, w2_packed, w2_scale, N: int, *, out=None,
+                 workspace=None, debug: bool = False):
+    """x fp16 [T,K] -> y fp16 [T,N] through two chained W8A8 linears; debug=True also returns H fp16 [T,F]."""
+    T, K = x.shape
+    dev = x.device
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=dev)
+    if workspace is None:
+        workspace = _ws(haq_ffn_workspace_bytes(T, K, F, N), dev)
+    h = torch.empty((T, F), dtype=torch.float16, device=dev) if debug else None
+    _check(lib().haq_w8a8_ffn(_ptr(x), C.c_int64(x.stride(0)), _ptr(s1), _ptr(w1_packed), _ptr(w1_scale), act, _ptr(s2),
+                              _ptr(w2_packed), _ptr(w2_scale), T, K, F, N, _ptr(y), C.c_int64(y.stride(0)), _ptr(h),
+                              _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
+    return (y, h) if debug else y
 
 
 @dataclass

@@ -53,6 +53,25 @@ LinearWs carve_linear(void* ws, int T, int K) {
     return w;
 }
 
+struct FfnWs {
+    int8_t *q1, *q2;
+    float *sx1, *sx2;
+    __half* h;
+    size_t bytes;
+};
+FfnWs carve_ffn(void* ws, int T, int K, int F) {
+    Carver c(ws);
+    FfnWs w;
+    const int64_t R = padded_rows(T);
+    w.q1 = c.take<int8_t>((size_t)K * R);
+    w.q2 = c.take<int8_t>((size_t)F * R);
+    w.sx1 = c.take<float>((size_t)T);
+    w.sx2 = c.take<float>((size_t)T);
+    w.h = c.take<__half>((size_t)T * F);
+    w.bytes = c.off;
+    return w;
+}
+
 struct MoeWs {
     int32_t *idx, *counts, *offsets, *perm, *inv;
     float *gw, *sx, *sx_sorted, *sh;
@@ -188,6 +207,40 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
     if (rc != HAQ_OK) return rc;
     if (sx_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(sx_dbg, w.sx, (size_t)T * sizeof(float), hipMemcpyDeviceToDevice, st));
     return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, st);
+}
+
+size_t haq_ffn_workspace_bytes(int32_t T, int32_t K, int32_t F, int32_t N) {
+    (void)N;
+    if (T < 0 || K <= 0 || F <= 0) return 0;
+    return carve_ffn(nullptr, T, K, F).bytes;
+}
+
+int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int8_t* w1_packed, const float* w1_scale,
+                     int32_t act, const float* s2, const int8_t* w2_packed, const float* w2_scale, int32_t T, int32_t K,
+                     int32_t F, int32_t N, void* y_fp16, int64_t ldy, void* h_dbg_fp16, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    if (T < 0 || K <= 0 || F <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: T=%d K=%d F=%d N=%d", T, K, F, N);
+    if (K % 64 != 0 || F % 64 != 0 || N % 16 != 0 || K > 65536 || F > 65536)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_ffn: K=%d and F=%d must be multiples of 64 (<= 65536), N=%d of 16", K, F, N);
+    if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_ffn: act=%d", act);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !w1_packed || !w1_scale || !w2_packed || !w2_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: null buffer");
+    if (ldx < K || ldx % 8 != 0 || ldy < N || ldy % 8 != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: ldx=%lld ldy=%lld (multiples of 8)", (long long)ldx, (long long)ldy);
+    if (!aligned16(x_fp16) || !aligned16(w1_packed) || !aligned16(w2_packed) || !aligned16(y_fp16) || (s1 && !aligned16(s1)) ||
+        (s2 && !aligned16(s2)) || (h_dbg_fp16 && !aligned16(h_dbg_fp16)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: pointers must be 16-byte aligned");
+    const size_t need = carve_ffn(nullptr, T, K, F).bytes;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_w8a8_ffn: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const FfnWs w = carve_ffn(workspace, T, K, F);
+    __half* h = h_dbg_fp16 ? (__half*)h_dbg_fp16 : w.h;
+    int rc = quant_packed(x_fp16, ldx, s1, T, K, w.q1, w.sx1, nullptr, st);
+    if (rc != HAQ_OK) return rc;
+    if ((rc = gemm_packed(w.q1, w.sx1, w1_packed, w1_scale, T, K, F, act, h, F, nullptr, st)) != HAQ_OK) return rc;
+    if ((rc = quant_packed(h, F, s2, T, F, w.q2, w.sx2, nullptr, st)) != HAQ_OK) return rc;
+    return gemm_packed(w.q2, w.sx2, w2_packed, w2_scale, T, F, N, HAQ_ACT_NONE, y_fp16, ldy, nullptr, st);
 }
 
 int64_t haq_packed_act_rows(int32_t T) { return T < 0 ? 0 : padded_rows(T); }

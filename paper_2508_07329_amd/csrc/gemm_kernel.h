@@ -89,7 +89,7 @@ struct GemmShape {
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int STAGE_BYTES = (BM + BN) * 64;
-    static constexpr int SCALE_BYTES = (BM + BN) * 4;
+    static constexpr int SCALE_BYTES = (BM + BN) * 4;  // row scales and channel scales of the tile
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + SCALE_BYTES;
 };
 

@@ -105,6 +105,7 @@ struct QuantArgs {
     int n_sel;         // with tab: the experts whose row groups this launch covers
     int sel[32];
     int max_rows;      // with tab: upper bound of the rows of the selected groups (grid sizing)
+
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 

@@ -144,11 +144,35 @@ def test_ffn_opt67b_full_size_sampled_rows():
     w1p, w2p = haq.haq_pack_weight(dev(W1q)), haq.haq_pack_weight(dev(W2q))
     h = haq.haq_w8a8_linear(dev(X), dev(s1), w1p, dev(sw1), wl.F, haq.HAQ_ACT_RELU)
     y = haq.haq_w8a8_linear(h, dev(s2), w2p, dev(sw2), wl.H, haq.HAQ_ACT_NONE)
+    yf, hf = haq.haq_w8a8_ffn(dev(X), dev(s1), w1p, dev(sw1), wl.F, haq.HAQ_ACT_RELU, dev(s2), w2p, dev(sw2), wl.H, debug=True)
+    assert bits_equal(host(hf), host(h)) and bits_equal(host(yf), host(y))
     h_ref = oracle.w8a8_linear(X[rows], s1, W1q, sw1, "relu")
     y_ref = oracle.w8a8_linear(h_ref, s2, W2q, sw2, "none")
     assert bits_equal(host(h)[rows], h_ref)
     assert fp16_close(host(y)[rows], y_ref)
     assert bits_equal(host(y)[rows], y_ref)
+
+
+@pytest.mark.parametrize("T,K,F,N,act", [(300, 256, 1088, 272, "relu"), (1, 64, 64, 16, "none"), (513, 832, 768, 1040, "relu")])
+def test_fused_ffn_equals_oracle_chain(T, K, F, N, act):
+    X, _, _ = hi.hidden_states(T + F, T, K, n_outlier=3)
+    W1, W2 = hi.gaussian_weight(T + F, 0, K, F), hi.gaussian_weight(T + F, 1, F, N)
+    if act == "none":  # the offline helper calibrates the second layer on a ReLU intermediate: do it by hand here
+        s1, W1q, sw1 = offline.quantize_linear(X, W1)
+        s2, W2q, sw2 = offline.quantize_linear(oracle.w8a8_linear(X, s1, W1q, sw1, act), W2)
+    else:
+        (s1, W1q, sw1), (s2, W2q, sw2) = offline.quantize_ffn(X, W1, W2)
+    h_ref = oracle.w8a8_linear(X, s1, W1q, sw1, act)
+    y_ref = oracle.w8a8_linear(h_ref, s2, W2q, sw2, "none")
+    y, h = haq.haq_w8a8_ffn(dev(X), dev(s1), haq.haq_pack_weight(dev(W1q)), dev(sw1), F, oracle.ACT[act], dev(s2),
+                            haq.haq_pack_weight(dev(W2q)), dev(sw2), N, debug=True)
+    assert bits_equal(host(h), h_ref), diff_report(host(h), h_ref)
+    assert fp16_close(host(y), y_ref)
+    assert bits_equal(host(y), y_ref), diff_report(host(y), y_ref)
+    y2 = haq.haq_w8a8_ffn(dev(X), dev(s1), haq.haq_pack_weight(dev(W1q)), dev(sw1), F, oracle.ACT[act], None,
+                          haq.haq_pack_weight(dev(oracle.quant_weight(W2, None)[0])), dev(oracle.quant_weight(W2, None)[1]), N)
+    y2_ref = oracle.w8a8_linear(h_ref, None, *oracle.quant_weight(W2, None), "none")
+    assert bits_equal(host(y2), y2_ref)
 
 
 # ------------------------------------------------------------------ MoE, small shapes, everything compared
