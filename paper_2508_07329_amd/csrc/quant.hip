@@ -60,6 +60,7 @@ __device__ __forceinline__ bool load_s16(const float* s, int c, float (&sv)[16],
     return fast;
 }
 
+// Two-pass kernel for rows longer than 16 * QMAX_THREADS channels.
 // Work-group = 8 consecutive output rows of one expert group (or of the matrix).  Threads
 // form G row groups x CL chunk lanes: thread (g, c) owns the 16-channel chunks c, c + CL, ...
 // of RS = 8 / G rows, so the reciprocals of the smoothing vector are formed once per chunk
@@ -205,6 +206,164 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_kernel(QuantArgs a,
     }
 }
 
+// Single-pass kernel for K <= 16 * QMAX_THREADS: thread (g, c) owns exactly one 16-channel
+// chunk of RS rows and keeps the raw halves in registers between the absmax reduction and
+// the rounding, so every row is read from memory once.
+//
+// Rounding in the common case: q = y / scale satisfies |q| <= 127 (1 + 2^-23) because
+// |y| <= absmax and scale = RN(absmax / 127) is a normal number, so RN-to-integer never
+// leaves [-127, 127] and the clamp of Eq. 1 is a no-op; adding 1.5 * 2^23 rounds q to an
+// integer (ties to even, like rint) and leaves its two's-complement low byte in the low
+// byte of the sum, which byte permutes gather four at a time.
+__device__ __forceinline__ uint32_t round_pack4(float q0, float q1, float q2, float q3) {
+    const uint32_t b0 = __float_as_uint(q0 + 12582912.0f), b1 = __float_as_uint(q1 + 12582912.0f);
+    const uint32_t b2 = __float_as_uint(q2 + 12582912.0f), b3 = __float_as_uint(q3 + 12582912.0f);
+    const uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(b3, b2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+template <int RS>
+__global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_reg_kernel(QuantArgs a, int CL) {
+    __shared__ float red[QMAX_THREADS / 64][RS];
+    const int tid = threadIdx.x;
+    const int c = tid % CL, g = tid / CL;
+    const int brows = (blockDim.x / CL) * RS;  // rows per work-group
+    const int waves_per_group = CL >> 6, wave = tid >> 6;
+    const int nchunk = a.K / 16;
+    int row0, row_end;
+    const float* s = a.s;
+    if (a.tab) {
+        int b = blockIdx.x, i = 0, e = 0;
+        row0 = row_end = 0;
+        for (; i < a.n_sel; ++i) {
+            e = a.sel[i];
+            const int lo = a.offsets[e], hi = a.offsets[e + 1];
+            const int nb = (hi - lo + brows - 1) / brows;
+            if (b < nb) {
+                row0 = lo + b * brows;
+                row_end = hi;
+                break;
+            }
+            b -= nb;
+        }
+        if (i == a.n_sel) return;  // the grid is an upper bound
+        s = a.tab[e].s_mid;
+    } else {
+        row0 = blockIdx.x * brows;
+        row_end = a.T;
+    }
+    row0 += g * RS;
+    const int nrow = min(RS, row_end - row0);  // may be <= 0
+    const bool active = c < nchunk;
+    uint4 raw[RS][2];
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        raw[r][0] = raw[r][1] = make_uint4(0, 0, 0, 0);
+        if (active && r < nrow) {
+            int src = row0 + r;
+            if (a.gather) src = a.gather[src] >> 1;
+            const uint4* px = reinterpret_cast<const uint4*>(a.x + (size_t)src * a.ldx + c * 16);
+            raw[r][0] = px[0];
+            raw[r][1] = px[1];
+        }
+    }
+    float sv[16], rv[16];
+    bool fast = true;
+    if (s && active) fast = load_s16(s, c, sv, rv);
+    auto unpack = [&](int r, float (&x)[16]) {
+        Half8 h0, h1;
+        *reinterpret_cast<uint4*>(&h0) = raw[r][0];
+        *reinterpret_cast<uint4*>(&h1) = raw[r][1];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            x[i] = h2f(h0.v[i]);
+            x[8 + i] = h2f(h1.v[i]);
+        }
+    };
+    float amax[RS];
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        float m = 0.0f;
+        unpack(r, x);
+        if (!s) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i]));
+        } else if (fast) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(div_by(x[i], sv[i], rv[i], true)));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i] / sv[i]));
+        }
+        amax[r] = m;
+    }
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) amax[r] = fmaxf(amax[r], __shfl_xor(amax[r], o));
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) red[wave][r] = amax[r];
+    }
+    __syncthreads();
+    if (!active) return;
+    // the rounding pass recomputes x / s from the raw halves; the empty asm keeps the
+    // compiler from carrying the 16 * RS quotients of the first pass across the barrier
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            asm volatile("" : "+v"(raw[r][h].x), "+v"(raw[r][h].y), "+v"(raw[r][h].z), "+v"(raw[r][h].w));
+    }
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        if (r < nrow) {
+            // every thread of the row group derives the row's scale from the per-wave maxima
+            float m = 0.0f;
+            for (int w = 0; w < waves_per_group; ++w) m = fmaxf(m, red[g * waves_per_group + w][r]);
+            const float scale = m / 127.0f;
+            const float rscale = 1.0f / scale;
+            const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+            const int t = row0 + r;
+            if (c == r) {
+                if (a.scale_dest) a.scale_dest[t] = scale;
+                if (a.scale) a.scale[a.gather ? (a.gather[t] >> 1) : t] = scale;
+            }
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (m != 0.0f) {
+                unpack(r, x);
+                if (fast && sfast) {  // the common case: both divisions through reciprocals
+                    float q[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float y = s ? div_by(x[i], sv[i], rv[i], true) : x[i];
+                        q[i] = div_by(y, scale, rscale, true);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float y = s ? x[i] / sv[i] : x[i];
+                        float q = rintf(y / scale);
+                        q = fminf(fmaxf(q, -127.0f), 127.0f);
+                        w[i / 4] |= (uint32_t)((int)q & 0xff) << (8 * (i % 4));
+                    }
+                }
+            }
+            const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+            if (a.q_rm) {
+                const int tr = a.gather ? (a.gather[t] >> 1) : t;
+                *reinterpret_cast<uint4*>(a.q_rm + (size_t)tr * a.ldq + c * 16) = v;
+            }
+            if (a.q_cm) *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + t) * 16) = v;
+        }
+    }
+}
+
 // ---- offline: per-channel magnitudes ----------------------------------------
 __global__ void channel_absmax_f16_kernel(const __half* x, int64_t ldx, int T, int K, float* ax) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -298,6 +457,19 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     const int threads = CL * G;
     // with per-expert groups every group may end in a partial block: T/8 + E is an upper bound
     const int blocks = a.tab ? a.max_rows / QBLOCK_ROWS + a.n_sel : cdiv(a.T, QBLOCK_ROWS);
+    if (nchunk <= CL) {
+        // one chunk per thread: the register-resident single pass, at most 4 rows per thread
+        const int RS = QBLOCK_ROWS / G > 4 ? 4 : QBLOCK_ROWS / G;
+        const int brows = RS * G;
+        const int nb = a.tab ? a.max_rows / brows + a.n_sel : cdiv(a.T, brows);
+        switch (RS) {
+            case 4: hipLaunchKernelGGL(smooth_quant_reg_kernel<4>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+            case 2: hipLaunchKernelGGL(smooth_quant_reg_kernel<2>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+            default: hipLaunchKernelGGL(smooth_quant_reg_kernel<1>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+        }
+        HAQ_CHECK_HIP(hipGetLastError());
+        return HAQ_OK;
+    }
     switch (QBLOCK_ROWS / G) {
         case 8: hipLaunchKernelGGL(smooth_quant_kernel<8>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
         case 4: hipLaunchKernelGGL(smooth_quant_kernel<4>, dim3(blocks), dim3(threads), 0, st, a, CL); break;

@@ -28,7 +28,7 @@ def _need_gpu():
 
 # ------------------------------------------------------------------ A1
 @pytest.mark.parametrize("T,K,with_s", [(16, 768, True), (2048, 4096, True), (37, 14336, True), (1, 64, False),
-                                         (9, 16384, True), (300, 832, False)])
+                                         (9, 16384, True), (300, 832, False), (11, 32768, True), (3, 65536, False)])
 def test_smooth_quant_act_bit_exact(T, K, with_s):
     X, _, _ = hi.hidden_states(100 + T, T, K, n_outlier=max(1, K // 200))
     if T > 4:
@@ -38,6 +38,26 @@ def test_smooth_quant_act_bit_exact(T, K, with_s):
     q, sx = haq.haq_smooth_quant_act(dev(X), None if s is None else dev(s))
     assert bits_equal(host(sx), sx_ref)
     assert bits_equal(host(q), q_ref)
+
+
+def test_smooth_quant_act_divisors_outside_reciprocal_range():
+    """Smoothing entries and row scales beyond the range in which the kernel divides through
+    reciprocals: those chunks and rows must take true divisions and still match bit for bit."""
+    T, K = 21, 1024
+    X, _, _ = hi.hidden_states(77, T, K, n_outlier=5)
+    rng = np.random.default_rng(78)
+    s = np.exp(rng.normal(0, 1, K)).astype(F32)
+    s[rng.integers(0, K, 40)] = F32(1e-20)
+    s[rng.integers(0, K, 40)] = F32(1e20)
+    X[5] = np.float16(6e-8)  # subnormal halves: a tiny row scale
+    X[6, :] = 0
+    X[6, 17] = np.float16(-3.0)
+    for sv in (s, np.full(K, 1e25, F32), np.full(K, 1e-13, F32)):
+        q_ref, sx_ref = oracle.smooth_quant_act(X, sv)
+        assert np.isfinite(sx_ref).all()
+        q, sx = haq.haq_smooth_quant_act(dev(X), dev(sv))
+        assert bits_equal(host(sx), sx_ref)
+        assert bits_equal(host(q), q_ref)
 
 
 def test_smooth_quant_act_strided_input_and_empty():
