@@ -76,6 +76,7 @@ struct MoeWs {
     int32_t *idx, *counts, *offsets, *perm, *inv;
     float *gw, *sx, *sx_sorted, *sh;
     ExpertTab* tab;
+    int32_t* blk_counts;
     int8_t *q_cm, *hq_cm;
     __half *mid, *y;
     float* pmax;
@@ -97,6 +98,7 @@ MoeWs carve_moe(void* ws, int T, int H, int I, int E) {
     w.sx_sorted = c.take<float>(P);
     w.sh = c.take<float>(P);
     w.tab = c.take<ExpertTab>(E);
+    w.blk_counts = c.take<int32_t>((size_t)route_blocks(T) * E + 1);
     w.q_cm = c.take<int8_t>((size_t)H * w.R);
     w.hq_cm = c.take<int8_t>((size_t)I * w.R);
     w.mid = c.take<__half>(P * (size_t)I);
@@ -378,7 +380,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
 
     int rc;
     if ((rc = launch_route_permute((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv,
-                                   st)) != HAQ_OK)
+                                   w.blk_counts, st)) != HAQ_OK)
         return rc;
 
     QuantArgs qa{};

@@ -38,6 +38,11 @@ struct TileCoord {
 // undo that so that each XCD (one L2) owns a contiguous range of tile ids, M fastest:
 // neighbouring work-groups of an XCD share weight tiles and the activation tiles stay in
 // its L2.  The grid is a multiple of 8 and at least the tile count.
+#ifndef HAQ_TILE_BAND
+#define HAQ_TILE_BAND 8
+#endif
+constexpr int TILE_BAND = HAQ_TILE_BAND;
+
 template <int BM, int BN>
 __device__ __forceinline__ TileCoord decode_tile(const GemmArgs& a) {
     TileCoord tc;
@@ -60,8 +65,14 @@ __device__ __forceinline__ TileCoord decode_tile(const GemmArgs& a) {
     if (slot >= per) return tc;
     const int id = xcd * per + slot;
     if (id >= total) return tc;
-    int mi = id % total_mt;
-    tc.n0 = (id / total_mt) * BN;
+    // bands of TILE_BAND row tiles, channel tiles inside a band, rows fastest: the
+    // work-groups resident on one XCD at a time then form a compact block of the tile grid
+    // (a row tile's activations and a channel tile's weights are each shared by ~8 of them
+    // in L2) instead of one channel tile across every row tile of every expert
+    const int band = id / (TILE_BAND * ntn), rem = id % (TILE_BAND * ntn);
+    const int band_rows = min(TILE_BAND, total_mt - band * TILE_BAND);
+    int mi = band * TILE_BAND + rem % band_rows;
+    tc.n0 = (rem / band_rows) * BN;
     if (!a.offsets) {
         tc.m0 = mi * BM;
         tc.m_end = a.M;

@@ -5,7 +5,10 @@
 namespace haq {
 int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
                          int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                         hipStream_t st);
+                         int32_t* blk_counts, hipStream_t st);
+// work-groups of the multi-work-group routing path for T tokens (0: the single work-group
+// kernel is used); blk_counts holds route_blocks(T) * E entries
+int route_blocks(int T);
 int launch_combine(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H, __half* out,
                    int64_t ldo, hipStream_t st);
 }  // namespace haq

@@ -50,6 +50,7 @@ struct TabAll {
 // ranks inside an expert follow pair id), and it drops the expert table into device memory
 // for the kernels that follow.
 constexpr int PERM_THREADS = 256;
+constexpr int ROUTE_SINGLE_MAX = 256;  // longer batches take the multi-work-group kernels
 __global__ __launch_bounds__(PERM_THREADS) void route_permute_kernel(const __half* logits, int64_t ldl, int T, int E,
                                                                      TabAll tab, ExpertTab* tab_dev, int32_t* idx,
                                                                      float* gw, int32_t* counts, int32_t* offsets,
@@ -113,6 +114,91 @@ __global__ __launch_bounds__(PERM_THREADS) void route_permute_kernel(const __hal
     }
 }
 
+
+// ---- the same result with many work-groups (long token batches) -------------------------
+// Kernel 1: one thread per token routes it; the work-group leaves its expert histogram.
+// Kernel 2: every work-group sums the histograms of the work-groups before it (that is the
+// rank base of its pairs inside each expert), ranks its own pairs with wave ballots -- a
+// token holds at most one pair per expert, so the rank of a pair among equal experts is the
+// number of earlier tokens that use that expert -- and scatters perm / inv.
+constexpr int RT_THREADS = 256;
+__global__ __launch_bounds__(RT_THREADS) void route_count_kernel(const __half* logits, int64_t ldl, int T, int E,
+                                                                 int32_t* idx, float* gw, int32_t* blk_counts) {
+    __shared__ int32_t hist[32];
+    const int tid = threadIdx.x, t = blockIdx.x * RT_THREADS + tid;
+    if (tid < 32) hist[tid] = 0;
+    __syncthreads();
+    if (t < T) {
+        int32_t id2[2];
+        float g2[2];
+        route_token(logits + (size_t)t * ldl, E, id2, g2);
+        idx[2 * t] = id2[0];
+        idx[2 * t + 1] = id2[1];
+        gw[2 * t] = g2[0];
+        gw[2 * t + 1] = g2[1];
+        atomicAdd(&hist[id2[0]], 1);  // integer counts: the order of the additions is immaterial
+        atomicAdd(&hist[id2[1]], 1);
+    }
+    __syncthreads();
+    if (tid < E) blk_counts[blockIdx.x * E + tid] = hist[tid];
+}
+
+__global__ __launch_bounds__(RT_THREADS) void permute_kernel(int T, int E, TabAll tab, ExpertTab* tab_dev,
+                                                             const int32_t* idx, const int32_t* blk_counts, int nblk,
+                                                             int32_t* counts, int32_t* offsets, int32_t* perm,
+                                                             int32_t* inv) {
+    __shared__ int32_t total[32], before[32], base[32];
+    __shared__ int32_t wave_cnt[RT_THREADS / 64][32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < E) {
+        int bef = 0, tot = 0;
+        for (int b = 0; b < nblk; ++b) {
+            const int c = blk_counts[b * E + tid];
+            if (b < (int)blockIdx.x) bef += c;
+            tot += c;
+        }
+        total[tid] = tot;
+        before[tid] = bef;
+        if (blockIdx.x == 0) {
+            tab_dev[tid] = tab.e[tid];
+            counts[tid] = tot;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            base[e] = run + before[e];
+            if (blockIdx.x == 0) offsets[e] = run;
+            run += total[e];
+        }
+        if (blockIdx.x == 0) offsets[E] = run;
+    }
+    const int t = blockIdx.x * RT_THREADS + tid;
+    const bool valid = t < T;
+    const int e0 = valid ? idx[2 * t] : -1, e1 = valid ? idx[2 * t + 1] : -1;
+    int r0 = 0, r1 = 0;
+    for (int e = 0; e < E; ++e) {
+        const unsigned long long mask = __ballot(e0 == e || e1 == e);
+        const int below = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
+        if (e0 == e) r0 = below;
+        if (e1 == e) r1 = below;
+    }
+    __syncthreads();
+    if (valid) {
+        for (int w = 0; w < wave; ++w) {
+            r0 += wave_cnt[w][e0];
+            r1 += wave_cnt[w][e1];
+        }
+        const int p0 = base[e0] + r0, p1 = base[e1] + r1;
+        perm[p0] = 2 * t;
+        inv[2 * t] = p0;
+        perm[p1] = 2 * t + 1;
+        inv[2 * t + 1] = p1;
+    }
+}
+
 // out[t] = fp16(g0 * y[inv[2t]] + g1 * y[inv[2t+1]]), 8 channels per thread.
 __global__ void combine_kernel(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H,
                                __half* out, int64_t ldo) {
@@ -139,11 +225,20 @@ __global__ void combine_kernel(const __half* y, int64_t ldy, const int32_t* inv,
 
 }  // namespace
 
+int route_blocks(int T) { return T > ROUTE_SINGLE_MAX ? cdiv(T, RT_THREADS) : 0; }
+
 int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
                          int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                         hipStream_t st) {
+                         int32_t* blk_counts, hipStream_t st) {
     TabAll tab{};
     for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
+    if (const int nblk = route_blocks(T)) {
+        hipLaunchKernelGGL(route_count_kernel, dim3(nblk), dim3(RT_THREADS), 0, st, logits, ldl, T, E, idx, gw, blk_counts);
+        hipLaunchKernelGGL(permute_kernel, dim3(nblk), dim3(RT_THREADS), 0, st, T, E, tab, tab_dev, (const int32_t*)idx,
+                           (const int32_t*)blk_counts, nblk, counts, offsets, perm, inv);
+        HAQ_CHECK_HIP(hipGetLastError());
+        return HAQ_OK;
+    }
     const size_t sm = ((size_t)E * PERM_THREADS + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(route_permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, logits, ldl, T, E, tab, tab_dev, idx, gw,
                        counts, offsets, perm, inv);

@@ -228,7 +228,7 @@ def _check_moe(m, dev_experts=None, tokens=None, ctx=None):
 
 
 @pytest.mark.parametrize("T,H,I,E", [(37, 128, 320, 8), (1, 128, 192, 8), (300, 256, 576, 8), (9, 128, 192, 2),
-                                      (530, 192, 448, 4)])
+                                      (530, 192, 448, 4), (257, 128, 192, 8), (700, 128, 192, 32)])
 def test_moe_small_everything_bit_exact(T, H, I, E):
     _check_moe(offline.small_moe(seed=20 + T, T=T, H=H, I=I, E=E))
 
