@@ -2,6 +2,8 @@
 // the offline weight-side kernels (Q(W s), per-channel magnitudes, packing).
 #include "haq_common.h"
 
+#include <mutex>
+
 namespace haq {
 
 namespace {
@@ -364,6 +366,209 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_reg_kernel(QuantArg
     }
 }
 
+#define QWAIT_VMCNT0() __builtin_amdgcn_s_waitcnt((0 & 0xF) | ((0 >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+#define QWAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
+#define QCFENCE() asm volatile("" ::: "memory")
+
+// Pipelined single pass for K <= 16 * QMAX_THREADS.  Thread (g, c) owns one 16-channel chunk
+// (reciprocals of the smoothing vector formed once per work-group) and walks over `nit` slabs
+// of RS rows per row group.  The halves of the next slab travel global -> LDS (16 B per lane,
+// no registers) while the current slab is reduced and rounded; a thread only ever reads back
+// the LDS slots its own wave's loads filled, so the only barrier is the one of the row
+// maximum.  Every row is read from memory once.
+template <int RS>
+__global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArgs a, int CL, int nit) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t qlds[];
+    const int nthr = blockDim.x;
+    float* red = reinterpret_cast<float*>(qlds + (size_t)2 * RS * 2 * nthr * 16);  // [2][QMAX_THREADS / 64][RS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = tid % CL, g = tid / CL;
+    const int G = nthr / CL;
+    const int waves_per_group = CL >> 6;
+    const int nchunk = a.K / 16;
+    const int slab = G * RS, brows = slab * nit;
+    int row0, row_end;
+    const float* s = a.s;
+    if (a.tab) {
+        int b = blockIdx.x, i = 0, e = 0;
+        row0 = row_end = 0;
+        for (; i < a.n_sel; ++i) {
+            e = a.sel[i];
+            const int lo = a.offsets[e], hi = a.offsets[e + 1];
+            const int nb = (hi - lo + brows - 1) / brows;
+            if (b < nb) {
+                row0 = lo + b * brows;
+                row_end = hi;
+                break;
+            }
+            b -= nb;
+        }
+        if (i == a.n_sel) return;  // the grid is an upper bound
+        s = a.tab[e].s_mid;
+    } else {
+        row0 = blockIdx.x * brows;
+        row_end = a.T;
+    }
+    const bool active = c < nchunk;
+    float sv[16], rv[16];
+    bool fast = true;
+    if (s && active) fast = load_s16(s, c, sv, rv);
+
+    // source row of slab `it`, row r of this thread (-1: none)
+    auto source = [&](int it, int (&src)[RS]) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            const int row = row0 + it * slab + g * RS + r;
+            src[r] = -1;
+            if (active && it < nit && row < row_end) src[r] = a.gather ? (a.gather[row] >> 1) : row;
+        }
+    };
+    auto issue = [&](int buf, const int (&src)[RS]) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            if (src[r] >= 0) {
+                const __half* p = a.x + (size_t)src[r] * a.ldx + c * 16;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(uintptr_t)(p + 8 * h),
+                        (__attribute__((address_space(3))) void*)(qlds + ((size_t)((buf * RS + r) * 2 + h) * nthr + wave * 64) * 16),
+                        16, 0, 0);
+            }
+        }
+    };
+    int src[RS], src_nxt[RS];
+    source(0, src);
+    issue(0, src);
+    source(1, src_nxt);
+    QWAIT_VMCNT0();  // slab 0 is in LDS
+    QCFENCE();
+    float x[16];
+    for (int it = 0; it < nit; ++it) {
+        const int base = row0 + it * slab;
+        if (base >= row_end) break;  // uniform over the work-group
+        uint4 raw[RS][2];
+#pragma unroll
+        for (int r = 0; r < RS; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                raw[r][h] = *reinterpret_cast<const uint4*>(qlds + ((size_t)(((it & 1) * RS + r) * 2 + h) * nthr + tid) * 16);
+        issue((it + 1) & 1, src_nxt);  // lands while this slab is reduced and rounded
+        int src_cur[RS];
+#pragma unroll
+        for (int r = 0; r < RS; ++r) src_cur[r] = src[r];
+#pragma unroll
+        for (int r = 0; r < RS; ++r) src[r] = src_nxt[r];
+        source(it + 2, src_nxt);
+        auto unpack = [&](int r) {
+            Half8 h0, h1;
+            *reinterpret_cast<uint4*>(&h0) = raw[r][0];
+            *reinterpret_cast<uint4*>(&h1) = raw[r][1];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                x[i] = h2f(h0.v[i]);
+                x[8 + i] = h2f(h1.v[i]);
+            }
+        };
+        float amax[RS];
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            float m = 0.0f;
+            if (src_cur[r] >= 0) {
+                unpack(r);
+                if (!s) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i]));
+                } else if (fast) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(div_by(x[i], sv[i], rv[i], true)));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i] / sv[i]));
+                }
+            }
+            amax[r] = m;
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) amax[r] = fmaxf(amax[r], __shfl_xor(amax[r], o));
+        }
+        float* redp = red + (size_t)(it & 1) * (QMAX_THREADS / 64) * RS;
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < RS; ++r) redp[wave * RS + r] = amax[r];
+        }
+        QWAIT_LGKM0();
+        QCFENCE();
+        __builtin_amdgcn_s_barrier();
+        QCFENCE();
+        // the rounding pass recomputes x / s from the raw halves; the empty asm keeps the
+        // compiler from carrying the quotients of the first pass across the barrier
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                asm volatile("" : "+v"(raw[r][h].x), "+v"(raw[r][h].y), "+v"(raw[r][h].z), "+v"(raw[r][h].w));
+        }
+        uint4 code[RS];
+        float scale[RS];
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            uint32_t w[4] = {0, 0, 0, 0};
+            scale[r] = 0.0f;
+            if (src_cur[r] >= 0) {
+                float m = 0.0f;
+                for (int w2 = 0; w2 < waves_per_group; ++w2) m = fmaxf(m, redp[(g * waves_per_group + w2) * RS + r]);
+                scale[r] = m / 127.0f;
+                const float rscale = 1.0f / scale[r];
+                const bool sfast = scale[r] >= 0x1p-100f && scale[r] <= 0x1p100f;
+                if (m != 0.0f) {
+                    unpack(r);
+                    if (fast && sfast) {  // the common case: both divisions through reciprocals
+                        float q[16];
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float y = s ? div_by(x[i], sv[i], rv[i], true) : x[i];
+                            q[i] = div_by(y, scale[r], rscale, true);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float y = s ? x[i] / sv[i] : x[i];
+                            float q = rintf(y / scale[r]);
+                            q = fminf(fmaxf(q, -127.0f), 127.0f);
+                            w[i / 4] |= (uint32_t)((int)q & 0xff) << (8 * (i % 4));
+                        }
+                    }
+                }
+            }
+            code[r] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        // the next slab has had the whole arithmetic phase to arrive, and the stores of the
+        // previous slab are long acknowledged: this wait costs nothing, and the stores below
+        // are not waited for until one slab later
+        QWAIT_VMCNT0();
+        QCFENCE();
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            if (src_cur[r] >= 0) {
+                const int t = base + g * RS + r;
+                if (c == r) {
+                    if (a.scale_dest) a.scale_dest[t] = scale[r];
+                    if (a.scale) a.scale[src_cur[r]] = scale[r];
+                }
+                if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)src_cur[r] * a.ldq + c * 16) = code[r];
+                if (a.q_cm) *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + t) * 16) = code[r];
+            }
+        }
+    }
+    QWAIT_VMCNT0();  // nothing may still be writing LDS when the work-group retires
+}
+
 // ---- offline: per-channel magnitudes ----------------------------------------
 __global__ void channel_absmax_f16_kernel(const __half* x, int64_t ldx, int T, int K, float* ax) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -458,7 +663,29 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     // with per-expert groups every group may end in a partial block: T/8 + E is an upper bound
     const int blocks = a.tab ? a.max_rows / QBLOCK_ROWS + a.n_sel : cdiv(a.T, QBLOCK_ROWS);
     if (nchunk <= CL) {
-        // one chunk per thread: the register-resident single pass, at most 4 rows per thread
+        // one chunk per thread.  With enough rows to give every CU several slabs, the
+        // pipelined kernel (2 rows per row group per slab, next slab in flight through LDS)
+        constexpr int LRS = 2;
+        const int rows = a.tab ? a.max_rows : a.T;
+        int nit = rows / (LRS * G * 256);
+        if (nit > 16) nit = 16;
+        if (nit >= 4) {
+            const int brows = LRS * G * nit;
+            const int nb = a.tab ? a.max_rows / brows + a.n_sel : cdiv(a.T, brows);
+            const size_t lds = (size_t)2 * LRS * 2 * threads * 16 + 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
+            static std::once_flag once;
+            static hipError_t attr_err = hipSuccess;
+            std::call_once(once, [&] {
+                attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               2 * LRS * 2 * QMAX_THREADS * 16 + 2 * (QMAX_THREADS / 64) * LRS * (int)sizeof(float));
+            });
+            HAQ_CHECK_HIP(attr_err);
+            hipLaunchKernelGGL(smooth_quant_lds_kernel<LRS>, dim3(nb), dim3(threads), lds, st, a, CL, nit);
+            HAQ_CHECK_HIP(hipGetLastError());
+            return HAQ_OK;
+        }
+        // otherwise the register-resident single pass, at most 4 rows per thread
         const int RS = QBLOCK_ROWS / G > 4 ? 4 : QBLOCK_ROWS / G;
         const int brows = RS * G;
         const int nb = a.tab ? a.max_rows / brows + a.n_sel : cdiv(a.T, brows);

@@ -28,7 +28,8 @@ def _need_gpu():
 
 # ------------------------------------------------------------------ A1
 @pytest.mark.parametrize("T,K,with_s", [(16, 768, True), (2048, 4096, True), (37, 14336, True), (1, 64, False),
-                                         (9, 16384, True), (300, 832, False), (11, 32768, True), (3, 65536, False)])
+                                         (9, 16384, True), (300, 832, False), (11, 32768, True), (3, 65536, False),
+                                         (2101, 16384, True), (8203, 4096, True), (16390, 832, False)])
 def test_smooth_quant_act_bit_exact(T, K, with_s):
     X, _, _ = hi.hidden_states(100 + T, T, K, n_outlier=max(1, K // 200))
     if T > 4:
