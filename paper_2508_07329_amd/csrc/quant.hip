@@ -371,13 +371,13 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_reg_kernel(QuantArg
 #define QCFENCE() asm volatile("" ::: "memory")
 
 // Pipelined single pass for K <= 16 * QMAX_THREADS.  Thread (g, c) owns one 16-channel chunk
-// (reciprocals of the smoothing vector formed once per work-group) and walks over `nit` slabs
-// of RS rows per row group.  The halves of the next slab travel global -> LDS (16 B per lane,
+// (reciprocals of the smoothing vector formed once per work-group) and walks over a run of
+// slabs of RS rows per row group.  The halves of the next slab travel global -> LDS (16 B per lane,
 // no registers) while the current slab is reduced and rounded; a thread only ever reads back
 // the LDS slots its own wave's loads filled, so the only barrier is the one of the row
 // maximum.  Every row is read from memory once.
 template <int RS>
-__global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArgs a, int CL, int nit) {
+__global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArgs a, int CL) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t qlds[];
     const int nthr = blockDim.x;
     float* red = reinterpret_cast<float*>(qlds + (size_t)2 * RS * 2 * nthr * 16);  // [2][QMAX_THREADS / 64][RS]
@@ -387,7 +387,24 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
     const int G = nthr / CL;
     const int waves_per_group = CL >> 6;
     const int nchunk = a.K / 16;
-    const int slab = G * RS, brows = slab * nit;
+    const int slab = G * RS;
+    // Slabs per work-group: the grid is fixed (one work-group per CU); every group (expert)
+    // is cut into runs of `nit` slabs, so no work-group does more than nit slabs whatever the
+    // group sizes are, and sum_e ceil(slabs_e / nit) <= total / nit + groups <= grid.
+    int nit;
+    if (a.tab) {
+        int total = 0;
+        for (int i = 0; i < a.n_sel; ++i) {
+            const int e = a.sel[i];
+            total += (a.offsets[e + 1] - a.offsets[e] + slab - 1) / slab;
+        }
+        const int avail = max(1, (int)gridDim.x - a.n_sel);
+        nit = max(1, (total + avail - 1) / avail);
+    } else {
+        const int total = (a.T + slab - 1) / slab;
+        nit = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    }
+    const int brows = slab * nit;
     int row0, row_end;
     const float* s = a.s;
     if (a.tab) {
@@ -664,14 +681,18 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     const int blocks = a.tab ? a.max_rows / QBLOCK_ROWS + a.n_sel : cdiv(a.T, QBLOCK_ROWS);
     if (nchunk <= CL) {
         // one chunk per thread.  With enough rows to give every CU several slabs, the
-        // pipelined kernel (2 rows per row group per slab, next slab in flight through LDS)
+        // pipelined kernel (2 rows per row group per slab, next slab in flight through LDS),
+        // one work-group per CU
         constexpr int LRS = 2;
         const int rows = a.tab ? a.max_rows : a.T;
-        int nit = rows / (LRS * G * 256);
-        if (nit > 16) nit = 16;
-        if (nit >= 4) {
-            const int brows = LRS * G * nit;
-            const int nb = a.tab ? a.max_rows / brows + a.n_sel : cdiv(a.T, brows);
+        static int n_cu = 0;
+        if (n_cu == 0) {
+            int devid = 0, v = 0;
+            HAQ_CHECK_HIP(hipGetDevice(&devid));
+            HAQ_CHECK_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, devid));
+            n_cu = v > 64 ? v : 256;
+        }
+        if (rows / (LRS * G) >= 4 * n_cu) {
             const size_t lds = (size_t)2 * LRS * 2 * threads * 16 + 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
             static std::once_flag once;
             static hipError_t attr_err = hipSuccess;
@@ -681,7 +702,7 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
                                                2 * LRS * 2 * QMAX_THREADS * 16 + 2 * (QMAX_THREADS / 64) * LRS * (int)sizeof(float));
             });
             HAQ_CHECK_HIP(attr_err);
-            hipLaunchKernelGGL(smooth_quant_lds_kernel<LRS>, dim3(nb), dim3(threads), lds, st, a, CL, nit);
+            hipLaunchKernelGGL(smooth_quant_lds_kernel<LRS>, dim3(n_cu), dim3(threads), lds, st, a, CL);
             HAQ_CHECK_HIP(hipGetLastError());
             return HAQ_OK;
         }
