@@ -29,11 +29,13 @@ constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave
 constexpr int DN_DEPTH = 14;
 
 // ---- gate / up projections + SwiGLU + per-unit row maxima of h / s_mid ---------------
-// Rows [32*rb, 32*rb + 32) of every expert; experts with fewer rows leave at once.
-__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a, int rb) {
+// Work-group (unit, e, rb) handles rows [32*rb, 32*rb + 32) of expert e; row blocks past the
+// expert's rows leave at once (rb is the slowest grid dimension, so those empty work-groups
+// come after all the streaming ones instead of taking slots between them).
+__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
     __shared__ int part[GU_WAVES][2][16][64];
     __shared__ float wmax[GU_WAVES][32];
-    const int e = blockIdx.y, unit = blockIdx.x;
+    const int e = blockIdx.y, unit = blockIdx.x, rb = blockIdx.z;
     const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
     if (m <= 0) return;
     const ExpertTab& t = a.tab[e];
@@ -171,9 +173,9 @@ __global__ __launch_bounds__(256) void decode_requant_kernel(DecodeArgs a) {
 }
 
 // ---- down projection ---------------------------------------------------------------------
-__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a, int rb) {
+__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
     __shared__ int part[DN_WAVES][16][64];
-    const int e = blockIdx.y, unit = blockIdx.x;
+    const int e = blockIdx.y, unit = blockIdx.x, rb = blockIdx.z;
     const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
     if (m <= 0) return;
     const ExpertTab& t = a.tab[e];
@@ -245,12 +247,12 @@ bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 3
 
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
-    const dim3 g1(a.I / 32, a.E), g2(a.H / 32, a.E);
-    // an expert holds at most T rows: one launch per block of 32 rows (experts with fewer leave at once)
+    // an expert holds at most T rows: one work-group per (unit, block of 32 rows)
     const int nrb = cdiv(T, 32);
-    for (int rb = 0; rb < nrb; ++rb) hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a, rb);
+    const dim3 g1(a.I / 32, a.E, nrb), g2(a.H / 32, a.E, nrb);
+    hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
     hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(256), 0, st, a);
-    for (int rb = 0; rb < nrb; ++rb) hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a, rb);
+    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
