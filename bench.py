@@ -29,6 +29,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# Fabric-side bytes of one GEMM launch of the default workload (average of fc1 and fc2), from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain
+# 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
+# of the committed summary profiles/gemm_i8_kernel__opt6.7b_ffn.md and only applies to that workload.
+GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.876e8
 
 
 def _events(torch, n):
@@ -145,7 +150,8 @@ def bench_ffn(args, torch, haq, hi):
                    "act": "relu", "smoothing_alpha": 0.5, "gemms_per_step": n_gemm},
         "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (int8 MFMA GEMM + dequant epilogue)",
                      "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
-                     "avg_launch_ms": gemm_avg * 1e3, "ops_per_launch": ops_per_gemm, "traffic": None},
+                     "avg_launch_ms": gemm_avg * 1e3, "ops_per_launch": ops_per_gemm,
+                     "traffic": GEMM_TRAFFIC_BYTES_OPT67B_FFN if wl is not None else None, "traffic_unit": "bytes per launch"},
         "cpu_baseline": cpu,
     }
 
