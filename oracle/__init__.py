@@ -229,3 +229,51 @@ def moe_mid_absmax(X, idx, s_in, experts: list[Expert]) -> np.ndarray:
     lib().oracle_moe_mid_absmax(_p(X), C.c_int64(H), _p(_c(idx, np.int32)), _p(_c(s_in, np.float32)), arr,
                                 T, H, I, E, _p(ax))
     return ax
+
+
+# ---- adaptive smoothing (Algorithm 1 step 1, Eq. 3) ----------------------------------------
+def matmul_f64(X: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """Full-precision X W (binary16 activations, binary32 weights, binary64 arithmetic)."""
+    X = _c(X, np.float16)
+    W = _c(W, np.float32)
+    T, K = X.shape
+    K2, N = W.shape
+    assert K == K2
+    Y = np.empty((T, N), np.float64)
+    lib().oracle_matmul_f64(_p(X), C.c_int64(K), _p(W), T, K, N, _p(Y))
+    return Y
+
+
+def mse_f64(Y: np.ndarray, Yref: np.ndarray) -> float:
+    Y = _c(Y, np.float16)
+    Yref = _c(Yref, np.float64)
+    T, N = Y.shape
+    assert Yref.shape == (T, N)
+    f = lib().oracle_mse_f64
+    f.restype = C.c_double
+    return float(f(_p(Y), C.c_int64(N), _p(Yref), T, N))
+
+
+def smoothing_search(X: np.ndarray, W: np.ndarray, exponents, use_weight: bool = False):
+    """Grid search of the smoothing exponent e (Algorithm 1 step 1).
+
+    For every e of the grid, in order: s = ax^e (Eq. 3; with use_weight the balanced form
+    ax^e / aw^(1-e)), the weight is folded and quantised, Q(W s), the calibration
+    activations go through the quantised layer, Q(W s) Q(X / s), and the loss is the mean
+    squared error against the full-precision X W (the norm of Eq. 1 read as Frobenius^2 /
+    size).  A candidate replaces the incumbent only if its loss is strictly smaller, so
+    the first of equal minima wins.  Returns (losses [n_e] float64, best index, best s).
+    """
+    ax = col_absmax_f16(X)
+    aw = row_absmax_f32(W) if use_weight else None
+    Yref = matmul_f64(X, W)
+    losses = np.empty(len(exponents), np.float64)
+    best, best_loss, best_s = -1, np.inf, None
+    for i, e in enumerate(exponents):
+        s = smoothing_vector(ax, aw, float(e))
+        Wq, sw = quant_weight(W, s)
+        Y = w8a8_linear(X, s, Wq, sw, "none")
+        losses[i] = mse_f64(Y, Yref)
+        if losses[i] < best_loss:
+            best, best_loss, best_s = i, losses[i], s
+    return losses, best, best_s

@@ -400,4 +400,37 @@ void oracle_moe_mid_absmax(const uint16_t* X, int64_t ldx, const int32_t* idx, c
     }
 }
 
+// ---- adaptive smoothing (Algorithm 1 step 1, Eq. 3) ---------------------------------------
+// Full-precision product the quantised layer is compared with: Yref = X W with the binary16
+// activations and binary32 weights taken as exact numbers, products and sums in binary64
+// (k ascending).  X [T x K], W [K x N], Yref [T x N].
+void oracle_matmul_f64(const uint16_t* X, int64_t ldx, const float* W, int T, int K, int N, double* Yref) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        double* y = Yref + (size_t)t * N;
+        for (int n = 0; n < N; ++n) y[n] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            const double x = (double)half_to_float(X[(size_t)t * ldx + k]);
+            const float* w = W + (size_t)k * N;
+            for (int n = 0; n < N; ++n) y[n] += x * (double)w[n];
+        }
+    }
+}
+
+// Quantisation loss of one candidate: mean over all T*N outputs of (Y - Yref)^2, the binary16
+// outputs of the quantised layer against the full-precision product, in binary64 (row sums
+// first, then the rows in order).
+double oracle_mse_f64(const uint16_t* Y, int64_t ldy, const double* Yref, int T, int N) {
+    double total = 0.0;
+    for (int t = 0; t < T; ++t) {
+        double row = 0.0;
+        for (int n = 0; n < N; ++n) {
+            const double d = (double)half_to_float(Y[(size_t)t * ldy + n]) - Yref[(size_t)t * N + n];
+            row += d * d;
+        }
+        total += row;
+    }
+    return total / ((double)T * (double)N);
+}
+
 }  // extern "C"

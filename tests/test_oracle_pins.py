@@ -417,6 +417,83 @@ def test_mid_absmax_matches_dumped_intermediate():
         assert np.array_equal(ax[e], ref)
 
 
+# ----------------------------------------------------------------- adaptive smoothing (Algorithm 1 step 1)
+def test_matmul_f64_is_the_library_product():
+    rng = np.random.default_rng(21)
+    X = (rng.standard_normal((13, 70)) * 3).astype(np.float16)
+    W = rng.standard_normal((70, 29)).astype(F32)
+    ref = X.astype(np.float64) @ W.astype(np.float64)  # library routine; shapes are not square: a transpose fails
+    got = oracle.matmul_f64(X, W)
+    assert got.shape == (13, 29)
+    assert np.allclose(got, ref, rtol=1e-13, atol=1e-13)
+    # exactly representable case: small integers give an exact product
+    Xi = rng.integers(-8, 9, (5, 16)).astype(np.float16)
+    Wi = rng.integers(-8, 9, (16, 7)).astype(F32)
+    assert np.array_equal(oracle.matmul_f64(Xi, Wi), (Xi.astype(np.int64) @ Wi.astype(np.int64)).astype(np.float64))
+
+
+def test_mse_f64_closed_forms():
+    T, N = 6, 10
+    Y = np.ones((T, N), np.float16)
+    assert oracle.mse_f64(Y, np.full((T, N), 0.5)) == 0.25            # every difference is 1/2
+    ref = np.ones((T, N)) - np.arange(T)[:, None]                      # row t is off by t
+    assert oracle.mse_f64(Y, ref) == sum(t * t for t in range(T)) / T
+    ref2 = np.ones((T, N))
+    ref2[2, 3] = -2.0                                                  # a single entry off by 3
+    assert oracle.mse_f64(Y, ref2) == 9.0 / (T * N)
+    assert oracle.mse_f64(Y, np.ones((T, N))) == 0.0
+
+
+def _flat_magnitude_case(seed, T=24, K=128, N=40):
+    """Activations whose every channel has absmax exactly 4 and weights whose every input
+    channel has absmax exactly 1/4: the smoothing vector is then a power of two for
+    e in {0, 1/2, 1}, and dividing / multiplying by a power of two is exact, so the quantised
+    layer produces bit-identical outputs for those exponents."""
+    rng = np.random.default_rng(seed)
+    X = rng.uniform(-3.9, 3.9, (T, K)).astype(np.float16)
+    X[rng.integers(0, T, K), np.arange(K)] = np.float16(4.0) * rng.choice([-1, 1], K).astype(np.float16)
+    W = rng.uniform(-0.24, 0.24, (K, N)).astype(F32)
+    W[np.arange(K), rng.integers(0, N, K)] = F32(0.25)
+    return X, W
+
+
+def test_smoothing_search_ties_keep_the_first_exponent():
+    X, W = _flat_magnitude_case(22)
+    grid = [0.0, 0.5, 1.0]
+    losses, best, s = oracle.smoothing_search(X, W, grid, use_weight=False)
+    assert losses[0] == losses[1] == losses[2] and losses[0] > 0   # s = 1, 2, 4: the same bits come out
+    assert best == 0 and np.array_equal(s, np.ones(128, F32))
+    # balanced form: ax^e / aw^(1-e) = 4^e * 4^(1-e) = 4 whatever e is
+    losses_b, best_b, s_b = oracle.smoothing_search(X, W, [0.25, 0.5, 0.75], use_weight=True)
+    assert losses_b[0] == losses_b[1] == losses_b[2] == losses[0]
+    assert best_b == 0 and np.array_equal(s_b, np.full(128, 4.0, F32))
+    # put a better candidate last and a worse one first: the order of the grid must not matter
+    # for which loss is minimal, and the strict comparison keeps the first of the equal ones
+    losses_r, best_r, _ = oracle.smoothing_search(X, W, [1.0, 0.0, 0.5], use_weight=False)
+    assert best_r == 0 and np.array_equal(losses_r, losses)
+
+
+def test_smoothing_search_finds_the_minimum_on_outlier_activations():
+    X, _, _ = hi.hidden_states(23, 96, 512, 4, 50.0)
+    W = hi.gaussian_weight(23, 0, 512, 160)
+    grid = [i / 10 for i in range(11)]
+    losses, best, s = oracle.smoothing_search(X, W, grid)
+    assert best == int(np.argmin(losses))                     # numpy's argmin is also first-of-equals
+    assert 0 < best < 10                                      # an interior exponent (outliers need some, not full, migration)
+    assert losses[best] < 0.5 * losses[0]                     # and it beats no smoothing clearly
+    assert np.array_equal(s, oracle.smoothing_vector(oracle.col_absmax_f16(X), None, grid[best]))
+    # the loss of the e = 0 candidate is that of the unsmoothed layer, computed independently
+    Wq1, sw1 = oracle.quant_weight(W, None)
+    exact = X.astype(np.float64) @ W.astype(np.float64)
+    mse_1 = np.mean((oracle.w8a8_linear(X, None, Wq1, sw1).astype(np.float64) - exact) ** 2)
+    assert np.isclose(losses[0], mse_1, rtol=1e-12)
+    # the balanced form at e = 1/2 is the fixed-alpha recipe used for the other workloads
+    s_half, Wq, sw = offline.quantize_linear(X, W, 0.5)
+    mse_h = np.mean((oracle.w8a8_linear(X, s_half, Wq, sw).astype(np.float64) - exact) ** 2)
+    losses_b, _, _ = oracle.smoothing_search(X, W, [0.5], use_weight=True)
+    assert np.isclose(losses_b[0], mse_h, rtol=1e-12)
+
+
 # ----------------------------------------------------------------- input recipe sanity
 def test_zipf_router_bias_reaches_target_popularity():
     wl = hi.MoeWorkload("zipf_small", 19, 2048, 256, 64, 8, "zipf")
