@@ -141,6 +141,47 @@ int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int
                      size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Adaptive activation smoothing (Algorithm 1 step 1; Eq. 3): grid search of the
+ * exponent e in [0, 1] of the smoothing vector for one linear layer, on
+ * calibration activations X (fp16 [T x K], device) and the layer's weight W
+ * (fp32 [K x N], device, input-channel major).
+ *
+ * For every exponent of the grid, in order:
+ *   s = ax^e  (ax_k = max_t |X_tk|; Eq. 3 -- with use_weight != 0 the balanced
+ *   form ax^e / aw^(1-e), aw_k = max_n |W_kn|; both as haq_smoothing_vector
+ *   evaluates them), the weight is folded and quantised, Q(W s), the calibration
+ *   activations go through the quantised layer exactly as haq_w8a8_linear runs
+ *   it, and the loss is the mean over all T*N outputs of (Y - Yref)^2, where
+ *   Yref = X W in binary64 (the norm of Eq. 1 read as a mean squared error).
+ * A candidate replaces the incumbent only if its loss is strictly smaller: the
+ * first of equal minima wins.
+ *
+ * exponents: host [n_e], 1 <= n_e <= 256, each in [0, 1].  Outputs: losses host
+ * [n_e] (binary64), *best host (index into the grid), s_best device [K].
+ * The call synchronises the stream (the decision is taken on the host) and is
+ * meant for the offline quantiser, not for a serving loop.  K % 64 == 0,
+ * K < 65536, N % 16 == 0.  Workspace (256-byte aligned, device) of
+ * haq_smoothing_search_workspace_bytes(T, K, N, n_e) bytes: it holds Yref
+ * (8 T N bytes), one candidate's weights and outputs, and the grid's vectors.
+ *
+ * The two building blocks are callable on their own:
+ * haq_reference_matmul_f64: Yref [T x N] binary64 (device) = X W, one binary64
+ *   accumulator per output, input channels in ascending order.
+ * haq_quant_loss_f64: *loss (device) = mean (Y - Yref)^2 for Y fp16 [T x N] (row
+ *   stride ldy); row sums run over the columns in order, then the rows in
+ *   order, so the value does not depend on the launch shape; row_scratch is T
+ *   doubles of device memory.
+ */
+size_t haq_smoothing_search_workspace_bytes(int32_t T, int32_t K, int32_t N, int32_t n_e);
+int32_t haq_reference_matmul_f64(const void* x_fp16, int64_t ldx, const float* w, int32_t T, int32_t K, int32_t N,
+                                 double* yref, void* stream);
+int32_t haq_quant_loss_f64(const void* y_fp16, int64_t ldy, const double* yref, int32_t T, int32_t N, double* row_scratch,
+                           double* loss, void* stream);
+int32_t haq_smoothing_search(const void* x_fp16, int64_t ldx, const float* w, int32_t T, int32_t K, int32_t N,
+                             const double* exponents, int32_t n_e, int32_t use_weight, double* losses, int32_t* best,
+                             float* s_best, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Top-2 routed SwiGLU expert FFN with W8A8 experts.
  *
  * Per token t: top-2 experts by router logit (lowest index wins ties); gate

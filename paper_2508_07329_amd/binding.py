@@ -20,6 +20,7 @@ __all__ = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
+    "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
@@ -35,6 +36,7 @@ EXPORTED_SYMBOLS = [
     "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ffn_workspace_bytes", "haq_w8a8_ffn", "haq_ctx_create",
     "haq_ctx_destroy",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
+    "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
 ]
 
 
@@ -67,7 +69,7 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.haq_last_error.restype = C.c_char_p
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
-                  "haq_ffn_workspace_bytes"):
+                  "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -299,3 +301,43 @@ def haq_moe_w8a8_ffn(x, logits, s_in, experts: list[ExpertWeights], I: int, *, c
                                   C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),
                                   C.c_size_t(workspace.numel()), _stream()))
     return (y, dbg) if debug else y
+
+
+# ---- adaptive smoothing (Algorithm 1 step 1) --------------------------------------------
+def haq_smoothing_search_workspace_bytes(T: int, K: int, N: int, n_e: int) -> int:
+    return int(lib().haq_smoothing_search_workspace_bytes(T, K, N, n_e))
+
+
+def haq_reference_matmul_f64(x, w, *, out=None):
+    """x fp16 [T,K], w fp32 [K,N] -> X W in binary64 [T,N]."""
+    T, K = x.shape
+    N = w.shape[1]
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float64, device=x.device)
+    _check(lib().haq_reference_matmul_f64(_ptr(x), C.c_int64(x.stride(0)), _ptr(w), T, K, N, _ptr(y), _stream()))
+    return y
+
+
+def haq_quant_loss_f64(y, yref):
+    """mean (y - yref)^2 over all entries, binary64; returns a 1-element device tensor."""
+    T, N = y.shape
+    scratch = torch.empty((T,), dtype=torch.float64, device=y.device)
+    loss = torch.empty((1,), dtype=torch.float64, device=y.device)
+    _check(lib().haq_quant_loss_f64(_ptr(y), C.c_int64(y.stride(0)), _ptr(yref), T, N, _ptr(scratch), _ptr(loss), _stream()))
+    return loss
+
+
+def haq_smoothing_search(x, w, exponents, use_weight: bool = False, *, workspace=None):
+    """Grid search of the smoothing exponent; returns (losses: list[float], best: int, s_best [K] device)."""
+    T, K = x.shape
+    N = w.shape[1]
+    n_e = len(exponents)
+    grid = (C.c_double * n_e)(*[float(e) for e in exponents])
+    losses = (C.c_double * n_e)()
+    best = C.c_int32(-1)
+    s_best = torch.empty((K,), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = _ws(haq_smoothing_search_workspace_bytes(T, K, N, n_e), x.device)
+    _check(lib().haq_smoothing_search(_ptr(x), C.c_int64(x.stride(0)), _ptr(w), T, K, N, grid, n_e, int(bool(use_weight)),
+                                      losses, C.byref(best), _ptr(s_best), _ptr(workspace), C.c_size_t(workspace.numel()),
+                                      _stream()))
+    return list(losses), int(best.value), s_best

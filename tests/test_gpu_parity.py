@@ -334,3 +334,58 @@ def test_moe_mixtral_prefill_zipf(layer):
     counts = _check_moe(_mixtral_case(wl, layer), layer["dev_experts"], tokens)
     share = counts / counts.sum()
     assert np.max(np.abs(share - hi.zipf_shares(8))) < 0.02
+
+
+# ------------------------------------------------------------------ adaptive smoothing grid search (Algorithm 1 step 1)
+def _search_case(name):
+    if name == "small_ragged":
+        X, _, _ = hi.hidden_states(61, 37, 128, 3, 40.0)
+        return X, hi.gaussian_weight(61, 0, 128, 48)
+    if name == "tiles_and_tails":
+        X, _, _ = hi.hidden_states(62, 203, 320, 4, 50.0)
+        return X, hi.gaussian_weight(62, 0, 320, 208)
+    l = hi.OPT125M_LINEAR
+    X, _, _ = hi.hidden_states(l.seed, l.T, l.K, l.n_outlier, l.mult)
+    return X, hi.gaussian_weight(l.seed, 0, l.K, l.N)
+
+
+@pytest.mark.parametrize("name", ["small_ragged", "tiles_and_tails", "opt125m_linear"])
+def test_reference_product_and_loss_bit_exact(name):
+    """One binary64 accumulator per output with ascending k, and sequential row sums: both
+    sides perform the same binary64 operations in the same order, so the bits agree."""
+    X, W = _search_case(name)
+    yref = haq.haq_reference_matmul_f64(dev(X), dev(W))
+    ref = oracle.matmul_f64(X, W)
+    assert bits_equal(host(yref), ref)
+    s, Wq, sw = offline.quantize_linear(X, W)
+    Y = oracle.w8a8_linear(X, s, Wq, sw)
+    loss = haq.haq_quant_loss_f64(dev(Y), yref)
+    assert float(host(loss)[0]) == oracle.mse_f64(Y, ref)
+
+
+@pytest.mark.parametrize("name,use_weight", [("small_ragged", False), ("small_ragged", True), ("tiles_and_tails", False),
+                                             ("opt125m_linear", False), ("opt125m_linear", True)])
+def test_smoothing_search_matches_oracle(name, use_weight):
+    X, W = _search_case(name)
+    grid = [i / 10 for i in range(11)]
+    losses_ref, best_ref, s_ref = oracle.smoothing_search(X, W, grid, use_weight)
+    losses, best, s = haq.haq_smoothing_search(dev(X), dev(W), grid, use_weight)
+    assert np.array_equal(np.asarray(losses), losses_ref), diff_report(np.asarray(losses), losses_ref)
+    assert best == best_ref
+    assert bits_equal(host(s), s_ref)
+
+
+def test_smoothing_search_ties_and_single_candidate():
+    rng = np.random.default_rng(63)
+    T, K, N = 24, 128, 48
+    X = rng.uniform(-3.9, 3.9, (T, K)).astype(np.float16)
+    X[rng.integers(0, T, K), np.arange(K)] = np.float16(4.0)
+    W = rng.uniform(-0.24, 0.24, (K, N)).astype(F32)
+    losses, best, s = haq.haq_smoothing_search(dev(X), dev(W), [1.0, 0.0, 0.5])
+    assert losses[0] == losses[1] == losses[2] and best == 0      # s = 4, 1, 2: identical outputs, first kept
+    assert bits_equal(host(s), np.full(K, 4.0, F32))
+    l1, b1, s1 = haq.haq_smoothing_search(dev(X), dev(W), [0.3])
+    lr, br, sr = oracle.smoothing_search(X, W, [0.3])
+    assert b1 == 0 and l1[0] == lr[0] and bits_equal(host(s1), sr)
+    with pytest.raises(haq.HaqError):
+        haq.haq_smoothing_search(dev(X), dev(W), [0.5, 1.5])
