@@ -12,7 +12,9 @@ GEMM), timed with events around its launches; `cpu_baseline` is the CPU oracle
 timed on a bounded sample of the same workload.
 
 Other workloads (--workload): linear (OPT-125m linear), moe_prefill (Mixtral
-layer, 4096 tokens, Zipf routing), moe_decode_b1 / _b8 / _b64.
+layer, 4096 tokens, Zipf routing), moe_decode_b1 / _b8 / _b64, moe_offload, and
+smooth_search (the offline grid search of the smoothing exponent on fc1 of the
+default block).
 """
 from __future__ import annotations
 
@@ -29,6 +31,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+PEAK_FP64_TFLOPS = 78.6  # vector fp64 FMA
 # Fabric-side bytes of one GEMM launch of the default workload (average of fc1 and fc2), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
@@ -368,6 +371,53 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
     }
 
 
+def bench_search(args, torch, haq, hi):
+    """Adaptive smoothing (Algorithm 1 step 1): 11 exponents on fc1 of the OPT-6.7B-shaped block."""
+    wl = hi.OPT67B_FFN
+    T, K, N = wl.T, wl.H, wl.F
+    X_h, _, _ = hi.hidden_states(wl.seed, T, K, wl.n_outlier, wl.mult)
+    W_h = hi.gaussian_weight(wl.seed, 0, K, N)
+    X, W = torch.from_numpy(X_h).to("cuda:0"), torch.from_numpy(W_h).to("cuda:0")
+    grid = [i / 10 for i in range(11)]
+    ws = torch.empty(haq.haq_smoothing_search_workspace_bytes(T, K, N, len(grid)), dtype=torch.uint8, device="cuda:0")
+    result = {}
+
+    def step():
+        result["r"] = haq.haq_smoothing_search(X, W, grid, False, workspace=ws)
+
+    sec = _time_steps(torch, step, args.steps, args.warmup)
+    losses, best, _ = result["r"]
+    yref = torch.empty((T, N), dtype=torch.float64, device="cuda:0")
+    ev = _events(torch, 2 * args.steps)
+    for i in range(args.steps):
+        ev[2 * i].record()
+        haq.haq_reference_matmul_f64(X, W, out=yref)
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    ref_s = float(np.mean([ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(args.steps)])) * 1e-3
+    flops = 2.0 * T * K * N
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        lo, bo, _ = oracle.smoothing_search(X_h, W_h, grid)
+        dt = time.perf_counter() - t0
+        cpu = {"value": len(grid) / dt, "unit": "candidates/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"the whole search once ({len(grid)} exponents, all {T} rows), {dt:.2f} s",
+               "same_best_exponent": bool(bo == best), "same_losses_bitwise": bool(np.array_equal(lo, np.asarray(losses)))}
+    return {
+        "metric": "smoothing grid search candidates/s (offline)", "value": len(grid) / sec, "unit": "candidates/s",
+        "ms_per_step": sec * 1e3, "dtype": "int8 candidates, fp64 reference and loss",
+        "config": {"workload": "opt-6.7b fc1 smoothing search", "tokens": T, "in_features": K, "out_features": N,
+                   "exponents": grid, "form": "s = ax^e"},
+        "best_exponent": grid[best], "losses": losses,
+        "roofline": {"bound": "alu", "kernel": "ref_gemm_f64_kernel (binary64 reference product, once per search)",
+                     "achieved": flops / ref_s / 1e12, "peak": PEAK_FP64_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / ref_s / 1e12 / PEAK_FP64_TFLOPS, "avg_launch_ms": ref_s * 1e3, "traffic": None},
+        "cpu_baseline": cpu,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,7 +425,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ffn",
                     choices=["ffn", "linear", "moe_prefill", "moe_decode_b1", "moe_decode_b8", "moe_decode_b64",
-                             "moe_offload"])
+                             "moe_offload", "smooth_search"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MB (reference for rocprofv3 --pmc byte counters)")
@@ -399,7 +449,12 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    res = bench_ffn(args, torch, haq, hi) if args.workload in ("ffn", "linear") else bench_moe(args, torch, haq, hi)
+    if args.workload in ("ffn", "linear"):
+        res = bench_ffn(args, torch, haq, hi)
+    elif args.workload == "smooth_search":
+        res = bench_search(args, torch, haq, hi)
+    else:
+        res = bench_moe(args, torch, haq, hi)
     line = {"metric": res.pop("metric"), "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"),
             "higher_is_better": res.pop("higher_is_better", True), "scaling": "weak", "vs_baseline": None,

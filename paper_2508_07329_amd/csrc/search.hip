@@ -80,42 +80,79 @@ __global__ __launch_bounds__(256) void ref_gemm_f64_kernel(const __half* x, int6
 
 // ---- loss = mean (Y - Yref)^2 in binary64 ------------------------------------------------------
 // Row sums run over the columns in order (one sequential chain per row, as the definition is
-// written), so the value does not depend on the launch shape: a work-group owns 64 rows, stages
-// 64 x 64 tiles of the differences' squares through LDS with coalesced loads, and thread r adds
-// the 64 values of row r in column order.  A single thread then adds the rows in order.
+// written), so the value does not depend on the launch shape.  A work-group owns 16 rows and
+// walks over tiles of 256 columns: all threads fetch the next tile (coalesced) and square the
+// differences while thread r < 16 adds the 256 values of row r of the current tile, in column
+// order, from LDS (two buffers, one barrier per tile).  A last small kernel adds the rows in
+// order.
+constexpr int LR = 16, LC = 256;
 __global__ __launch_bounds__(256) void row_sq_err_kernel(const __half* y, int64_t ldy, const double* yref, int T, int N,
                                                          double* row_sum) {
-    __shared__ double sq[64][65];
+    __shared__ double sq[2][LR][LC + 2];
     const int tid = threadIdx.x;
-    const int row0 = blockIdx.x * 64;
+    const int row0 = blockIdx.x * LR;
+    const int ntile = (N + LC - 1) / LC;
+    double v[LR];
+    auto fetch = [&](int tile) {  // thread = one column of the tile, all 16 rows
+        const int col = tile * LC + tid;
+        const int colc = min(col, N - 1);  // loads stay unconditional (clamped), masked afterwards
+        __half yv[LR];
+        double rv[LR];
+#pragma unroll
+        for (int r = 0; r < LR; ++r) {
+            const int rowc = min(row0 + r, T - 1);
+            yv[r] = y[(size_t)rowc * ldy + colc];
+            rv[r] = yref[(size_t)rowc * N + colc];
+        }
+#pragma unroll
+        for (int r = 0; r < LR; ++r) {
+            const double d = (double)h2f(yv[r]) - rv[r];
+            v[r] = (row0 + r < T && col < N) ? d * d : 0.0;
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int r = 0; r < LR; ++r) sq[buf][r][tid] = v[r];
+    };
+    fetch(0);
+    stage(0);
+    __syncthreads();
     double run = 0.0;
-    for (int c0 = 0; c0 < N; c0 += 64) {
-        for (int i = tid; i < 64 * 64; i += 256) {
-            const int r = i / 64, c = i % 64;
-            const int row = row0 + r, col = c0 + c;
-            double v = 0.0;
-            if (row < T && col < N) {
-                const double d = (double)h2f(y[(size_t)row * ldy + col]) - yref[(size_t)row * N + col];
-                v = d * d;
+    for (int tile = 0; tile < ntile; ++tile) {
+        const int buf = tile & 1;
+        if (tile + 1 < ntile) fetch(tile + 1);  // in flight while the chain below runs
+        if (tid < LR) {
+            const int lim = min(LC, N - tile * LC);
+            const double* p = sq[buf][tid];
+            int c = 0;
+            for (; c + 16 <= lim; c += 16) {  // 16 loads ahead of the dependent additions
+                double t[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t[i] = p[c + i];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) run += t[i];
             }
-            sq[r][c] = v;
+            for (; c < lim; ++c) run += p[c];
         }
-        __syncthreads();
-        if (tid < 64) {
-            const int lim = min(64, N - c0);
-            for (int c = 0; c < lim; ++c) run += sq[tid][c];
-        }
+        if (tile + 1 < ntile) stage(buf ^ 1);
         __syncthreads();
     }
-    if (tid < 64 && row0 + tid < T) row_sum[row0 + tid] = run;
+    if (tid < LR && row0 + tid < T) row_sum[row0 + tid] = run;
 }
 
-__global__ void total_loss_kernel(const double* row_sum, int T, int N, double* loss) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        double total = 0.0;
-        for (int t = 0; t < T; ++t) total += row_sum[t];
-        *loss = total / ((double)T * (double)N);
+__global__ __launch_bounds__(256) void total_loss_kernel(const double* row_sum, int T, int N, double* loss) {
+    __shared__ double part[1024];
+    double total = 0.0;
+    for (int t0 = 0; t0 < T; t0 += 1024) {  // rows in order, 1024 at a time through LDS
+        for (int i = threadIdx.x; i < 1024; i += 256) part[i] = t0 + i < T ? row_sum[t0 + i] : 0.0;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int lim = min(1024, T - t0);
+            for (int i = 0; i < lim; ++i) total += part[i];
+        }
+        __syncthreads();
     }
+    if (threadIdx.x == 0) *loss = total / ((double)T * (double)N);
 }
 
 struct SearchWs {
@@ -180,8 +217,8 @@ int32_t haq_quant_loss_f64(const void* y_fp16, int64_t ldy, const double* yref, 
     if (T <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_loss_f64: T=%d N=%d", T, N);
     if (!y_fp16 || !yref || !row_scratch || !loss || ldy < N) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_loss_f64: null buffer or ldy=%lld", (long long)ldy);
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(row_sq_err_kernel, dim3(cdiv(T, 64)), dim3(256), 0, st, (const __half*)y_fp16, ldy, yref, T, N, row_scratch);
-    hipLaunchKernelGGL(total_loss_kernel, dim3(1), dim3(64), 0, st, (const double*)row_scratch, T, N, loss);
+    hipLaunchKernelGGL(row_sq_err_kernel, dim3(cdiv(T, LR)), dim3(256), 0, st, (const __half*)y_fp16, ldy, yref, T, N, row_scratch);
+    hipLaunchKernelGGL(total_loss_kernel, dim3(1), dim3(256), 0, st, (const double*)row_scratch, T, N, loss);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -389,3 +389,16 @@ def test_smoothing_search_ties_and_single_candidate():
     assert b1 == 0 and l1[0] == lr[0] and bits_equal(host(s1), sr)
     with pytest.raises(haq.HaqError):
         haq.haq_smoothing_search(dev(X), dev(W), [0.5, 1.5])
+
+
+def test_smoothing_search_full_size_fc1():
+    """fc1 of the OPT-6.7B-shaped block, the shape bench.py's smooth_search workload times."""
+    wl = hi.OPT67B_FFN
+    X, _, _ = hi.hidden_states(wl.seed, wl.T, wl.H, wl.n_outlier, wl.mult)
+    W = hi.gaussian_weight(wl.seed, 0, wl.H, wl.F)
+    grid = [0.0, 0.5, 0.8]
+    losses_ref, best_ref, s_ref = oracle.smoothing_search(X, W, grid)
+    losses, best, s = haq.haq_smoothing_search(dev(X), dev(W), grid)
+    assert np.array_equal(np.asarray(losses), losses_ref)
+    assert best == best_ref == 1
+    assert bits_equal(host(s), s_ref)
