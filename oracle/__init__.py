@@ -277,3 +277,64 @@ def smoothing_search(X: np.ndarray, W: np.ndarray, exponents, use_weight: bool =
         if losses[i] < best_loss:
             best, best_loss, best_s = i, losses[i], s
     return losses, best, best_s
+
+
+# ---- offload scheduler (Section III.C: cost model, LRU expert cache, Algorithm 2) -----------
+# Plain host logic, written out step by step.
+def n_critical(t_e: float, latency_cpu: float, latency_gpu: float):
+    """Critical batch size of Eq. 7-8.  Computing an expert on the CPU costs
+    T_CPU = n * latency_cpu, moving it to the GPU and computing there costs
+    T_sum = t_e + n * latency_gpu; the expert is transferred when n > n_critical, and
+    n_critical is the largest n for which the CPU is not slower (T_CPU <= T_sum).
+    None when the CPU is never slower."""
+    if not latency_cpu > latency_gpu:
+        return None
+    n = 0
+    while (n + 1) * latency_cpu <= t_e + (n + 1) * latency_gpu:
+        n += 1
+    return n
+
+
+def lru_trace(accesses, capacity: int):
+    """Least-recently-used cache of `capacity` entries over a sequence of keys.
+    Returns (hit flags per access, cache content from least to most recently used)."""
+    cache = []  # least recently used first
+    hits = []
+    for key in accesses:
+        if key in cache:
+            hits.append(True)
+            cache.remove(key)
+        else:
+            hits.append(False)
+            if len(cache) >= capacity:
+                cache.pop(0)
+        cache.append(key)
+    return hits, cache
+
+
+def select_experts(num_layers: int, top_k: int, supplement_k: int, path_stats, expert_freq):
+    """Algorithm 2.  path_stats[layer] = [(experts of one activation path at this layer,
+    frequency), ...]; expert_freq[layer] = [(expert, frequency), ...].  Stage I walks the
+    layer's paths from the most frequent down and takes their experts until top_k are
+    selected (top_k >= 1); stage II adds the layer's most frequently activated experts
+    until top_k + supplement_k are selected.  Equal frequencies keep their input order.
+    Returns a list of expert lists in order of selection."""
+    selected = [[] for _ in range(num_layers)]
+    for layer in range(num_layers):
+        paths = sorted(path_stats[layer], key=lambda pf: -pf[1])  # stable
+        for path, _ in paths:
+            for e in path:
+                if e not in selected[layer]:
+                    selected[layer].append(e)
+                if len(selected[layer]) >= top_k:
+                    break
+            if len(selected[layer]) >= top_k:
+                break
+    for layer in range(num_layers):
+        experts = sorted(expert_freq[layer], key=lambda ef: -ef[1])
+        for e, _ in experts:
+            if len(selected[layer]) >= top_k + supplement_k:
+                break
+            if e not in selected[layer]:
+                selected[layer].append(e)
+    return selected

@@ -28,6 +28,19 @@ constexpr int DN_WAVES = 8;    // down: 32 channels per work-group, K split 8 wa
 constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave (two operands each)
 constexpr int DN_DEPTH = 14;
 
+// blockIdx.y enumerates the experts that hold rows, in index order (the grid has min(E, 2T)
+// of them: with one token only two experts can be active, and work-groups that find nothing
+// to do would still cost dispatch slots).  Returns -1 past the last active expert.
+__device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, int j) {
+    for (int e = 0; e < E; ++e) {
+        if (offsets[e + 1] > offsets[e]) {
+            if (j == 0) return e;
+            --j;
+        }
+    }
+    return -1;
+}
+
 // ---- gate / up projections + SwiGLU + per-unit row maxima of h / s_mid ---------------
 // Work-group (unit, e, rb) handles rows [32*rb, 32*rb + 32) of expert e; row blocks past the
 // expert's rows leave at once (rb is the slowest grid dimension, so those empty work-groups
@@ -35,7 +48,8 @@ constexpr int DN_DEPTH = 14;
 __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
     __shared__ int part[GU_WAVES][2][16][64];
     __shared__ float wmax[GU_WAVES][32];
-    const int e = blockIdx.y, unit = blockIdx.x, rb = blockIdx.z;
+    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y), unit = blockIdx.x, rb = blockIdx.z;
+    if (e < 0) return;
     const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
     if (m <= 0) return;
     const ExpertTab& t = a.tab[e];
@@ -175,7 +189,8 @@ __global__ __launch_bounds__(256) void decode_requant_kernel(DecodeArgs a) {
 // ---- down projection ---------------------------------------------------------------------
 __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
     __shared__ int part[DN_WAVES][16][64];
-    const int e = blockIdx.y, unit = blockIdx.x, rb = blockIdx.z;
+    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y), unit = blockIdx.x, rb = blockIdx.z;
+    if (e < 0) return;
     const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
     if (m <= 0) return;
     const ExpertTab& t = a.tab[e];
@@ -249,7 +264,8 @@ int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
     // an expert holds at most T rows: one work-group per (unit, block of 32 rows)
     const int nrb = cdiv(T, 32);
-    const dim3 g1(a.I / 32, a.E, nrb), g2(a.H / 32, a.E, nrb);
+    const int ne = a.E < P ? a.E : P;  // at most 2T experts can hold rows
+    const dim3 g1(a.I / 32, ne, nrb), g2(a.H / 32, ne, nrb);
     hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
     hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(256), 0, st, a);
     hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);

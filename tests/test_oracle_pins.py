@@ -494,6 +494,47 @@ def test_smoothing_search_finds_the_minimum_on_outlier_activations():
     assert np.isclose(losses_b[0], mse_h, rtol=1e-12)
 
 
+# ----------------------------------------------------------------- offload scheduler (Section III.C)
+def test_lru_trace_textbook_reference_string():
+    # the classic 20-reference string with 3 frames: 12 misses under LRU (15 under FIFO, 9 under OPT)
+    refs = [7, 0, 1, 2, 0, 3, 0, 4, 2, 3, 0, 3, 2, 1, 2, 0, 1, 7, 0, 1]
+    hits, cache = oracle.lru_trace(refs, 3)
+    assert len(hits) - sum(hits) == 12
+    assert hits[:8] == [False, False, False, False, True, False, True, False]
+    assert cache == [7, 0, 1]                      # least recently used first
+    # capacity >= distinct keys: only compulsory misses; capacity 1: a hit only on immediate repeats
+    assert sum(oracle.lru_trace(refs, 6)[0]) == len(refs) - 6
+    assert oracle.lru_trace([1, 1, 2, 2, 2, 1], 1)[0] == [False, True, False, True, True, False]
+    # LRU differs from FIFO here: after 1 2 3 1 4, LRU evicted 2 (FIFO would have evicted 1)
+    assert oracle.lru_trace([1, 2, 3, 1, 4], 3)[1] == [3, 1, 4]
+
+
+def test_n_critical_is_the_break_even_batch():
+    # T_CPU = n, T_sum = 10 + n/2: equal at n = 20, the GPU wins from 21 on
+    assert oracle.n_critical(10.0, 1.0, 0.5) == 20
+    assert oracle.n_critical(10.1, 1.0, 0.5) == 20 and oracle.n_critical(9.9, 1.0, 0.5) == 19
+    assert oracle.n_critical(0.0, 1.0, 0.5) == 0      # free transfer: any batch goes to the GPU
+    assert oracle.n_critical(5.0, 1.0, 1.0) is None   # the CPU is never slower
+    for t_e, lc, lg in [(12.7, 0.9, 0.004), (3.0, 0.25, 0.125), (1e-3, 2.0, 1.0)]:
+        n = oracle.n_critical(t_e, lc, lg)
+        assert n * lc <= t_e + n * lg and (n + 1) * lc > t_e + (n + 1) * lg
+
+
+def test_select_experts_worked_example():
+    # one layer, 8 experts.  Paths (top-2 pairs at this layer) by frequency: (3,5) 40, (5,1) 30, (0,2) 5.
+    paths = [[((0, 2), 5), ((3, 5), 40), ((5, 1), 30)]]
+    freq = [[(0, 10), (1, 30), (2, 8), (3, 45), (4, 33), (5, 70), (6, 2), (7, 31)]]
+    # stage I with top_k = 3: 3, 5 from the hottest path, then 5 (already in), 1 -> stop at three
+    assert oracle.select_experts(1, 3, 0, paths, freq) == [[3, 5, 1]]
+    # stage II adds by expert frequency, skipping what is in: 5 (in), 3 (in), 4, 7
+    assert oracle.select_experts(1, 3, 2, paths, freq) == [[3, 5, 1, 4, 7]]
+    # top_k = 2 stops inside the first path; equal frequencies keep input order
+    assert oracle.select_experts(1, 2, 1, paths, [[(0, 9), (6, 9), (3, 9)]]) == [[3, 5, 0]]
+    # layers are independent
+    two = oracle.select_experts(2, 1, 1, [paths[0], [((7, 6), 1)]], [freq[0], [(6, 5), (2, 4)]])
+    assert two == [[3, 5], [7, 6]]
+
+
 # ----------------------------------------------------------------- input recipe sanity
 def test_zipf_router_bias_reaches_target_popularity():
     wl = hi.MoeWorkload("zipf_small", 19, 2048, 256, 64, 8, "zipf")
