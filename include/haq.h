@@ -224,19 +224,60 @@ typedef struct haq_moe_debug { /* every field optional (NULL to skip); all devic
 } haq_moe_debug;
 
 /* Context for layers with host-resident experts: owns a side stream, events and
- * `n_slots` HBM staging slots, each large enough for one expert of the given
- * geometry.  Creating and destroying it allocates / frees; the FFN call does not. */
+ * `n_slots` HBM slots, each large enough for one expert of the given geometry.
+ * Creating and destroying it allocates / frees; the FFN call does not.
+ *
+ * The slots are the GPU expert cache of Section III.C.1(c): a host-resident
+ * expert that a call activates is first looked up in the slots (a hit costs no
+ * transfer); on a miss it is copied into a free slot, else into the least
+ * recently used one.  The cache persists across calls on the same context and
+ * is keyed by the host address of the expert's gate/up matrix: after changing
+ * the bytes behind an address call haq_ctx_cache_invalidate.  Calls that share
+ * a context must not overlap.
+ * haq_ctx_cache_stats: totals since creation (any output may be NULL);
+ * slot_keys [n_slots] receives the address cached in each slot (NULL: empty). */
 typedef struct haq_ctx haq_ctx;
 int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out_host);
 int32_t haq_ctx_destroy(haq_ctx* ctx);
+int32_t haq_ctx_cache_stats(const haq_ctx* ctx, int64_t* hits, int64_t* misses, int64_t* bytes_copied,
+                            const void** slot_keys);
+int32_t haq_ctx_cache_invalidate(haq_ctx* ctx);
+
+/* ------------------------------------------------------------------------
+ * Host-side planning of the offload runtime (no device work).
+ *
+ * haq_offload_n_critical (Eq. 7-8): computing a host-resident expert on the CPU
+ * costs T_CPU = n * latency_cpu; transferring it costs T_sum = t_e + n *
+ * latency_gpu.  *n_critical = the largest batch n for which the CPU is not
+ * slower; the expert is worth transferring when n_inputs > *n_critical.
+ * *n_critical = -1 when latency_cpu <= latency_gpu (never transfer).  This
+ * library has no CPU compute path: haq_moe_w8a8_ffn always transfers; the
+ * figure is for a host runtime that owns one.
+ *
+ * haq_select_experts (Algorithm 2): which experts of every layer to keep
+ * resident.  Layer l owns the paths path_offsets[l] .. path_offsets[l+1]-1;
+ * path p lists path_len experts of that layer (path_experts [n_paths x
+ * path_len], the layer's slice of one activation path) with frequency
+ * path_freq[p]; expert_freq is [num_layers x experts_per_layer].  Stage I
+ * takes the experts of the layer's paths from the most frequent path down
+ * until top_k (>= 1) are selected; stage II adds the layer's most frequently
+ * activated experts until top_k + supplement_k are.  Equal frequencies keep
+ * input (index) order.  selected is [num_layers x (top_k + supplement_k)] in
+ * order of selection, padded with -1; n_selected [num_layers].  All host.    */
+int32_t haq_offload_n_critical(double t_e, double latency_cpu, double latency_gpu, int64_t* n_critical);
+int32_t haq_select_experts(int32_t num_layers, int32_t experts_per_layer, int32_t top_k, int32_t supplement_k,
+                           const int32_t* path_offsets, const int32_t* path_experts, int32_t path_len,
+                           const double* path_freq, const double* expert_freq, int32_t* selected,
+                           int32_t* n_selected);
 
 size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
 
 /* experts: HOST array of E descriptors (read during the call only).  ctx may be
  * NULL when every expert is device resident.  2 <= E <= 32, top_k must be 2,
- * H % 64 == 0, I % 64 == 0.  Host-resident experts are copied into the
- * context's staging slots with hipMemcpyAsync on its side stream while resident
- * experts compute; results are identical to the all-resident call.           */
+ * H % 64 == 0, I % 64 == 0.  Host-resident experts that the call activates and
+ * the context's cache does not hold are copied into its slots with
+ * hipMemcpyAsync on its side stream while resident experts compute; results
+ * are identical to the all-resident call.                                    */
 int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl,
                          const float* s_in, const haq_expert_desc* experts_host, int32_t T, int32_t H, int32_t I,
                          int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg_host,

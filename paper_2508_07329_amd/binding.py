@@ -21,6 +21,7 @@ __all__ = [
     "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
+    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
@@ -37,6 +38,7 @@ EXPORTED_SYMBOLS = [
     "haq_ctx_destroy",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
+    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
 ]
 
 
@@ -341,3 +343,44 @@ def haq_smoothing_search(x, w, exponents, use_weight: bool = False, *, workspace
                                       losses, C.byref(best), _ptr(s_best), _ptr(workspace), C.c_size_t(workspace.numel()),
                                       _stream()))
     return list(losses), int(best.value), s_best
+
+
+# ---- expert cache and offload planning (Section III.C) -----------------------------------
+def haq_ctx_cache_stats(ctx):
+    """(hits, misses, bytes_copied, [address cached in each slot or None])."""
+    h, m, b = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+    keys = (C.c_void_p * 32)()
+    _check(lib().haq_ctx_cache_stats(ctx, C.byref(h), C.byref(m), C.byref(b), keys))
+    return int(h.value), int(m.value), int(b.value), list(keys)
+
+
+def haq_ctx_cache_invalidate(ctx):
+    _check(lib().haq_ctx_cache_invalidate(ctx))
+
+
+def haq_offload_n_critical(t_e: float, latency_cpu: float, latency_gpu: float):
+    """Largest batch for which computing on the CPU is not slower; None if it never is."""
+    n = C.c_int64(0)
+    _check(lib().haq_offload_n_critical(C.c_double(t_e), C.c_double(latency_cpu), C.c_double(latency_gpu), C.byref(n)))
+    return None if n.value < 0 else int(n.value)
+
+
+def haq_select_experts(num_layers: int, experts_per_layer: int, top_k: int, supplement_k: int, path_stats, expert_freq):
+    """path_stats[layer] = [(experts of the path at this layer, frequency), ...]; expert_freq[layer] =
+    [frequency of expert 0, 1, ...].  Returns the selected experts of every layer in order of selection."""
+    path_len = next((len(p[0]) for layer in path_stats for p in layer), 1)
+    offs, flat, freq = [0], [], []
+    for layer in range(num_layers):
+        for path, f in path_stats[layer]:
+            assert len(path) == path_len
+            flat.extend(int(e) for e in path)
+            freq.append(float(f))
+        offs.append(len(freq))
+    ef = [float(expert_freq[l][e]) for l in range(num_layers) for e in range(experts_per_layer)]
+    cap = top_k + supplement_k
+    sel = (C.c_int32 * max(1, num_layers * cap))()
+    nsel = (C.c_int32 * max(1, num_layers))()
+    _check(lib().haq_select_experts(num_layers, experts_per_layer, top_k, supplement_k, (C.c_int32 * len(offs))(*offs),
+                                    (C.c_int32 * max(1, len(flat)))(*flat), path_len, (C.c_double * max(1, len(freq)))(*freq),
+                                    (C.c_double * len(ef))(*ef), sel, nsel))
+    return [[int(sel[l * cap + i]) for i in range(nsel[l])] for l in range(num_layers)]

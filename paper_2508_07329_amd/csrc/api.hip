@@ -159,6 +159,12 @@ struct haq_ctx {
     hipEvent_t routed = nullptr, call_done = nullptr;
     bool used = false;
     int32_t* counts_host = nullptr;  // pinned
+    // the slots double as an expert cache with least-recently-used replacement: which host
+    // expert (keyed by the address of its gate/up matrix) a slot holds, and when it was last used
+    const void* slot_key[32] = {};
+    uint64_t slot_tick[32] = {};
+    uint64_t tick = 0;
+    int64_t hits = 0, misses = 0, bytes_copied = 0;
 };
 
 extern "C" {
@@ -318,6 +324,25 @@ int32_t haq_ctx_destroy(haq_ctx* c) {
     return HAQ_OK;
 }
 
+int32_t haq_ctx_cache_stats(const haq_ctx* c, int64_t* hits, int64_t* misses, int64_t* bytes_copied, const void** slot_keys) {
+    if (!c) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_cache_stats: null context");
+    if (hits) *hits = c->hits;
+    if (misses) *misses = c->misses;
+    if (bytes_copied) *bytes_copied = c->bytes_copied;
+    if (slot_keys)
+        for (int i = 0; i < c->n_slots; ++i) slot_keys[i] = c->slot_key[i];
+    return HAQ_OK;
+}
+
+int32_t haq_ctx_cache_invalidate(haq_ctx* c) {
+    if (!c) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_cache_invalidate: null context");
+    for (int i = 0; i < 32; ++i) {
+        c->slot_key[i] = nullptr;
+        c->slot_tick[i] = 0;
+    }
+    return HAQ_OK;
+}
+
 size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E) {
     if (T < 0 || H <= 0 || I <= 0 || E <= 0) return 0;
     return carve_moe(nullptr, T, H, I, E).bytes;
@@ -351,11 +376,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
             if (d.location != HAQ_LOC_HOST_PINNED) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d location=%d", e, d.location);
             if (!ctx) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: expert %d is host resident but no context was given", e);
             if (ctx->H != H || ctx->I != I) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: context was created for H=%d I=%d", ctx->H, ctx->I);
-            // the i-th host-resident expert is staged in slot i mod n_slots
-            int8_t* slot = ctx->slot[n_host % ctx->n_slots];
-            tab[e].w13 = slot;
-            tab[e].w2 = slot + ctx->w13_bytes;
-            host_expert[n_host++] = e;
+            host_expert[n_host++] = e;  // its slot is chosen once the routing histogram is known
         }
     }
     const size_t need = carve_moe(nullptr, T, H, I, E).bytes;
@@ -494,7 +515,11 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     HAQ_CHECK_HIP(hipEventRecord(ctx->routed, st));
     HAQ_CHECK_HIP(hipEventSynchronize(ctx->routed));
     // slots may still be read by the previous call on another stream
-    if (ctx->used) HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->call_done, 0));
+    if (ctx->used) {
+        HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->call_done, 0));
+        // and a cached expert was copied during an earlier call, possibly issued from another stream
+        HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->call_done, 0));
+    }
     int resident[32], n_res = 0, res_rows = 0;
     bool is_host[32] = {};
     for (int i = 0; i < n_host; ++i) is_host[host_expert[i]] = true;
@@ -503,45 +528,76 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
             resident[n_res++] = e;
             res_rows += ctx->counts_host[e];
         }
-    // activated host experts, in list order; entry i of the host list is staged in slot i mod n_slots
+    // Activated host experts in expert order.  Each one looks for its weights in the slots (hit:
+    // nothing to copy); on a miss it takes a free slot, else the least recently used one (cache
+    // fill and LRU replacement of Section III.C.1c).  With more activated host experts than
+    // slots the victim may be a slot handed out earlier in this very call: the copy then waits
+    // for that expert's GEMMs.
     int order[32], n_order = 0;
     for (int i = 0; i < n_host; ++i)
-        if (ctx->counts_host[host_expert[i]] > 0) order[n_order++] = i;
-    bool issued[32] = {}, slot_taken[32] = {};
-    auto issue_copy = [&](int i) -> int {
-        const int e = host_expert[i];
-        int8_t* slot = ctx->slot[i % ctx->n_slots];
+        if (ctx->counts_host[host_expert[i]] > 0) order[n_order++] = host_expert[i];
+    int slot_of[32], prev_user[32], user_this_call[32];
+    bool hit[32];
+    for (int sl = 0; sl < ctx->n_slots; ++sl) user_this_call[sl] = -1;
+    for (int k = 0; k < n_order; ++k) {
+        const void* key = experts[order[k]].w13;
+        int sl = -1;
+        for (int c = 0; c < ctx->n_slots; ++c)
+            if (ctx->slot_key[c] == key) sl = c;
+        hit[k] = sl >= 0;
+        if (sl < 0) {
+            for (int c = 0; c < ctx->n_slots && sl < 0; ++c)
+                if (!ctx->slot_key[c]) sl = c;
+            if (sl < 0) {
+                sl = 0;
+                for (int c = 1; c < ctx->n_slots; ++c)
+                    if (ctx->slot_tick[c] < ctx->slot_tick[sl]) sl = c;
+            }
+            ctx->misses += 1;
+            ctx->bytes_copied += (int64_t)(ctx->w13_bytes + ctx->w2_bytes);
+        } else {
+            ctx->hits += 1;
+        }
+        slot_of[k] = sl;
+        prev_user[k] = user_this_call[sl];  // >= 0 only after an eviction inside this call
+        user_this_call[sl] = k;
+        ctx->slot_key[sl] = key;
+        ctx->slot_tick[sl] = ++ctx->tick;
+        tab[order[k]].w13 = ctx->slot[sl];
+        tab[order[k]].w2 = ctx->slot[sl] + ctx->w13_bytes;
+    }
+    if ((rc = launch_set_tab(tab, E, w.tab, st)) != HAQ_OK) return rc;
+    bool issued[32] = {};
+    auto issue_copy = [&](int k) -> int {
+        const int e = order[k];
+        int8_t* slot = ctx->slot[slot_of[k]];
         HAQ_CHECK_HIP(hipMemcpyAsync(slot, experts[e].w13, ctx->w13_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
         HAQ_CHECK_HIP(hipMemcpyAsync(slot + ctx->w13_bytes, experts[e].w2, ctx->w2_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
-        HAQ_CHECK_HIP(hipEventRecord(ctx->copied[i], ctx->copy_stream));
-        issued[i] = true;
+        HAQ_CHECK_HIP(hipEventRecord(ctx->copied[k], ctx->copy_stream));
+        issued[k] = true;
         return HAQ_OK;
     };
-    // the first user of every slot is copied right away
-    for (int k = 0; k < n_order; ++k) {
-        const int i = order[k], sl = i % ctx->n_slots;
-        if (slot_taken[sl]) continue;
-        slot_taken[sl] = true;
-        if ((rc = issue_copy(i)) != HAQ_OK) return rc;
-    }
+    // misses whose slot is not in use by an earlier expert of this call are copied right away
+    for (int k = 0; k < n_order; ++k)
+        if (!hit[k] && prev_user[k] < 0 && (rc = issue_copy(k)) != HAQ_OK) return rc;
     // device-resident experts compute while the first copies are in flight
     if (n_res > 0 && (rc = run_experts(resident, n_res, res_rows)) != HAQ_OK) return rc;
     for (int k = 0; k < n_order; ++k) {
-        const int i = order[k], e = host_expert[i];
-        HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[i], 0));  // issued: either above or when its slot's previous user finished
+        const int e = order[k];
+        if (!hit[k]) {
+            if (!issued[k]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
+            HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[k], 0));
+        }
         if ((rc = run_experts(&e, 1, ctx->counts_host[e])) != HAQ_OK) return rc;
-        HAQ_CHECK_HIP(hipEventRecord(ctx->done[i], st));
-        // this expert's slot is free after its GEMMs: hand it to the next activated expert of the same slot
+        HAQ_CHECK_HIP(hipEventRecord(ctx->done[k], st));
+        // a later expert of this call that evicts this one may overwrite the slot after these GEMMs
         for (int k2 = k + 1; k2 < n_order; ++k2) {
-            const int j = order[k2];
-            if (j % ctx->n_slots != i % ctx->n_slots) continue;
-            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->done[i], 0));
-            if ((rc = issue_copy(j)) != HAQ_OK) return rc;
+            if (prev_user[k2] != k) continue;
+            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->done[k], 0));
+            if ((rc = issue_copy(k2)) != HAQ_OK) return rc;
             break;
         }
     }
-    for (int k = 0; k < n_order; ++k)
-        if (!issued[order[k]]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
     rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
     HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
     ctx->used = true;

@@ -9,6 +9,7 @@ int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const 
 // work-groups of the multi-work-group routing path for T tokens (0: the single work-group
 // kernel is used); blk_counts holds route_blocks(T) * E entries
 int route_blocks(int T);
+int launch_set_tab(const ExpertTab* tab_host, int E, ExpertTab* tab_dev, hipStream_t st);
 int launch_combine(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H, __half* out,
                    int64_t ldo, hipStream_t st);
 }  // namespace haq

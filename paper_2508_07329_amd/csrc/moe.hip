@@ -199,6 +199,12 @@ __global__ __launch_bounds__(RT_THREADS) void permute_kernel(int T, int E, TabAl
     }
 }
 
+// Rewrites the device copy of the expert table (the staging slot of a streamed expert is only
+// known once the routing histogram is back on the host).
+__global__ void set_tab_kernel(TabAll tab, int E, ExpertTab* tab_dev) {
+    if ((int)threadIdx.x < E) tab_dev[threadIdx.x] = tab.e[threadIdx.x];
+}
+
 // out[t] = fp16(g0 * y[inv[2t]] + g1 * y[inv[2t+1]]), 8 channels per thread.
 __global__ void combine_kernel(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H,
                                __half* out, int64_t ldo) {
@@ -242,6 +248,14 @@ int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const 
     const size_t sm = ((size_t)E * PERM_THREADS + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(route_permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, logits, ldl, T, E, tab, tab_dev, idx, gw,
                        counts, offsets, perm, inv);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int launch_set_tab(const ExpertTab* tab_host, int E, ExpertTab* tab_dev, hipStream_t st) {
+    TabAll tab{};
+    for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
+    hipLaunchKernelGGL(set_tab_kernel, dim3(1), dim3(64), 0, st, tab, E, tab_dev);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -80,3 +80,36 @@ def test_smoothing_vector_host_function_matches_oracle():
         assert rc == 0
         assert np.array_equal(s, oracle.smoothing_vector(ax, aw if use_w else None, alpha))
     assert L.haq_smoothing_vector(ax.ctypes.data_as(C.c_void_p), None, 257, C.c_double(1.5), s.ctypes.data_as(C.c_void_p)) == -1
+
+
+def test_n_critical_host_function_matches_oracle():
+    rng = np.random.default_rng(5)
+    cases = [(10.0, 1.0, 0.5), (10.1, 1.0, 0.5), (9.9, 1.0, 0.5), (0.0, 1.0, 0.5), (5.0, 1.0, 1.0), (5.0, 0.5, 1.0),
+             (12.7e-3, 0.9e-3, 0.004e-3), (3.0, 0.25, 0.125)]
+    cases += [tuple(rng.uniform(0.01, 20.0, 3)) for _ in range(200)]
+    for t_e, lc, lg in cases:
+        assert haq.haq_offload_n_critical(t_e, lc, lg) == oracle.n_critical(t_e, lc, lg), (t_e, lc, lg)
+    import pytest
+    with pytest.raises(haq.HaqError):
+        haq.haq_offload_n_critical(-1.0, 1.0, 0.5)
+
+
+def test_select_experts_host_function_matches_oracle():
+    # the worked example of the oracle's pin, with dense frequency arrays
+    paths = [[((0, 2), 5), ((3, 5), 40), ((5, 1), 30)]]
+    freq = [[10, 30, 8, 45, 33, 70, 2, 31]]
+    assert haq.haq_select_experts(1, 8, 3, 2, paths, freq) == [[3, 5, 1, 4, 7]]
+    # random layers, ties included (integer frequencies from a small range)
+    rng = np.random.default_rng(6)
+    for trial in range(50):
+        L, E = int(rng.integers(1, 5)), int(rng.integers(2, 17))
+        top_k, supp = int(rng.integers(1, 5)), int(rng.integers(0, 4))
+        path_stats, expert_freq = [], []
+        for _ in range(L):
+            n_paths = int(rng.integers(0, 7))
+            path_stats.append([(tuple(int(e) for e in rng.choice(E, 2, replace=False)), int(rng.integers(0, 5)))
+                               for _ in range(n_paths)])
+            expert_freq.append([int(f) for f in rng.integers(0, 6, E)])
+        ref = oracle.select_experts(L, top_k, supp, path_stats, [list(enumerate(f)) for f in expert_freq])
+        got = haq.haq_select_experts(L, E, top_k, supp, path_stats, expert_freq)
+        assert got == ref, (trial, path_stats, expert_freq, top_k, supp)

@@ -402,3 +402,48 @@ def test_smoothing_search_full_size_fc1():
     assert np.array_equal(np.asarray(losses), losses_ref)
     assert best == best_ref == 1
     assert bits_equal(host(s), s_ref)
+
+
+# ------------------------------------------------------------------ LRU expert cache across calls (Section III.C.1c)
+def test_expert_cache_follows_lru_across_calls():
+    """Calls whose routing activates chosen subsets of the host-resident experts: hits, misses and the
+    final slot contents must follow a plain LRU cache, and every output must equal the all-resident one."""
+    E, H, I, n_slots = 8, 128, 320, 3
+    m = offline.small_moe(seed=71, T=40, H=H, I=I, E=E)
+    dev_experts = upload_experts(m["experts"])
+    host_ids = (2, 3, 4, 5, 6, 7)
+    mixed = _offload(dev_experts, host_ids)
+    X, s_in = dev(m["X"]), dev(m["s_in"])
+    # each call allows only a subset of experts (the others get a logit nobody can pick)
+    subsets = [(0, 2, 3), (2, 4), (0, 1), (5, 2), (3, 6, 7, 4), (2, 1), (7, 6, 5, 4, 3, 2), (2, 3)]
+    ctx = haq.haq_ctx_create(H, I, n_slots)
+    try:
+        trace, hits_total = [], 0
+        for sub in subsets:
+            logits = m["logits"].copy()
+            mask = np.ones(E, bool)
+            mask[list(sub)] = False
+            logits[:, mask] = -100
+            ref = haq.haq_moe_w8a8_ffn(X, dev(logits), s_in, dev_experts, I)
+            out, dbg = haq.haq_moe_w8a8_ffn(X, dev(logits), s_in, mixed, I, ctx=ctx, debug=True)
+            assert bits_equal(host(out), host(ref)), f"subset {sub}"
+            counts = host(dbg.counts)
+            trace += [e for e in range(E) if e in host_ids and counts[e] > 0]   # activated host experts, expert order
+        hit_flags, cache = oracle.lru_trace(trace, n_slots)
+        hits, misses, nbytes, keys = haq.haq_ctx_cache_stats(ctx)
+        assert hits == sum(hit_flags) and misses == len(trace) - sum(hit_flags) and hits > 0
+        per_expert = haq.haq_packed_bytes(H, 2 * I) + haq.haq_packed_bytes(I, H)
+        assert nbytes == misses * per_expert
+        cached = {k for k in keys[:n_slots] if k}
+        assert cached == {mixed[e].w13.data_ptr() for e in cache}
+        # after invalidation the next call misses again and still computes the same result
+        haq.haq_ctx_cache_invalidate(ctx)
+        logits = m["logits"].copy()
+        logits[:, [0, 1, 4, 5, 6, 7]] = -100
+        out = haq.haq_moe_w8a8_ffn(X, dev(logits), s_in, mixed, I, ctx=ctx)
+        assert bits_equal(host(out), host(haq.haq_moe_w8a8_ffn(X, dev(logits), s_in, dev_experts, I)))
+        h2, m2, _, _ = haq.haq_ctx_cache_stats(ctx)
+        assert (h2, m2) == (hits, misses + 2)
+    finally:
+        torch.cuda.synchronize()
+        haq.haq_ctx_destroy(ctx)
