@@ -338,3 +338,38 @@ def select_experts(num_layers: int, top_k: int, supplement_k: int, path_stats, e
             if e not in selected[layer]:
                 selected[layer].append(e)
     return selected
+
+
+# ---- Hessian-aware weight quantisation (Section III.B.2; Algorithm 1 step 2) -------------------
+def hessian(X: np.ndarray, s: np.ndarray | None, percdamp: float = 0.01) -> np.ndarray:
+    X = _c(X, np.float16)
+    T, K = X.shape
+    H = np.empty((K, K), np.float64)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_hessian(_p(X), C.c_int64(K), _p(s_), T, K, C.c_double(percdamp), _p(H))
+    return H
+
+
+def inverse_cholesky_upper(H: np.ndarray) -> np.ndarray:
+    H = _c(H, np.float64)
+    K = H.shape[0]
+    U = np.empty((K, K), np.float64)
+    rc = lib().oracle_inverse_cholesky_upper(_p(H), K, _p(U))
+    if rc != 0:
+        raise ValueError(f"the Hessian is not positive definite (pivot {rc - 1})")
+    return U
+
+
+def gptq(W: np.ndarray, s: np.ndarray | None, U: np.ndarray):
+    W = _c(W, np.float32)
+    K, N = W.shape
+    Wq = np.empty((K, N), np.int8)
+    sw = np.empty(N, np.float32)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_gptq(_p(W), _p(s_), _p(_c(U, np.float64)), K, N, _p(Wq), _p(sw))
+    return Wq, sw
+
+
+def hessian_quant_weight(X: np.ndarray, W: np.ndarray, s: np.ndarray | None, percdamp: float = 0.01):
+    """Q(W s) with error compensation along the input channels (Eq. 4-6): returns (Wq, sw)."""
+    return gptq(W, s, inverse_cholesky_upper(hessian(X, s, percdamp)))

@@ -433,4 +433,107 @@ double oracle_mse_f64(const uint16_t* Y, int64_t ldy, const double* Yref, int T,
     return total / ((double)T * (double)N);
 }
 
+// ---- Hessian-aware weight quantisation (Section III.B.2, Eq. 4-6; Algorithm 1 step 2) ---------
+// Everything here is binary64 and every sum has a stated order, so that an implementation
+// that performs the same operations gets the same bits.
+//
+// H = 2 Xs^T Xs over the calibration rows, Xs = X / s (the smoothed activations the layer
+// will see; the division is the binary32 one of the activation path), sums over the tokens
+// in ascending order with one fused multiply-add per term.  A channel that never fires
+// (H_jj = 0) gets H_jj = 1.  Damping: percdamp times the mean of the diagonal (summed in
+// index order) is added to the diagonal, the usual safeguard for the inversion.
+void oracle_hessian(const uint16_t* X, int64_t ldx, const float* s, int T, int K, double percdamp, double* H) {
+    std::vector<double> xs((size_t)T * K);
+    for (int t = 0; t < T; ++t)
+        for (int k = 0; k < K; ++k) {
+            const float x = half_to_float(X[(size_t)t * ldx + k]);
+            xs[(size_t)t * K + k] = (double)(s ? x / s[k] : x);
+        }
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int j = 0; j < K; ++j)
+        for (int l = 0; l < K; ++l) {
+            double acc = 0.0;
+            for (int t = 0; t < T; ++t) acc = std::fma(xs[(size_t)t * K + j], xs[(size_t)t * K + l], acc);
+            H[(size_t)j * K + l] = 2.0 * acc;
+        }
+    for (int j = 0; j < K; ++j)
+        if (H[(size_t)j * K + j] == 0.0) H[(size_t)j * K + j] = 1.0;
+    double tr = 0.0;
+    for (int j = 0; j < K; ++j) tr += H[(size_t)j * K + j];
+    const double damp = percdamp * (tr / (double)K);
+    for (int j = 0; j < K; ++j) H[(size_t)j * K + j] += damp;
+}
+
+// U upper triangular with H^-1 = U^T U (the Cholesky reformulation: row i of U is, up to the
+// factor U_ii, row i of the inverse Hessian of the channels not yet quantised, i.e. what
+// Eq. 5-6 need at step i).  Route: flip H (reverse both index orders), Cholesky-factorise
+// the flipped matrix, A = L L^T, invert the triangle, M = L^-1, and flip back: U = flip(M).
+//   L_jj = sqrt(a_jj - sum_{k<j} L_jk^2),  L_ij = (a_ij - sum_{k<j} L_ik L_jk) / L_jj,
+//   M_jj = 1 / L_jj,  M_ij = -(sum_{j<=k<i} L_ik M_kj) / L_ii,
+// every sum accumulated from the leading term with one fused multiply-add per k ascending.
+// Returns 0, or j + 1 if the pivot of column j is not positive.
+int oracle_inverse_cholesky_upper(const double* H, int K, double* U) {
+    std::vector<double> L((size_t)K * K, 0.0), M((size_t)K * K, 0.0);
+    auto A = [&](int i, int j) { return H[(size_t)(K - 1 - i) * K + (K - 1 - j)]; };
+    for (int j = 0; j < K; ++j) {
+        double d = A(j, j);
+        for (int k = 0; k < j; ++k) d = std::fma(-L[(size_t)j * K + k], L[(size_t)j * K + k], d);
+        if (!(d > 0.0)) return j + 1;
+        const double ljj = std::sqrt(d);
+        L[(size_t)j * K + j] = ljj;
+#pragma omp parallel for schedule(static)
+        for (int i = j + 1; i < K; ++i) {
+            double v = A(i, j);
+            for (int k = 0; k < j; ++k) v = std::fma(-L[(size_t)i * K + k], L[(size_t)j * K + k], v);
+            L[(size_t)i * K + j] = v / ljj;
+        }
+    }
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int j = 0; j < K; ++j) {
+        M[(size_t)j * K + j] = 1.0 / L[(size_t)j * K + j];
+        for (int i = j + 1; i < K; ++i) {
+            double v = 0.0;
+            for (int k = j; k < i; ++k) v = std::fma(-L[(size_t)i * K + k], M[(size_t)k * K + j], v);
+            M[(size_t)i * K + j] = v / L[(size_t)i * K + i];
+        }
+    }
+    for (int a = 0; a < K; ++a)
+        for (int b = 0; b < K; ++b) U[(size_t)a * K + b] = M[(size_t)(K - 1 - a) * K + (K - 1 - b)];
+    return 0;
+}
+
+// Input channels in order (Section III.B.2 steps 1-3).  The per-output-channel grid is the
+// one of plain rounding, scale_n = max_k |s_k W_kn| / 127 in binary32; the working copy of
+// the folded weight is binary64.  Channel i: code = clamp(rne(w_in / scale_n)), the error
+// e_n = (w_in - code * scale_n) / U_ii, and every later channel j > i is compensated,
+// w_jn <- w_jn - e_n U_ij (one fused multiply-add): Eq. 6 with row i of the remaining
+// inverse Hessian written through U.  Output channels are independent of each other.
+void oracle_gptq(const float* W, const float* s, const double* U, int K, int N, int8_t* Wq, float* col_scale) {
+    std::vector<float> a(N, 0.0f);
+    for (int k = 0; k < K; ++k) {
+        const float sk = s ? s[k] : 1.0f;
+        for (int n = 0; n < N; ++n) a[n] = std::fmax(a[n], std::fabs(sk * W[(size_t)k * N + n]));
+    }
+    for (int n = 0; n < N; ++n) col_scale[n] = a[n] / 127.0f;
+#pragma omp parallel
+    {
+        std::vector<double> w(K);
+#pragma omp for schedule(static)
+        for (int n = 0; n < N; ++n) {
+            for (int k = 0; k < K; ++k) w[k] = (double)((s ? s[k] : 1.0f) * W[(size_t)k * N + n]);
+            const double scale = (double)col_scale[n];
+            for (int i = 0; i < K; ++i) {
+                double code = 0.0;
+                if (a[n] != 0.0f) {
+                    code = std::nearbyint(w[i] / scale);
+                    code = std::fmin(std::fmax(code, -127.0), 127.0);
+                }
+                Wq[(size_t)i * N + n] = (int8_t)code;
+                const double err = (w[i] - code * scale) / U[(size_t)i * K + i];
+                for (int j = i + 1; j < K; ++j) w[j] = std::fma(-err, U[(size_t)i * K + j], w[j]);
+            }
+        }
+    }
+}
+
 }  // extern "C"

@@ -494,6 +494,113 @@ def test_smoothing_search_finds_the_minimum_on_outlier_activations():
     assert np.isclose(losses_b[0], mse_h, rtol=1e-12)
 
 
+# ----------------------------------------------------------------- Hessian-aware weight quantisation (Eq. 4-6)
+def _correlated_activations(seed, T, K, rank):
+    """Activations with strong correlation between channels (a few latent factors + noise)."""
+    rng = np.random.default_rng(seed)
+    Z = rng.standard_normal((T, rank))
+    A = rng.standard_normal((rank, K))
+    return (Z @ A + 0.1 * rng.standard_normal((T, K))).astype(np.float16)
+
+
+def test_hessian_is_twice_the_gram_matrix_plus_damping():
+    X = _correlated_activations(31, 90, 48, 6)
+    X[:, 7] = 0                                            # a channel that never fires
+    s = np.exp(np.random.default_rng(31).normal(0, 0.5, 48)).astype(F32)
+    H = oracle.hessian(X, s, 0.01)
+    Xs = (X.astype(F32) / s).astype(np.float64)            # the binary32 division of the activation path
+    G = 2.0 * Xs.T @ Xs                                    # library product
+    G[7, 7] = 1.0
+    G += 0.01 * np.mean(np.diag(G)) * np.eye(48)
+    assert np.allclose(H, G, rtol=1e-12, atol=1e-12) and np.array_equal(H, H.T)
+    assert np.allclose(oracle.hessian(X, None, 0.0)[np.arange(48) != 7][:, np.arange(48) != 7],
+                       (2.0 * X.astype(np.float64).T @ X.astype(np.float64))[np.arange(48) != 7][:, np.arange(48) != 7],
+                       rtol=1e-12)
+
+
+def test_inverse_cholesky_upper_against_library_routines():
+    X = _correlated_activations(32, 150, 40, 5)
+    H = oracle.hessian(X, None, 0.01)
+    U = oracle.inverse_cholesky_upper(H)
+    assert np.array_equal(U, np.triu(U)) and np.all(np.diag(U) > 0)
+    assert np.allclose(U.T @ U @ H, np.eye(40), atol=1e-8)
+    assert np.allclose(U, np.linalg.cholesky(np.linalg.inv(H)).T, rtol=1e-8, atol=1e-12)
+    # row i of U is row i of the inverse Hessian of the remaining channels i.., up to the factor U_ii
+    for i in (0, 3, 17, 39):
+        HF_inv = np.linalg.inv(H[i:, i:])
+        assert np.allclose(U[i, i:] * U[i, i], HF_inv[0], rtol=1e-7, atol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.inverse_cholesky_upper(np.array([[1.0, 2.0], [2.0, 1.0]]))   # indefinite
+
+
+def test_gptq_two_channel_closed_form():
+    # K = 2, one output channel: Eq. 6 by hand with the explicit inverse
+    H = np.array([[4.0, 1.0], [1.0, 3.0]])
+    U = oracle.inverse_cholesky_upper(H)
+    W = np.array([[0.30], [-1.27]], F32)                   # absmax 1.27 -> scale 0.01
+    Wq, sw = oracle.gptq(W, None, U)
+    scale = float(sw[0])
+    assert np.isclose(scale, 1.27 / 127)
+    q0 = np.rint(np.float64(W[0, 0]) / scale)
+    Hinv = np.linalg.inv(H)
+    w1 = np.float64(W[1, 0]) - (np.float64(W[0, 0]) - q0 * scale) / Hinv[0, 0] * Hinv[1, 0]
+    assert Wq[0, 0] == q0 and Wq[1, 0] == np.clip(np.rint(w1 / scale), -127, 127)
+    # a case where the compensation moves a code.  A third, uncorrelated channel pins the scale to 0.01;
+    # channel 0 rounds 1.49 -> 1 and leaves +0.0049, of which -Hinv10/Hinv00 = 1/3 moves to channel 1:
+    # 5.40 + 0.163 = 5.563 rounds to 6, where plain rounding gives 5
+    H3 = np.array([[4.0, 1.0, 0.0], [1.0, 3.0, 0.0], [0.0, 0.0, 2.0]])
+    W3 = np.array([[0.0149], [0.0540], [1.27]], F32)
+    Wq3, sw3 = oracle.gptq(W3, None, oracle.inverse_cholesky_upper(H3))
+    assert np.isclose(float(sw3[0]), 0.01)
+    assert Wq3[:, 0].tolist() == [1, 6, 127]
+    assert oracle.quant_weight(W3, None)[0][:, 0].tolist() == [1, 5, 127]
+
+
+def test_gptq_equals_plain_rounding_for_uncorrelated_channels():
+    # orthogonal activation columns: H is diagonal, U is diagonal, nothing is compensated
+    rng = np.random.default_rng(33)
+    Q, _ = np.linalg.qr(rng.standard_normal((64, 32)))
+    X = np.zeros((64, 32), np.float16)
+    X[np.arange(32), np.arange(32)] = (rng.uniform(1, 3, 32)).astype(np.float16)   # one token per channel
+    W = rng.standard_normal((32, 24)).astype(F32)
+    s = np.exp(rng.normal(0, 0.3, 32)).astype(F32)
+    Wq, sw = oracle.hessian_quant_weight(X, W, s)
+    Wr, swr = oracle.quant_weight(W, s)
+    assert np.array_equal(Wq, Wr) and np.array_equal(sw, swr)
+
+
+def test_gptq_matches_the_definition_with_explicit_remaining_inverse():
+    # Eq. 5-6 verbatim on a tiny layer: at every step the inverse Hessian of the channels not yet
+    # quantised is recomputed with a library inverse; the codes must agree
+    X = _correlated_activations(34, 60, 12, 3)
+    W = (np.random.default_rng(34).standard_normal((12, 5)) * 0.05).astype(F32)
+    H = oracle.hessian(X, None, 0.01)
+    Wq, sw = oracle.gptq(W, None, oracle.inverse_cholesky_upper(H))
+    Wd = W.astype(np.float64).copy()
+    ref = np.zeros((12, 5), np.int8)
+    for i in range(12):
+        HF_inv = np.linalg.inv(H[i:, i:])                  # F = {i, ..., 11}
+        for n in range(5):
+            q = np.clip(np.rint(Wd[i, n] / float(sw[n])), -127, 127)
+            ref[i, n] = q
+            delta = -(Wd[i, n] - q * float(sw[n])) / HF_inv[0, 0] * HF_inv[:, 0]
+            Wd[i + 1:, n] += delta[1:]
+    assert np.array_equal(Wq, ref)
+
+
+def test_gptq_lowers_the_output_error_on_correlated_activations():
+    # the objective of Eq. 4 against plain rounding (Table I's ordering of GPTQ-style vs RTN in proxy form)
+    X = _correlated_activations(35, 256, 128, 8)
+    W = hi.gaussian_weight(35, 0, 128, 96)
+    Wq, sw = oracle.hessian_quant_weight(X, W, None)
+    Wr, swr = oracle.quant_weight(W, None)
+    Xd, Wd = X.astype(np.float64), W.astype(np.float64)
+    err_g = np.sum((Xd @ Wd - Xd @ (Wq * sw.astype(np.float64))) ** 2)
+    err_r = np.sum((Xd @ Wd - Xd @ (Wr * swr.astype(np.float64))) ** 2)
+    assert err_g < 0.6 * err_r
+    assert np.array_equal(sw, swr) and np.abs(Wq.astype(int)).max() <= 127
+
+
 # ----------------------------------------------------------------- offload scheduler (Section III.C)
 def test_lru_trace_textbook_reference_string():
     # the classic 20-reference string with 3 frames: 12 misses under LRU (15 under FIFO, 9 under OPT)
