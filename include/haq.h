@@ -182,6 +182,43 @@ int32_t haq_smoothing_search(const void* x_fp16, int64_t ldx, const float* w, in
                              float* s_best, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Hessian-aware weight quantisation (Section III.B.2, Eq. 4-6; Algorithm 1 step
+ * 2), offline: Q(W s) with the rounding error of every input channel pushed onto
+ * the channels not yet quantised, so that the layer's output on the calibration
+ * activations, not the weight itself, is preserved (Eq. 4).
+ *
+ *   H = 2 Xs^T Xs over the T calibration rows, Xs = X / s (binary32 division as
+ *   on the activation path; s NULL = ones); a channel with H_jj = 0 gets H_jj =
+ *   1; percdamp * mean(diag H) is added to the diagonal.
+ *   U = upper triangular with H^-1 = U^T U: row i of U is, up to U_ii, row i of
+ *   the inverse Hessian of the channels i, i+1, ... (what Eq. 5-6 need at step
+ *   i; the Cholesky reformulation the paper mentions).
+ *   Grid: scale_n = max_k |s_k W_kn| / 127 as haq_quant_weight.  Input channels
+ *   i = 0 .. K-1 in order: code = clamp(rne(w_in / scale_n)), e_n = (w_in -
+ *   code scale_n) / U_ii, and w_jn -= e_n U_ij for every j > i (Eq. 6).
+ * All arithmetic is binary64 with one fused multiply-add per term and sums in
+ * ascending order of the token / eliminated column / quantised channel, so the
+ * result is defined bit for bit.
+ *
+ * x_fp16 [T x K] device, w fp32 [K x N] device, s [K] device or NULL.  Outputs
+ * wq int8 [K x N] dense and w_scale [N] (device), to be packed with
+ * haq_pack_weight.  K < 65536.  The calls synchronise the stream once (the
+ * factorisation reports a non-positive pivot as HAQ_ERR_INVALID_ARG).
+ * Workspace: haq_hessian_quant_workspace_bytes(K, N) bytes, 256-byte aligned
+ * (three K x K and one K x N binary64 matrices).
+ * Building blocks: haq_hessian_f64 (H [K x K] device), and
+ * haq_inverse_cholesky_upper_f64 (U [K x K] device from H; U may alias H).     */
+size_t haq_hessian_quant_workspace_bytes(int32_t K, int32_t N);
+size_t haq_inverse_cholesky_workspace_bytes(int32_t K);
+int32_t haq_hessian_f64(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K, double percdamp,
+                        double* H, void* stream);
+int32_t haq_inverse_cholesky_upper_f64(const double* H, int32_t K, double* U, void* workspace,
+                                       size_t workspace_bytes, void* stream);
+int32_t haq_hessian_quant_weight(const void* x_fp16, int64_t ldx, int32_t T, const float* w, const float* s,
+                                 int32_t K, int32_t N, double percdamp, int8_t* wq, float* w_scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Top-2 routed SwiGLU expert FFN with W8A8 experts.
  *
  * Per token t: top-2 experts by router logit (lowest index wins ties); gate

@@ -22,6 +22,8 @@ __all__ = [
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
+    "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
+    "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
@@ -39,6 +41,8 @@ EXPORTED_SYMBOLS = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
+    "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
+    "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
 ]
 
 
@@ -71,7 +75,8 @@ def lib() -> C.CDLL:
         L = C.CDLL(LIB_PATH)
         L.haq_last_error.restype = C.c_char_p
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
-                  "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes"):
+                  "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes", "haq_hessian_quant_workspace_bytes",
+                  "haq_inverse_cholesky_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -384,3 +389,40 @@ def haq_select_experts(num_layers: int, experts_per_layer: int, top_k: int, supp
                                     (C.c_int32 * max(1, len(flat)))(*flat), path_len, (C.c_double * max(1, len(freq)))(*freq),
                                     (C.c_double * len(ef))(*ef), sel, nsel))
     return [[int(sel[l * cap + i]) for i in range(nsel[l])] for l in range(num_layers)]
+
+
+# ---- Hessian-aware weight quantisation (Algorithm 1 step 2) ---------------------------------
+def haq_hessian_quant_workspace_bytes(K: int, N: int) -> int:
+    return int(lib().haq_hessian_quant_workspace_bytes(K, N))
+
+
+def haq_inverse_cholesky_workspace_bytes(K: int) -> int:
+    return int(lib().haq_inverse_cholesky_workspace_bytes(K))
+
+
+def haq_hessian_f64(x, s, percdamp: float = 0.01):
+    T, K = x.shape
+    H = torch.empty((K, K), dtype=torch.float64, device=x.device)
+    _check(lib().haq_hessian_f64(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), T, K, C.c_double(percdamp), _ptr(H), _stream()))
+    return H
+
+
+def haq_inverse_cholesky_upper_f64(H):
+    K = H.shape[0]
+    U = torch.empty((K, K), dtype=torch.float64, device=H.device)
+    ws = _ws(int(lib().haq_inverse_cholesky_workspace_bytes(K)), H.device)
+    _check(lib().haq_inverse_cholesky_upper_f64(_ptr(H), K, _ptr(U), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return U
+
+
+def haq_hessian_quant_weight(x, w, s, percdamp: float = 0.01, *, workspace=None):
+    """x fp16 [T,K] calibration activations, w fp32 [K,N], s [K] or None -> (wq int8 [K,N], w_scale [N])."""
+    T, K = x.shape
+    N = w.shape[1]
+    wq = torch.empty((K, N), dtype=torch.int8, device=w.device)
+    sw = torch.empty((N,), dtype=torch.float32, device=w.device)
+    if workspace is None:
+        workspace = _ws(int(lib().haq_hessian_quant_workspace_bytes(K, N)), w.device)
+    _check(lib().haq_hessian_quant_weight(_ptr(x), C.c_int64(x.stride(0)), T, _ptr(w), _ptr(s), K, N, C.c_double(percdamp),
+                                          _ptr(wq), _ptr(sw), _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
+    return wq, sw

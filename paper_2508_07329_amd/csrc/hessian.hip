@@ -1,0 +1,442 @@
+// Hessian-aware weight quantisation (Section III.B.2, Eq. 4-6; Algorithm 1 step 2), offline.
+//
+// Everything is binary64 and every accumulation is a chain of fused multiply-adds in a stated
+// order (tokens ascending for the Hessian, eliminated columns ascending for the factorisation,
+// quantised input channels ascending for the compensation).  Blocking only regroups which
+// work-item applies a link of a chain and when; it never reorders a chain, so the bits do not
+// depend on the tile sizes below.
+//
+//   H  = 2 Xs^T Xs + damping                       hessian_kernel, hessian_finish_kernel
+//   A  = flip(H) = L L^T                           chol_panel_kernel, chol_trail_kernel
+//   M  = L^-1 (lower)                              tri_inverse_kernel
+//   U  = flip(M): upper, H^-1 = U^T U              flip_kernel
+//   channels i ascending: code, error, compensate  gptq_block_kernel, gptq_update_kernel
+#include "haq_common.h"
+
+namespace haq {
+
+namespace {
+
+constexpr int HT = 64, HK = 16;  // Hessian tile (outputs) and token step
+constexpr int PB = 32;           // Cholesky panel width
+constexpr int GB = 32;           // input channels quantised per compensation block
+
+// ---- H = 2 Xs^T Xs -------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void hessian_kernel(const __half* x, int64_t ldx, const float* s, int T, int K, double* H) {
+    __shared__ double xa[HK][HT + 1];
+    __shared__ double xb[HK][HT + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid % 16, ty = tid / 16;
+    const int j0 = blockIdx.y * HT, l0 = blockIdx.x * HT;
+    double acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int t0 = 0; t0 < T; t0 += HK) {
+        const int tt = tid / 16, c = (tid % 16) * 4;
+        const int t = t0 + tt;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ja = j0 + c + i, lb = l0 + c + i;
+            double va = 0.0, vb = 0.0;
+            if (t < T && ja < K) {
+                const float v = h2f(x[(size_t)t * ldx + ja]);
+                va = (double)(s ? v / s[ja] : v);
+            }
+            if (t < T && lb < K) {
+                const float v = h2f(x[(size_t)t * ldx + lb]);
+                vb = (double)(s ? v / s[lb] : v);
+            }
+            xa[tt][c + i] = va;
+            xb[tt][c + i] = vb;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < HK; ++kk) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) av[i] = xa[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = xb[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fma(av[i], bv[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = j0 + ty * 4 + i;
+        if (j >= K) continue;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int l = l0 + tx * 4 + jj;
+            if (l < K) H[(size_t)j * K + l] = 2.0 * acc[i][jj];
+        }
+    }
+}
+
+// Dead channels get a unit diagonal; damping = percdamp * mean(diag), the diagonal summed in index order.
+__global__ __launch_bounds__(256) void hessian_finish_kernel(double* H, int K, double percdamp) {
+    __shared__ double part[1024];
+    __shared__ double damp_s;
+    double tr = 0.0;
+    for (int j0 = 0; j0 < K; j0 += 1024) {
+        for (int i = threadIdx.x; i < 1024; i += 256) {
+            const int j = j0 + i;
+            double d = 0.0;
+            if (j < K) {
+                d = H[(size_t)j * K + j];
+                if (d == 0.0) {
+                    d = 1.0;
+                    H[(size_t)j * K + j] = 1.0;
+                }
+            }
+            part[i] = d;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int lim = min(1024, K - j0);
+            for (int i = 0; i < lim; ++i) tr += part[i];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) damp_s = percdamp * (tr / (double)K);
+    __syncthreads();
+    const double damp = damp_s;
+    for (int j = threadIdx.x; j < K; j += 256) H[(size_t)j * K + j] += damp;
+}
+
+// A(i, j) = H(K-1-i, K-1-j); also used to turn M into U.
+__global__ void flip_kernel(const double* src, int K, double* dst) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x, i = blockIdx.y;
+    if (j < K) dst[(size_t)i * K + j] = src[(size_t)(K - 1 - i) * K + (K - 1 - j)];
+}
+
+// ---- Cholesky, right-looking in panels of PB columns ------------------------------------------
+// Panel kernel: every work-group first factorises the PB x PB diagonal block in LDS (redundantly:
+// it is tiny), then its threads each take one row below the block and solve it against the block,
+// column by column: v = A_ic; v -= L_ik L_ck for the panel's earlier columns k ascending; L_ic = v / L_cc.
+// Work-group 0 leaves the factorised diagonal block in `dblock` (it cannot go to A here: the other
+// work-groups may still be reading the unfactorised block); chol_store_diag_kernel moves it afterwards.
+// status: first non-positive pivot + 1.
+__global__ __launch_bounds__(256) void chol_panel_kernel(double* A, int K, int j0, double* dblock, int* status) {
+    __shared__ double D[PB][PB + 1];
+    const int tid = threadIdx.x;
+    const int pb = min(PB, K - j0);
+    for (int i = tid; i < PB * PB; i += 256) {
+        const int r = i / PB, c = i % PB;
+        D[r][c] = (r < pb && c <= r) ? A[(size_t)(j0 + r) * K + j0 + c] : 0.0;
+    }
+    __syncthreads();
+    for (int c = 0; c < pb; ++c) {
+        // column c of the block: rows r >= c, each by one thread (the chain over k < c is sequential)
+        if (tid >= c && tid < pb) {
+            const int r = tid;
+            double v = D[r][c];
+            for (int k = 0; k < c; ++k) v = __builtin_fma(-D[r][k], D[c][k], v);
+            D[r][c] = v;  // not yet divided
+        }
+        __syncthreads();
+        if (tid == c) {
+            const double d = D[c][c];
+            if (!(d > 0.0) && blockIdx.x == 0) atomicCAS(status, 0, j0 + c + 1);
+            D[c][c] = sqrt(d);
+        }
+        __syncthreads();
+        if (tid > c && tid < pb) D[tid][c] = D[tid][c] / D[c][c];
+        __syncthreads();
+    }
+    if (blockIdx.x == 0)
+        for (int i = tid; i < PB * PB; i += 256) dblock[i] = D[i / PB][i % PB];
+    // rows below the diagonal block
+    const int i = j0 + pb + blockIdx.x * 256 + tid;
+    if (i < K) {
+        double row[PB];
+#pragma unroll
+        for (int c = 0; c < PB; ++c) row[c] = c < pb ? A[(size_t)i * K + j0 + c] : 0.0;
+#pragma unroll
+        for (int c = 0; c < PB; ++c) {
+            if (c < pb) {
+                double v = row[c];
+#pragma unroll
+                for (int k = 0; k < PB; ++k)
+                    if (k < c) v = __builtin_fma(-row[k], D[c][k], v);
+                row[c] = v / D[c][c];
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < PB; ++c)
+            if (c < pb) A[(size_t)i * K + j0 + c] = row[c];
+    }
+}
+
+__global__ __launch_bounds__(256) void chol_store_diag_kernel(double* A, int K, int j0, const double* dblock) {
+    const int pb = min(PB, K - j0);
+    for (int i = threadIdx.x; i < PB * PB; i += 256) {
+        const int r = i / PB, c = i % PB;
+        if (r < pb && c <= r) A[(size_t)(j0 + r) * K + j0 + c] = dblock[i];
+    }
+}
+
+// Trailing update after a panel: for i >= l >= j0 + PB: A_il -= L_ik L_lk, k over the panel ascending.
+// 64 x 64 tiles of the lower triangle, 4 x 4 elements per thread.
+__global__ __launch_bounds__(256) void chol_trail_kernel(double* A, int K, int j0) {
+    const int base = j0 + PB;
+    const int ti = blockIdx.y, tl = blockIdx.x;
+    if (tl > ti) return;  // only tiles that touch the lower triangle
+    __shared__ double Li[64][PB + 1];
+    __shared__ double Ll[64][PB + 1];
+    const int tid = threadIdx.x;
+    const int i0 = base + ti * 64, l0 = base + tl * 64;
+    for (int e = tid; e < 64 * PB; e += 256) {
+        const int r = e / PB, c = e % PB;
+        Li[r][c] = (i0 + r < K) ? A[(size_t)(i0 + r) * K + j0 + c] : 0.0;
+        Ll[r][c] = (l0 + r < K) ? A[(size_t)(l0 + r) * K + j0 + c] : 0.0;
+    }
+    __syncthreads();
+    const int tx = tid % 16, ty = tid / 16;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int i = i0 + ty * 4 + a;
+        if (i >= K) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int l = l0 + tx * 4 + b;
+            if (l > i || l >= K) continue;
+            double v = A[(size_t)i * K + l];
+#pragma unroll
+            for (int k = 0; k < PB; ++k) v = __builtin_fma(-Li[ty * 4 + a][k], Ll[tx * 4 + b][k], v);
+            A[(size_t)i * K + l] = v;
+        }
+    }
+}
+
+// ---- M = L^-1, one thread per column ------------------------------------------------------------
+// M_jj = 1 / L_jj; M_ij = -(sum_{j <= k < i} L_ik M_kj) / L_ii, the sum a chain over k ascending.
+// The k loop runs over the same k for all lanes of a wave (lanes whose column starts later are
+// masked), so the loads of M are coalesced and L_ik is one address per wave.
+__global__ __launch_bounds__(64) void tri_inverse_kernel(const double* L, int K, double* M) {
+    __shared__ double lrow[512];
+    const int j = blockIdx.x * 64 + threadIdx.x;
+    const int jmin = blockIdx.x * 64;
+    const bool on = j < K;
+    for (int i = jmin; i < K; ++i) {
+        double v = 0.0;
+        for (int k0 = jmin; k0 < i; k0 += 512) {  // row i of L, 512 entries at a time through LDS
+            const int lim = min(512, i - k0);
+            __syncthreads();
+            for (int e = threadIdx.x; e < lim; e += 64) lrow[e] = L[(size_t)i * K + k0 + e];
+            __syncthreads();
+            if (on) {
+                for (int e = 0; e < lim; ++e) {
+                    const int k = k0 + e;
+                    if (k >= j) v = __builtin_fma(-lrow[e], M[(size_t)k * K + j], v);
+                }
+            }
+        }
+        if (on) {
+            const double lii = L[(size_t)i * K + i];
+            if (i == j) M[(size_t)i * K + j] = 1.0 / lii;
+            else if (i > j) M[(size_t)i * K + j] = v / lii;
+            else M[(size_t)i * K + j] = 0.0;
+        }
+    }
+    if (on)
+        for (int i = 0; i < jmin; ++i) M[(size_t)i * K + j] = 0.0;
+}
+
+// ---- the quantise-and-compensate sweep ------------------------------------------------------------
+__global__ void fold_weight_kernel(const float* w, const float* s, int K, int N, double* w64) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x, k = blockIdx.y;
+    if (n < N) w64[(size_t)k * N + n] = (double)((s ? s[k] : 1.0f) * w[(size_t)k * N + n]);
+}
+
+// Channels b0 .. b0 + GB - 1, one thread per output channel n: code, error, compensation of the
+// block's later channels; the errors go to err [GB x N] for the rows below the block.
+__global__ __launch_bounds__(64) void gptq_block_kernel(double* w64, const double* U, const float* scale, int K, int N, int b0,
+                                                        int8_t* wq, double* err) {
+    __shared__ double Ub[GB][GB + 1];
+    const int gb = min(GB, K - b0);
+    for (int e = threadIdx.x; e < GB * GB; e += 64) {
+        const int r = e / GB, c = e % GB;
+        Ub[r][c] = (r < gb && c < gb) ? U[(size_t)(b0 + r) * K + b0 + c] : 0.0;
+    }
+    __syncthreads();
+    const int n = blockIdx.x * 64 + threadIdx.x;
+    if (n >= N) return;
+    const float sc_f = scale[n];
+    const double sc = (double)sc_f;
+    double w[GB];
+#pragma unroll
+    for (int i = 0; i < GB; ++i) w[i] = i < gb ? w64[(size_t)(b0 + i) * N + n] : 0.0;
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+        if (i < gb) {
+            double code = 0.0;
+            if (sc_f != 0.0f) {
+                code = __builtin_rint(w[i] / sc);
+                code = fmin(fmax(code, -127.0), 127.0);
+            }
+            wq[(size_t)(b0 + i) * N + n] = (int8_t)code;
+            const double e = (w[i] - code * sc) / Ub[i][i];
+            err[(size_t)i * N + n] = e;
+#pragma unroll
+            for (int j = 0; j < GB; ++j)
+                if (j > i && j < gb) w[j] = __builtin_fma(-e, Ub[i][j], w[j]);
+        }
+    }
+}
+
+// Rows j >= b0 + GB: w_jn -= err_in U_ij for the block's channels i ascending.  64 rows x 64
+// output channels per work-group, 4 x 4 per thread.
+__global__ __launch_bounds__(256) void gptq_update_kernel(double* w64, const double* U, const double* err, int K, int N, int b0) {
+    __shared__ double Es[GB][64 + 1];  // [i][n]
+    __shared__ double Us[GB][64 + 1];  // [i][j]
+    const int tid = threadIdx.x;
+    const int r0 = b0 + GB + blockIdx.y * 64, n0 = blockIdx.x * 64;
+    for (int e = tid; e < GB * 64; e += 256) {
+        const int i = e / 64, c = e % 64;
+        Es[i][c] = (n0 + c < N) ? err[(size_t)i * N + n0 + c] : 0.0;
+        Us[i][c] = (r0 + c < K) ? U[(size_t)(b0 + i) * K + r0 + c] : 0.0;
+    }
+    __syncthreads();
+    const int tx = tid % 16, ty = tid / 16;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int j = r0 + ty * 4 + a;
+        if (j >= K) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int n = n0 + tx * 4 + b;
+            if (n >= N) continue;
+            double v = w64[(size_t)j * N + n];
+#pragma unroll
+            for (int i = 0; i < GB; ++i) v = __builtin_fma(-Es[i][tx * 4 + b], Us[i][ty * 4 + a], v);
+            w64[(size_t)j * N + n] = v;
+        }
+    }
+}
+
+struct HessWs {
+    double *H, *A, *M, *w64, *err;
+    int* status;
+    size_t bytes;
+};
+
+HessWs carve_hess(void* ws, int K, int N) {
+    uint8_t* base = (uint8_t*)ws;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        void* p = base ? base + off : nullptr;
+        off += (size_t)round_up((int64_t)bytes, 256);
+        return p;
+    };
+    HessWs w;
+    w.H = (double*)take((size_t)K * K * 8);
+    w.A = (double*)take((size_t)K * K * 8);
+    w.M = (double*)take((size_t)K * K * 8);
+    w.w64 = (double*)take((size_t)K * N * 8);
+    w.err = (double*)take((size_t)GB * N * 8);
+    w.status = (int*)take(64 + PB * PB * 8);
+    w.bytes = off;
+    return w;
+}
+
+}  // namespace
+
+}  // namespace haq
+
+using namespace haq;
+
+extern "C" {
+
+int32_t haq_hessian_f64(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K, double percdamp, double* H,
+                        void* stream) {
+    if (T <= 0 || K <= 0 || !(percdamp >= 0.0)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_hessian_f64: T=%d K=%d percdamp=%g", T, K, percdamp);
+    if (!x_fp16 || !H || ldx < K) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_hessian_f64: null buffer or ldx=%lld", (long long)ldx);
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(hessian_kernel, dim3(cdiv(K, HT), cdiv(K, HT)), dim3(256), 0, st, (const __half*)x_fp16, ldx, s, T, K, H);
+    hipLaunchKernelGGL(hessian_finish_kernel, dim3(1), dim3(256), 0, st, H, K, percdamp);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+size_t haq_inverse_cholesky_workspace_bytes(int32_t K) {
+    if (K <= 0) return 0;
+    return 2 * (size_t)round_up((int64_t)K * K * 8, 256) + 64 + PB * PB * 8;
+}
+
+// H may alias U: H is read once, into A, before anything else runs.
+static int32_t inverse_cholesky_upper(const double* H, int K, double* U, double* A, double* M, int* status, hipStream_t st) {
+    double* dblock = reinterpret_cast<double*>(status) + 8;  // PB x PB doubles behind the status word
+    HAQ_CHECK_HIP(hipMemsetAsync(status, 0, sizeof(int), st));
+    hipLaunchKernelGGL(flip_kernel, dim3(cdiv(K, 256), K), dim3(256), 0, st, H, K, A);
+    for (int j0 = 0; j0 < K; j0 += PB) {
+        const int pb = K - j0 < PB ? K - j0 : PB;
+        const int below = K - j0 - pb;
+        hipLaunchKernelGGL(chol_panel_kernel, dim3(below > 0 ? cdiv(below, 256) : 1), dim3(256), 0, st, A, K, j0, dblock, status);
+        hipLaunchKernelGGL(chol_store_diag_kernel, dim3(1), dim3(256), 0, st, A, K, j0, (const double*)dblock);
+        if (below > 0) {
+            const int nt = cdiv(below, 64);
+            hipLaunchKernelGGL(chol_trail_kernel, dim3(nt, nt), dim3(256), 0, st, A, K, j0);
+        }
+    }
+    hipLaunchKernelGGL(tri_inverse_kernel, dim3(cdiv(K, 64)), dim3(64), 0, st, (const double*)A, K, M);
+    hipLaunchKernelGGL(flip_kernel, dim3(cdiv(K, 256), K), dim3(256), 0, st, (const double*)M, K, U);
+    HAQ_CHECK_HIP(hipGetLastError());
+    int host_status = 0;
+    HAQ_CHECK_HIP(hipMemcpyAsync(&host_status, status, sizeof(int), hipMemcpyDeviceToHost, st));
+    HAQ_CHECK_HIP(hipStreamSynchronize(st));
+    if (host_status != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "the Hessian is not positive definite (pivot %d of the flipped matrix)", host_status - 1);
+    return HAQ_OK;
+}
+
+int32_t haq_inverse_cholesky_upper_f64(const double* H, int32_t K, double* U, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+    if (K <= 0 || K > 65535 || !H || !U) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_inverse_cholesky_upper_f64: K=%d or null buffer", K);
+    if (!workspace || workspace_bytes < haq_inverse_cholesky_workspace_bytes(K) || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_inverse_cholesky_upper_f64: workspace of %zu bytes (256-byte aligned) needed, got %zu",
+                 haq_inverse_cholesky_workspace_bytes(K), workspace_bytes);
+    const size_t mat = (size_t)round_up((int64_t)K * K * 8, 256);
+    return inverse_cholesky_upper(H, K, U, (double*)workspace, (double*)((uint8_t*)workspace + mat),
+                                  (int*)((uint8_t*)workspace + 2 * mat), (hipStream_t)stream);
+}
+
+size_t haq_hessian_quant_workspace_bytes(int32_t K, int32_t N) {
+    if (K <= 0 || N <= 0) return 0;
+    return carve_hess(nullptr, K, N).bytes;
+}
+
+int32_t haq_hessian_quant_weight(const void* x_fp16, int64_t ldx, int32_t T, const float* w, const float* s, int32_t K,
+                                 int32_t N, double percdamp, int8_t* wq, float* w_scale, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (T <= 0 || K <= 0 || N <= 0 || K > 65535) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_hessian_quant_weight: T=%d K=%d N=%d", T, K, N);
+    if (!x_fp16 || !w || !wq || !w_scale || ldx < K) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_hessian_quant_weight: null buffer or ldx=%lld", (long long)ldx);
+    const size_t need = carve_hess(nullptr, K, N).bytes;
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_hessian_quant_weight: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    HessWs ws = carve_hess(workspace, K, N);
+    int rc;
+    // the per-output-channel grid is the one of plain rounding (its codes are overwritten below)
+    if ((rc = haq_quant_weight(w, s, K, N, wq, w_scale, stream)) != HAQ_OK) return rc;
+    if ((rc = haq_hessian_f64(x_fp16, ldx, s, T, K, percdamp, ws.H, stream)) != HAQ_OK) return rc;
+    if ((rc = inverse_cholesky_upper(ws.H, K, ws.H, ws.A, ws.M, ws.status, st)) != HAQ_OK) return rc;  // U replaces H
+    const double* U = ws.H;
+    hipLaunchKernelGGL(fold_weight_kernel, dim3(cdiv(N, 256), K), dim3(256), 0, st, w, s, K, N, ws.w64);
+    for (int b0 = 0; b0 < K; b0 += GB) {
+        hipLaunchKernelGGL(gptq_block_kernel, dim3(cdiv(N, 64)), dim3(64), 0, st, ws.w64, U, (const float*)w_scale, K, N, b0, wq, ws.err);
+        const int below = K - b0 - GB;
+        if (below > 0)
+            hipLaunchKernelGGL(gptq_update_kernel, dim3(cdiv(N, 64), cdiv(below, 64)), dim3(256), 0, st, ws.w64, U,
+                               (const double*)ws.err, K, N, b0);
+    }
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+}  // extern "C"

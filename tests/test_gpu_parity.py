@@ -447,3 +447,41 @@ def test_expert_cache_follows_lru_across_calls():
     finally:
         torch.cuda.synchronize()
         haq.haq_ctx_destroy(ctx)
+
+
+# ------------------------------------------------------------------ Hessian-aware weight quantisation (Algorithm 1 step 2)
+def _correlated(seed, T, K, rank):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, rank)) @ rng.standard_normal((rank, K)) + 0.1 * rng.standard_normal((T, K))).astype(np.float16)
+
+
+@pytest.mark.parametrize("T,K,N,with_s", [(200, 64, 48, True), (203, 320, 208, True), (90, 96, 16, False), (512, 768, 3072, True)])
+def test_hessian_quantiser_bit_exact(T, K, N, with_s):
+    """Binary64 chains in the same order on both sides: Hessian, factor of its inverse, codes and scales."""
+    X = _correlated(80 + K, T, K, max(4, K // 16))
+    if K > 64:
+        X[:, 5] = 0  # a channel that never fires
+    W = hi.gaussian_weight(80 + K, 0, K, N)
+    s = oracle.smoothing_vector(oracle.col_absmax_f16(X), oracle.row_absmax_f32(W), 0.5) if with_s else None
+    H_ref = oracle.hessian(X, s, 0.01)
+    H = haq.haq_hessian_f64(dev(X), None if s is None else dev(s), 0.01)
+    assert bits_equal(host(H), H_ref), diff_report(host(H), H_ref)
+    U_ref = oracle.inverse_cholesky_upper(H_ref)
+    U = haq.haq_inverse_cholesky_upper_f64(H)
+    assert bits_equal(host(U), U_ref), diff_report(host(U), U_ref)
+    Wq_ref, sw_ref = oracle.gptq(W, s, U_ref)
+    Wq, sw = haq.haq_hessian_quant_weight(dev(X), dev(W), None if s is None else dev(s), 0.01)
+    assert bits_equal(host(sw), sw_ref)
+    assert bits_equal(host(Wq), Wq_ref), diff_report(host(Wq), Wq_ref)
+    # and the result is what the method is for: a lower output error than plain rounding
+    Wr, _ = oracle.quant_weight(W, s)
+    Xs = (X.astype(F32) / (s if s is not None else F32(1))).astype(np.float64)
+    Ws = ((s[:, None] if s is not None else F32(1)) * W).astype(np.float64)
+    err = lambda q: np.sum((Xs @ Ws - Xs @ (q * sw_ref.astype(np.float64))) ** 2)
+    assert err(host(Wq)) < err(Wr)
+
+
+def test_hessian_quantiser_rejects_an_indefinite_matrix():
+    H = torch.tensor([[1.0, 2.0], [2.0, 1.0]], dtype=torch.float64, device="cuda:0")
+    with pytest.raises(haq.HaqError):
+        haq.haq_inverse_cholesky_upper_f64(H)
