@@ -13,8 +13,8 @@ timed on a bounded sample of the same workload.
 
 Other workloads (--workload): linear (OPT-125m linear), moe_prefill (Mixtral
 layer, 4096 tokens, Zipf routing), moe_decode_b1 / _b8 / _b64, moe_offload, and
-smooth_search (the offline grid search of the smoothing exponent on fc1 of the
-default block).
+smooth_search and hessian_quant (the offline grid search of the smoothing
+exponent and the Hessian-aware weight quantiser, on fc1 of the default block).
 """
 from __future__ import annotations
 
@@ -429,6 +429,54 @@ def bench_search(args, torch, haq, hi):
     }
 
 
+def bench_hessian(args, torch, haq, hi):
+    """Hessian-aware weight quantisation (Algorithm 1 step 2) of fc1 of the OPT-6.7B-shaped block."""
+    wl = hi.OPT67B_FFN
+    T, K, N = wl.T, wl.H, wl.F
+    X_h, _, _ = hi.hidden_states(wl.seed, T, K, wl.n_outlier, wl.mult)
+    W_h = hi.gaussian_weight(wl.seed, 0, K, N)
+    X, W = torch.from_numpy(X_h).to("cuda:0"), torch.from_numpy(W_h).to("cuda:0")
+    s = haq.haq_smoothing_vector(haq.haq_channel_absmax_f16(X), haq.haq_weight_row_absmax(W), 0.5)
+    ws = torch.empty(haq.haq_hessian_quant_workspace_bytes(K, N), dtype=torch.uint8, device="cuda:0")
+    out = {}
+
+    def step():
+        out["r"] = haq.haq_hessian_quant_weight(X, W, s, 0.01, workspace=ws)
+
+    sec = _time_steps(torch, step, args.steps, args.warmup)
+    wq, sw = out["r"]
+    # what it buys on the run-time path: loss of the W8A8 layer against the binary64 product, both quantisers
+    yref = haq.haq_reference_matmul_f64(X, W)
+    wr, swr = haq.haq_quant_weight(W, s)
+    loss = {}
+    for name, (q, sc) in (("hessian_aware", (wq, sw)), ("round_to_nearest", (wr, swr))):
+        y = haq.haq_w8a8_linear(X, s, haq.haq_pack_weight(q), sc, N)
+        loss[name] = float(haq.haq_quant_loss_f64(y, yref).cpu()[0])
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        Ks, Ns = 1024, 2048
+        t0 = time.perf_counter()
+        oracle.hessian_quant_weight(X_h[:, :Ks], W_h[:Ks, :Ns], s.cpu().numpy()[:Ks], 0.01)
+        dt = time.perf_counter() - t0
+        cpu = {"value": Ks * Ns / dt / 1e6, "unit": "Mweights/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {Ks} input channels x first {Ns} output channels, all {T} calibration rows, once, {dt:.2f} s "
+                         "(the cost grows faster than the weight count: K^2 T + K^3 + K^2 N)"}
+    flops = float(K) * K * N  # the compensation sweep: K^2 N / 2 fused multiply-adds
+    return {
+        "metric": "Hessian-aware weight quantisation throughput (offline)", "value": K * N / sec / 1e6, "unit": "Mweights/s",
+        "ms_per_step": sec * 1e3, "dtype": "f64",
+        "config": {"workload": "opt-6.7b fc1 hessian-aware quantisation", "calibration_rows": T, "in_features": K,
+                   "out_features": N, "percdamp": 0.01, "smoothing_alpha": 0.5},
+        "w8a8_layer_loss": loss, "codes_changed_vs_rtn": float((wq != wr).float().mean().cpu()),
+        "roofline": {"bound": "alu", "kernel": "whole call (binary64 chains: Hessian, factorisation, inverse, sweep)",
+                     "achieved": (2.0 * K * K * T + K ** 3 / 3.0 + K ** 3 / 3.0 + flops) / sec / 1e12, "peak": PEAK_FP64_TFLOPS,
+                     "unit": "TFLOP/s", "frac": (2.0 * K * K * T + 2.0 * K ** 3 / 3.0 + flops) / sec / 1e12 / PEAK_FP64_TFLOPS,
+                     "traffic": None},
+        "cpu_baseline": cpu,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -436,7 +484,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ffn",
                     choices=["ffn", "linear", "moe_prefill", "moe_decode_b1", "moe_decode_b8", "moe_decode_b64",
-                             "moe_offload", "smooth_search"])
+                             "moe_offload", "smooth_search", "hessian_quant"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MB (reference for rocprofv3 --pmc byte counters)")
@@ -464,6 +512,8 @@ def main():
         res = bench_ffn(args, torch, haq, hi)
     elif args.workload == "smooth_search":
         res = bench_search(args, torch, haq, hi)
+    elif args.workload == "hessian_quant":
+        res = bench_hessian(args, torch, haq, hi)
     else:
         res = bench_moe(args, torch, haq, hi)
     line = {"metric": res.pop("metric"), "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1,

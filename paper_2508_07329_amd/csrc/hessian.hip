@@ -8,7 +8,7 @@
 //
 //   H  = 2 Xs^T Xs + damping                       hessian_kernel, hessian_finish_kernel
 //   A  = flip(H) = L L^T                           chol_panel_kernel, chol_trail_kernel
-//   M  = L^-1 (lower)                              tri_inverse_kernel
+//   M  = L^-1 (lower)                              tri_inverse_block_kernel
 //   U  = flip(M): upper, H^-1 = U^T U              flip_kernel
 //   channels i ascending: code, error, compensate  gptq_block_kernel, gptq_update_kernel
 #include "haq_common.h"
@@ -19,7 +19,7 @@ namespace {
 
 constexpr int HT = 64, HK = 16;  // Hessian tile (outputs) and token step
 constexpr int PB = 32;           // Cholesky panel width
-constexpr int GB = 32;           // input channels quantised per compensation block
+constexpr int GB = 64;           // input channels quantised per compensation block
 
 // ---- H = 2 Xs^T Xs -------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void hessian_kernel(const __half* x, int64_t ldx, const float* s, int T, int K, double* H) {
@@ -214,38 +214,80 @@ __global__ __launch_bounds__(256) void chol_trail_kernel(double* A, int K, int j
     }
 }
 
-// ---- M = L^-1, one thread per column ------------------------------------------------------------
+// ---- M = L^-1, blocks of TR rows ---------------------------------------------------------------
 // M_jj = 1 / L_jj; M_ij = -(sum_{j <= k < i} L_ik M_kj) / L_ii, the sum a chain over k ascending.
-// The k loop runs over the same k for all lanes of a wave (lanes whose column starts later are
-// masked), so the loads of M are coalesced and L_ik is one address per wave.
-__global__ __launch_bounds__(64) void tri_inverse_kernel(const double* L, int K, double* M) {
-    __shared__ double lrow[512];
-    const int j = blockIdx.x * 64 + threadIdx.x;
-    const int jmin = blockIdx.x * 64;
-    const bool on = j < K;
-    for (int i = jmin; i < K; ++i) {
-        double v = 0.0;
-        for (int k0 = jmin; k0 < i; k0 += 512) {  // row i of L, 512 entries at a time through LDS
-            const int lim = min(512, i - k0);
-            __syncthreads();
-            for (int e = threadIdx.x; e < lim; e += 64) lrow[e] = L[(size_t)i * K + k0 + e];
-            __syncthreads();
-            if (on) {
-                for (int e = 0; e < lim; ++e) {
-                    const int k = k0 + e;
-                    if (k >= j) v = __builtin_fma(-lrow[e], M[(size_t)k * K + j], v);
-                }
+// A launch handles rows i0 .. i0 + TR - 1 (the launches run in row order); a work-group owns 64
+// columns.  First the links k < i0 of every chain (M_kj from earlier launches): wave w carries the
+// chains of rows 8w .. 8w + 7 for the 64 columns, the same k for all lanes (lanes whose column
+// starts later are masked), L tile and M chunk through LDS.  Then wave 0 adds the links inside the
+// block, row by row, with the M_kj it has just produced.  M must be zero on entry (the part above
+// the diagonal is never written).
+constexpr int TR = 32, TW = 4, RPW = TR / TW;
+__global__ __launch_bounds__(64 * TW) void tri_inverse_block_kernel(const double* L, int K, int i0, double* M) {
+    __shared__ double Lt[TR][64 + 1];  // [row][k in chunk]; later the diagonal block
+    __shared__ double Ms[64][64];      // [k in chunk][column]
+    __shared__ double Acc[TR][64];     // chains after the links k < i0
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int jmin = blockIdx.x * 64, j = jmin + lane;
+    const int rows = min(TR, K - i0);
+    if (jmin >= i0 + rows) return;  // uniform: the whole work-group lies right of the diagonal block
+    const bool on = j < i0 + rows;
+    double acc[RPW];
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) acc[r] = 0.0;
+    for (int k0 = jmin; k0 < i0; k0 += 64) {
+        const int lim = min(64, i0 - k0);
+        __syncthreads();
+        for (int e = tid; e < TR * 64; e += 64 * TW) {
+            const int r = e / 64, c = e % 64;
+            Lt[r][c] = (r < rows && c < lim) ? L[(size_t)(i0 + r) * K + k0 + c] : 0.0;
+        }
+        for (int e = tid; e < 64 * 64; e += 64 * TW) {  // coalesced over the columns
+            const int kk = e / 64, c = e % 64;
+            const int k = k0 + kk, col = jmin + c;
+            Ms[kk][c] = (kk < lim && col < i0 + rows && k >= col) ? M[(size_t)k * K + col] : 0.0;
+        }
+        __syncthreads();
+        if (on) {
+            // Ms is zero where k < j or past the chunk's end, and a link with M_kj = 0 leaves the chain
+            // as it is (v - L * 0 = v exactly; a chain never holds -0 because it starts from +0), so the
+            // loop needs no per-lane condition and unrolls
+#pragma unroll 8
+            for (int e = 0; e < 64; ++e) {
+                const double m = Ms[e][lane];
+#pragma unroll
+                for (int r = 0; r < RPW; ++r) acc[r] = __builtin_fma(-Lt[wave * RPW + r][e], m, acc[r]);
             }
         }
-        if (on) {
-            const double lii = L[(size_t)i * K + i];
-            if (i == j) M[(size_t)i * K + j] = 1.0 / lii;
-            else if (i > j) M[(size_t)i * K + j] = v / lii;
-            else M[(size_t)i * K + j] = 0.0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RPW; ++r) Acc[wave * RPW + r][lane] = acc[r];
+    for (int e = tid; e < TR * TR; e += 64 * TW) {
+        const int r = e / TR, c = e % TR;
+        Lt[r][c] = (r < rows && c <= r) ? L[(size_t)(i0 + r) * K + i0 + c] : 0.0;
+    }
+    __syncthreads();
+    if (wave != 0 || !on) return;
+    double mloc[TR];
+#pragma unroll
+    for (int r = 0; r < TR; ++r) {
+        mloc[r] = 0.0;
+        if (r < rows) {
+            const int i = i0 + r;
+            if (i == j) {
+                mloc[r] = 1.0 / Lt[r][r];
+                M[(size_t)i * K + j] = mloc[r];
+            } else if (i > j) {
+                double v = Acc[r][lane];
+#pragma unroll
+                for (int c = 0; c < TR; ++c)
+                    if (c < r && i0 + c >= j) v = __builtin_fma(-Lt[r][c], mloc[c], v);
+                mloc[r] = v / Lt[r][r];
+                M[(size_t)i * K + j] = mloc[r];
+            }
         }
     }
-    if (on)
-        for (int i = 0; i < jmin; ++i) M[(size_t)i * K + j] = 0.0;
 }
 
 // ---- the quantise-and-compensate sweep ------------------------------------------------------------
@@ -291,31 +333,62 @@ __global__ __launch_bounds__(64) void gptq_block_kernel(double* w64, const doubl
 }
 
 // Rows j >= b0 + GB: w_jn -= err_in U_ij for the block's channels i ascending.  64 rows x 64
-// output channels per work-group, 4 x 4 per thread.
+// output channels per work-group, 4 x 4 per thread held in registers; the block's channels come
+// through LDS 32 at a time (in order).
 __global__ __launch_bounds__(256) void gptq_update_kernel(double* w64, const double* U, const double* err, int K, int N, int b0) {
-    __shared__ double Es[GB][64 + 1];  // [i][n]
-    __shared__ double Us[GB][64 + 1];  // [i][j]
+    constexpr int GH = 32;
+    __shared__ double Es[GH][64 + 1];  // [i][n]
+    __shared__ double Us[GH][64 + 1];  // [i][j]
     const int tid = threadIdx.x;
     const int r0 = b0 + GB + blockIdx.y * 64, n0 = blockIdx.x * 64;
-    for (int e = tid; e < GB * 64; e += 256) {
-        const int i = e / 64, c = e % 64;
-        Es[i][c] = (n0 + c < N) ? err[(size_t)i * N + n0 + c] : 0.0;
-        Us[i][c] = (r0 + c < K) ? U[(size_t)(b0 + i) * K + r0 + c] : 0.0;
-    }
-    __syncthreads();
     const int tx = tid % 16, ty = tid / 16;
+    const bool full_cols = n0 + tx * 4 + 3 < N && (N % 2 == 0);
+    double v[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int j = r0 + ty * 4 + a;
+        const double* p = w64 + (size_t)j * N + n0 + tx * 4;
+        if (j < K && full_cols) {  // 32 contiguous bytes per thread, two 16-byte accesses
+            const double2 lo = *reinterpret_cast<const double2*>(p), hi = *reinterpret_cast<const double2*>(p + 2);
+            v[a][0] = lo.x; v[a][1] = lo.y; v[a][2] = hi.x; v[a][3] = hi.y;
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v[a][b] = (j < K && n0 + tx * 4 + b < N) ? p[b] : 0.0;
+        }
+    }
+    for (int h = 0; h < GB; h += GH) {
+        __syncthreads();
+        for (int e = tid; e < GH * 64; e += 256) {
+            const int i = e / 64, c = e % 64;
+            Es[i][c] = (n0 + c < N) ? err[(size_t)(h + i) * N + n0 + c] : 0.0;
+            Us[i][c] = (r0 + c < K) ? U[(size_t)(b0 + h + i) * K + r0 + c] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int i = 0; i < GH; ++i) {
+            double ev[4], uv[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) ev[b] = Es[i][tx * 4 + b];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) uv[a] = Us[i][ty * 4 + a];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) v[a][b] = __builtin_fma(-ev[b], uv[a], v[a][b]);
+        }
+    }
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         const int j = r0 + ty * 4 + a;
         if (j >= K) continue;
+        double* p = w64 + (size_t)j * N + n0 + tx * 4;
+        if (full_cols) {
+            *reinterpret_cast<double2*>(p) = make_double2(v[a][0], v[a][1]);
+            *reinterpret_cast<double2*>(p + 2) = make_double2(v[a][2], v[a][3]);
+        } else {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int n = n0 + tx * 4 + b;
-            if (n >= N) continue;
-            double v = w64[(size_t)j * N + n];
-#pragma unroll
-            for (int i = 0; i < GB; ++i) v = __builtin_fma(-Es[i][tx * 4 + b], Us[i][ty * 4 + a], v);
-            w64[(size_t)j * N + n] = v;
+            for (int b = 0; b < 4; ++b)
+                if (n0 + tx * 4 + b < N) p[b] = v[a][b];
         }
     }
 }
@@ -384,7 +457,9 @@ static int32_t inverse_cholesky_upper(const double* H, int K, double* U, double*
             hipLaunchKernelGGL(chol_trail_kernel, dim3(nt, nt), dim3(256), 0, st, A, K, j0);
         }
     }
-    hipLaunchKernelGGL(tri_inverse_kernel, dim3(cdiv(K, 64)), dim3(64), 0, st, (const double*)A, K, M);
+    HAQ_CHECK_HIP(hipMemsetAsync(M, 0, (size_t)K * K * sizeof(double), st));
+    for (int i0 = 0; i0 < K; i0 += TR)
+        hipLaunchKernelGGL(tri_inverse_block_kernel, dim3(cdiv(i0 + TR < K ? i0 + TR : K, 64)), dim3(64 * TW), 0, st, (const double*)A, K, i0, M);
     hipLaunchKernelGGL(flip_kernel, dim3(cdiv(K, 256), K), dim3(256), 0, st, (const double*)M, K, U);
     HAQ_CHECK_HIP(hipGetLastError());
     int host_status = 0;
