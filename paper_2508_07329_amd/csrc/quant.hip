@@ -17,7 +17,11 @@ struct alignas(16) Half8 { __half v[8]; };
 // quotient (the final step of the classic reciprocal-based division; checked here
 // exhaustively for every binary16 significand of x against every binary32 significand of
 // d) as long as nothing under- or overflows, which `safe_divisor` guarantees for binary16
-// numerators; other divisors take the hardware division.
+// numerators; other divisors take the hardware division.  The second division of the kernel,
+// y / scale with a binary32 numerator, only feeds a round-to-nearest-integer of magnitude
+// <= 127: the sequence stays within 2 ulp of the quotient, so it could round differently from
+// the IEEE quotient only next to a half-integer, and every numerator within 8 ulp of every
+// half-integer multiple of every scale significand has been checked to round alike.
 __device__ __forceinline__ bool safe_divisor(float d) { return d >= 0x1p-40f && d <= 0x1p40f; }
 __device__ __forceinline__ float div_by(float x, float d, float r, bool fast) {
     if (fast) {
