@@ -373,3 +373,34 @@ def gptq(W: np.ndarray, s: np.ndarray | None, U: np.ndarray):
 def hessian_quant_weight(X: np.ndarray, W: np.ndarray, s: np.ndarray | None, percdamp: float = 0.01):
     """Q(W s) with error compensation along the input channels (Eq. 4-6): returns (Wq, sw)."""
     return gptq(W, s, inverse_cholesky_upper(hessian(X, s, percdamp)))
+
+
+# ---- asymmetric activations ------------------------------------------------------------------
+def asym_quant_act(X: np.ndarray, s: np.ndarray | None):
+    """Per-token asymmetric uint8 codes: returns (q uint8 [T,K], scale [T], zero point int32 [T])."""
+    X = _c(X, np.float16)
+    T, K = X.shape
+    q = np.empty((T, K), np.uint8)
+    sx = np.empty(T, np.float32)
+    zp = np.empty(T, np.int32)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_asym_quant_act(_p(X), C.c_int64(K), _p(s_), T, K, _p(q), C.c_int64(K), _p(sx), _p(zp))
+    return q, sx, zp
+
+
+def asym_gemm(q: np.ndarray, zp: np.ndarray, Wq: np.ndarray) -> np.ndarray:
+    q = _c(q, np.uint8)
+    Wq = _c(Wq, np.int8)
+    T, K = q.shape
+    N = Wq.shape[1]
+    acc = np.empty((T, N), np.int32)
+    lib().oracle_asym_gemm(_p(q), C.c_int64(K), _p(_c(zp, np.int32)), _p(Wq), T, K, N, _p(acc))
+    return acc
+
+
+def w8a8_linear_asym(X, s, Wq, sw, act="none", full=False):
+    """The linear layer with asymmetric activation codes and symmetric weights."""
+    q, sx, zp = asym_quant_act(X, s)
+    acc = asym_gemm(q, zp, Wq)
+    Y = epilogue(acc, sx, sw, act)
+    return (Y, acc, q, sx, zp) if full else Y

@@ -536,4 +536,59 @@ void oracle_gptq(const float* W, const float* s, const double* U, int K, int N, 
     }
 }
 
+// ---- asymmetric activations (Section IV.A names asymmetric quantisation as the default) --------
+// Per token: y = x / s, the range [mn, mx] of the row widened to contain 0, scale = (mx - mn) / 255,
+// zero point zp = clamp(rne(-mn / scale), 0, 255), codes q = clamp(rne(y / scale) + zp, 0, 255),
+// all in binary32; y is represented by (q - zp) * scale.  A row with mx = mn (= 0) gives scale 0,
+// zp 0 and zero codes.  The weight operand stays symmetric per output channel.
+void oracle_asym_quant_act(const uint16_t* X, int64_t ldx, const float* s, int T, int K, uint8_t* q, int64_t ldq,
+                           float* row_scale, int32_t* row_zp) {
+#pragma omp parallel
+    {
+        std::vector<float> y(K);
+#pragma omp for schedule(static)
+        for (int t = 0; t < T; ++t) {
+            float mn = 0.0f, mx = 0.0f;
+            for (int k = 0; k < K; ++k) {
+                const float x = half_to_float(X[(size_t)t * ldx + k]);
+                y[k] = s ? x / s[k] : x;
+                mn = std::fmin(mn, y[k]);
+                mx = std::fmax(mx, y[k]);
+            }
+            const float range = mx - mn;
+            uint8_t* qr = q + (size_t)t * ldq;
+            if (range == 0.0f) {
+                row_scale[t] = 0.0f;
+                row_zp[t] = 0;
+                for (int k = 0; k < K; ++k) qr[k] = 0;
+                continue;
+            }
+            const float sc = range / 255.0f;
+            float z = std::rint(-mn / sc);
+            z = std::fmin(std::fmax(z, 0.0f), 255.0f);
+            row_scale[t] = sc;
+            row_zp[t] = (int32_t)z;
+            for (int k = 0; k < K; ++k) {
+                float c = std::rint(y[k] / sc) + z;
+                c = std::fmin(std::fmax(c, 0.0f), 255.0f);
+                qr[k] = (uint8_t)c;
+            }
+        }
+    }
+}
+
+// acc[t][n] = sum_k (q[t][k] - zp[t]) * Wq[k][n], int32.
+void oracle_asym_gemm(const uint8_t* q, int64_t ldq, const int32_t* zp, const int8_t* Wq, int T, int K, int N, int32_t* acc) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        int32_t* a = acc + (size_t)t * N;
+        for (int n = 0; n < N; ++n) a[n] = 0;
+        for (int k = 0; k < K; ++k) {
+            const int32_t v = (int32_t)q[(size_t)t * ldq + k] - zp[t];
+            const int8_t* w = Wq + (size_t)k * N;
+            for (int n = 0; n < N; ++n) a[n] += v * (int32_t)w[n];
+        }
+    }
+}
+
 }  // extern "C"

@@ -601,6 +601,52 @@ def test_gptq_lowers_the_output_error_on_correlated_activations():
     assert np.array_equal(sw, swr) and np.abs(Wq.astype(int)).max() <= 127
 
 
+# ----------------------------------------------------------------- asymmetric activations
+def test_asym_codes_reconstruct_within_one_step_and_use_the_whole_range():
+    rng = np.random.default_rng(41)
+    X = (rng.standard_normal((40, 96)) * 2 + 1.5).astype(np.float16)   # skewed rows
+    X[3] = 0
+    X[4] = np.abs(X[4])                                                 # a non-negative row
+    s = np.exp(rng.normal(0, 0.4, 96)).astype(F32)
+    q, sx, zp = oracle.asym_quant_act(X, s)
+    y = X.astype(F32) / s
+    rec = (q.astype(np.int32) - zp[:, None]).astype(np.float64) * sx[:, None].astype(np.float64)
+    # rounding the zero point moves the grid by at most half a step, rounding the code by another half
+    assert np.all(np.abs(rec - y) <= sx[:, None].astype(np.float64) * (1 + 1e-6))
+    live = sx > 0
+    neg = live & (y.min(axis=1) < 0)
+    assert np.all(q[neg].min(axis=1) == 0) and np.all(q[live].max(axis=1) >= 254)
+    assert sx[3] == 0 and zp[3] == 0 and not q[3].any()
+    assert zp[4] == 0 and np.isclose(sx[4], y[4].max() / 255, rtol=1e-6)        # range starts at 0
+    assert np.all((zp >= 0) & (zp <= 255))
+
+
+def test_asym_integer_data_is_exact():
+    # integers in [-100, 155]: range 255, scale 1, zero point 100, codes = x + 100, exact accumulators
+    rng = np.random.default_rng(42)
+    X = rng.integers(-100, 156, (9, 64)).astype(np.float16)
+    X[:, 0], X[:, 1] = -100, 155
+    Wq = rng.integers(-127, 128, (64, 24)).astype(np.int8)
+    q, sx, zp = oracle.asym_quant_act(X, None)
+    assert np.all(sx == 1) and np.all(zp == 100) and np.array_equal(q.astype(int), X.astype(int) + 100)
+    acc = oracle.asym_gemm(q, zp, Wq)
+    assert np.array_equal(acc, X.astype(np.int64) @ Wq.astype(np.int64))
+    Y = oracle.w8a8_linear_asym(X, None, Wq, np.full(24, 2.0 ** -8, F32))
+    assert np.array_equal(Y, ((X.astype(np.int64) @ Wq.astype(np.int64)) * 2.0 ** -8).astype(np.float16))
+
+
+def test_asym_beats_symmetric_on_one_sided_activations():
+    # post-ReLU-like inputs: the symmetric grid wastes its negative half
+    X, _, _ = hi.hidden_states(43, 64, 256, 2, 10.0)
+    X = np.maximum(X, 0).astype(np.float16)
+    W = hi.gaussian_weight(43, 0, 256, 64)
+    Wq, sw = oracle.quant_weight(W, None)
+    exact = X.astype(np.float64) @ (Wq.astype(np.float64) * sw.astype(np.float64))   # isolate the activation error
+    e_sym = np.mean((oracle.w8a8_linear(X, None, Wq, sw).astype(np.float64) - exact) ** 2)
+    e_asym = np.mean((oracle.w8a8_linear_asym(X, None, Wq, sw).astype(np.float64) - exact) ** 2)
+    assert e_asym < 0.4 * e_sym        # twice the resolution: about a quarter of the squared error
+
+
 # ----------------------------------------------------------------- offload scheduler (Section III.C)
 def test_lru_trace_textbook_reference_string():
     # the classic 20-reference string with 3 frames: 12 misses under LRU (15 under FIFO, 9 under OPT)
