@@ -128,6 +128,29 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
                         size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The linear layer with ASYMMETRIC activation codes (the quantisation mode the
+ * paper's experimental setup, Section IV.A, names as its default); the weight
+ * operand stays symmetric per output channel.  Per token t, with y = x / s:
+ *   mn = min(0, min_k y), mx = max(0, max_k y), scale_t = (mx - mn) / 255,
+ *   zp_t = clamp(rne(-mn / scale_t), 0, 255), q = clamp(rne(y / scale_t) + zp_t, 0, 255)
+ * (binary32, IEEE division, round half to even; a row with mx = mn gives scale 0,
+ * zp 0, q 0), acc[t][n] = sum_k (q[t][k] - zp_t) Wq[k][n] (int32, exact), then the
+ * same epilogue as haq_w8a8_linear with scale_t in place of sx_t.
+ * The packed activation operand holds q - 128 and the GEMM epilogue adds
+ * (128 - zp_t) * colsum[n] to the accumulator, colsum[n] = sum_k Wq[k][n] from
+ * haq_weight_colsum (offline, int32 [N], device).
+ * Optional outputs: acc_dbg int32 [T x N] (corrected accumulators), q_dbg uint8
+ * [T x K] dense codes, sx_dbg [T], zp_dbg int32 [T].  K % 64 == 0, K <= 16384,
+ * N % 16 == 0.                                                                */
+int32_t haq_weight_colsum(const int8_t* wq, int32_t K, int32_t N, int32_t* colsum, void* stream);
+size_t haq_linear_asym_workspace_bytes(int32_t T, int32_t K, int32_t N);
+int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, const int8_t* w_packed,
+                             const float* w_scale, const int32_t* w_colsum, int32_t T, int32_t K, int32_t N,
+                             int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg, uint8_t* q_dbg,
+                             float* sx_dbg, int32_t* zp_dbg, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/* ------------------------------------------------------------------------
  * Two chained smoothed W8A8 linears (a dense FFN block, e.g. OPT: fc1, ReLU, fc2):
  *   H = fp16(act(deq(Q(s1^-1 X) W1q)));   Y = fp16(deq(Q(s2^-1 H) W2q)).
  * Results are identical to two haq_w8a8_linear calls; the block call keeps H and

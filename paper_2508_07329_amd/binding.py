@@ -24,6 +24,7 @@ __all__ = [
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
+    "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
@@ -43,6 +44,7 @@ EXPORTED_SYMBOLS = [
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
+    "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
 ]
 
 
@@ -76,7 +78,7 @@ def lib() -> C.CDLL:
         L.haq_last_error.restype = C.c_char_p
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
                   "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes", "haq_hessian_quant_workspace_bytes",
-                  "haq_inverse_cholesky_workspace_bytes"):
+                  "haq_inverse_cholesky_workspace_bytes", "haq_linear_asym_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -426,3 +428,35 @@ def haq_hessian_quant_weight(x, w, s, percdamp: float = 0.01, *, workspace=None)
     _check(lib().haq_hessian_quant_weight(_ptr(x), C.c_int64(x.stride(0)), T, _ptr(w), _ptr(s), K, N, C.c_double(percdamp),
                                           _ptr(wq), _ptr(sw), _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
     return wq, sw
+
+
+# ---- asymmetric activation codes ---------------------------------------------------------------
+def haq_weight_colsum(wq):
+    K, N = wq.shape
+    out = torch.empty((N,), dtype=torch.int32, device=wq.device)
+    _check(lib().haq_weight_colsum(_ptr(wq), K, N, _ptr(out), _stream()))
+    return out
+
+
+def haq_linear_asym_workspace_bytes(T: int, K: int, N: int) -> int:
+    return int(lib().haq_linear_asym_workspace_bytes(T, K, N))
+
+
+def haq_w8a8_linear_asym(x, s, w_packed, w_scale, w_colsum, N: int, act: int = HAQ_ACT_NONE, *, out=None, workspace=None,
+                         debug: bool = False):
+    """x fp16 [T,K] -> y fp16 [T,N]; with debug=True also (acc int32 [T,N], q uint8 [T,K], scale [T], zp int32 [T])."""
+    T, K = x.shape
+    dev = x.device
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=dev)
+    if workspace is None:
+        workspace = _ws(haq_linear_asym_workspace_bytes(T, K, N), dev)
+    acc = q = sx = zp = None
+    if debug:
+        acc = torch.empty((T, N), dtype=torch.int32, device=dev)
+        q = torch.empty((T, K), dtype=torch.uint8, device=dev)
+        sx = torch.empty((T,), dtype=torch.float32, device=dev)
+        zp = torch.empty((T,), dtype=torch.int32, device=dev)
+    _check(lib().haq_w8a8_linear_asym(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), _ptr(w_packed), _ptr(w_scale), _ptr(w_colsum),
+                                      T, K, N, act, _ptr(y), C.c_int64(y.stride(0)), _ptr(acc), _ptr(q), _ptr(sx), _ptr(zp),
+                                      _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
+    return (y, acc, q, sx, zp) if debug else y

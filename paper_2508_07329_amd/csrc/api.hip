@@ -217,6 +217,56 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
     return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, st);
 }
 
+size_t haq_linear_asym_workspace_bytes(int32_t T, int32_t K, int32_t N) {
+    (void)N;
+    if (T < 0 || K <= 0) return 0;
+    return carve_linear(nullptr, T, K).bytes + (size_t)round_up((int64_t)(T > 0 ? T : 1) * 4, 256);
+}
+
+int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, const int8_t* w_packed, const float* w_scale,
+                             const int32_t* w_colsum, int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16,
+                             int64_t ldy, int32_t* acc_dbg, uint8_t* q_dbg, float* sx_dbg, int32_t* zp_dbg, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: T=%d K=%d N=%d", T, K, N);
+    if (K % 64 != 0 || K > 16384 || N % 16 != 0)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: K=%d must be a multiple of 64 (<= 16384), N=%d of 16", K, N);
+    if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: act=%d", act);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !w_packed || !w_scale || !w_colsum || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: null buffer");
+    if (ldx < K || ldx % 8 != 0 || ldy < N || ldy % 8 != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: ldx=%lld ldy=%lld (multiples of 8)", (long long)ldx, (long long)ldy);
+    if (!aligned16(x_fp16) || !aligned16(w_packed) || !aligned16(y_fp16) || (s && !aligned16(s)) || (q_dbg && !aligned16(q_dbg)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: pointers must be 16-byte aligned");
+    const size_t need = haq_linear_asym_workspace_bytes(T, K, N);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_w8a8_linear_asym: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    const LinearWs w = carve_linear(workspace, T, K);
+    int32_t* zp = reinterpret_cast<int32_t*>((uint8_t*)workspace + w.bytes);
+    int rc = launch_asym_quant((const __half*)x_fp16, ldx, s, T, K, w.q_cm, w.R, q_dbg, K, w.sx, zp, st);
+    if (rc == HAQ_ERR_UNSUPPORTED) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: K=%d not supported", K);
+    if (rc != HAQ_OK) return rc;
+    if (sx_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(sx_dbg, w.sx, (size_t)T * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (zp_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(zp_dbg, zp, (size_t)T * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+    GemmArgs ga{};
+    ga.A = w.q_cm;
+    ga.R = w.R;
+    ga.sx = w.sx;
+    ga.K = K;
+    ga.N = N;
+    ga.Npad = round_up(N, NPAD);
+    ga.M = T;
+    ga.B = w_packed;
+    ga.sw = w_scale;
+    ga.act = act;
+    ga.Y = (__half*)y_fp16;
+    ga.ldy = ldy;
+    ga.acc_dbg = acc_dbg;
+    ga.zp = zp;
+    ga.colsum = w_colsum;
+    return launch_gemm(ga, EPI_LINEAR_ASYM, st);
+}
+
 size_t haq_ffn_workspace_bytes(int32_t T, int32_t K, int32_t F, int32_t N) {
     (void)N;
     if (T < 0 || K <= 0 || F <= 0) return 0;

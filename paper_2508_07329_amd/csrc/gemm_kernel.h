@@ -114,7 +114,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     constexpr int GA = 4 * BM / 64, GB = 4 * BN / 64;  // 1 KB (64 rows x 16 B) load groups per K-step
     constexpr int LPW = (GA + GB) / NW;                // direct-to-LDS loads per wave per K-step
     static_assert((GA + GB) % NW == 0, "load groups must divide among the waves");
-    static_assert(EPI == EPI_LINEAR || NI % 2 == 0, "gate/up blocks come in pairs");
+    static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate/up blocks come in pairs");
     constexpr int OUT_WN = (EPI == EPI_SWIGLU) ? WN / 2 : WN;  // output channels per wave tile
     constexpr int PITCH = OUT_WN * 2 + 16;                     // staged fp16 row pitch in bytes
     static_assert(32 * PITCH * NW <= STAGES * STAGE_BYTES, "epilogue staging must fit in the ring");
@@ -295,7 +295,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     for (int i = 0; i < MI; ++i) {
         const int rloc = wm * WM + i * 32 + m_l;
         const float sx = sx_s[rloc];
-        if (EPI == EPI_LINEAR) {
+        if (EPI != EPI_SWIGLU) {
+            int zshift = 0;  // 128 - zero point of this lane's token row (asymmetric codes only)
+            if (EPI == EPI_LINEAR_ASYM) zshift = (tc.m0 + rloc < tc.m_end) ? 128 - a.zp[tc.m0 + rloc] : 0;
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -306,7 +308,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
                     __half hv[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int v = acc[i][j][4 * q + e];
+                        int v = acc[i][j][4 * q + e];
+                        if (EPI == EPI_LINEAR_ASYM) {
+                            const int col = tc.n0 + wn * WN + nloc + e;
+                            if (col < a.N) v += zshift * a.colsum[col];
+                        }
                         if (DBG) {
                             const int row = tc.m0 + rloc, col = tc.n0 + wn * WN + nloc + e;
                             if (row < tc.m_end && col < a.N) a.acc_dbg[(size_t)row * a.N + col] = v;

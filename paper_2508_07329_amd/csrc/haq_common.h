@@ -109,7 +109,7 @@ struct QuantArgs {
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 
-enum { EPI_LINEAR = 0, EPI_SWIGLU = 1 };
+enum { EPI_LINEAR = 0, EPI_SWIGLU = 1, EPI_LINEAR_ASYM = 2 };
 
 struct GemmArgs {
     const int8_t* A;   // chunk-major [K/16][R][16]
@@ -133,8 +133,14 @@ struct GemmArgs {
     __half* Y;
     int64_t ldy;
     int32_t* acc_dbg;  // optional dense [rows x N]
+    // asymmetric activation codes (EPI_LINEAR_ASYM): A holds code - 128; the accumulator is corrected by
+    // (128 - zp[row]) * colsum[channel] before it is dequantised
+    const int32_t* zp;      // [rows]
+    const int32_t* colsum;  // [N] column sums of the weight codes
 };
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st);
+int launch_asym_quant(const __half* x, int64_t ldx, const float* s, int T, int K, int8_t* q_cm, int64_t R, uint8_t* q_rm,
+                      int64_t ldq, float* scale, int32_t* zp, hipStream_t st);
 
 // Decode path (at most 64 rows per expert): weight-streaming kernels.
 struct DecodeArgs {

@@ -590,6 +590,150 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
     QWAIT_VMCNT0();  // nothing may still be writing LDS when the work-group retires
 }
 
+
+// ---- asymmetric activation codes ---------------------------------------------------------------
+// Per token: range [mn, mx] of y = x / s widened to contain 0, scale = (mx - mn) / 255, zero point
+// zp = clamp(rne(-mn / scale), 0, 255), code = clamp(rne(y / scale) + zp, 0, 255).  The packed
+// operand holds code - 128 (the MFMA operands are signed; the GEMM epilogue adds
+// (128 - zp) * column sum back).  Same thread mapping as the register-resident symmetric kernel.
+struct AsymQuantArgs {
+    const __half* x;
+    int64_t ldx;
+    const float* s;
+    int T, K;
+    int8_t* q_cm;     // packed, code - 128
+    int64_t R;
+    uint8_t* q_rm;    // optional dense [T x K] codes
+    int64_t ldq;
+    float* scale;     // [T]
+    int32_t* zp;      // [T]
+};
+
+template <int RS>
+__global__ __launch_bounds__(QMAX_THREADS) void asym_quant_kernel(AsymQuantArgs a, int CL) {
+    __shared__ float red_mn[QMAX_THREADS / 64][RS];
+    __shared__ float red_mx[QMAX_THREADS / 64][RS];
+    const int tid = threadIdx.x;
+    const int c = tid % CL, g = tid / CL;
+    const int brows = (blockDim.x / CL) * RS;
+    const int waves_per_group = CL >> 6, wave = tid >> 6;
+    const int nchunk = a.K / 16;
+    const int row0 = blockIdx.x * brows + g * RS;
+    const int nrow = min(RS, a.T - row0);
+    const bool active = c < nchunk;
+    uint4 raw[RS][2];
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        raw[r][0] = raw[r][1] = make_uint4(0, 0, 0, 0);
+        if (active && r < nrow) {
+            const uint4* px = reinterpret_cast<const uint4*>(a.x + (size_t)(row0 + r) * a.ldx + c * 16);
+            raw[r][0] = px[0];
+            raw[r][1] = px[1];
+        }
+    }
+    float sv[16], rv[16];
+    bool fast = true;
+    if (a.s && active) fast = load_s16(a.s, c, sv, rv);
+    float x[16];
+    auto smoothed = [&](int r) {  // y of this thread's chunk of row r into x[]
+        Half8 h0, h1;
+        *reinterpret_cast<uint4*>(&h0) = raw[r][0];
+        *reinterpret_cast<uint4*>(&h1) = raw[r][1];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            x[i] = h2f(h0.v[i]);
+            x[8 + i] = h2f(h1.v[i]);
+        }
+        if (a.s) {
+            if (fast) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x[i] = div_by(x[i], sv[i], rv[i], true);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x[i] = x[i] / sv[i];
+            }
+        }
+    };
+    float mn[RS], mx[RS];
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        mn[r] = mx[r] = 0.0f;  // the range always contains 0 (also covers inactive lanes and absent rows)
+        if (active && r < nrow) {
+            smoothed(r);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                mn[r] = fminf(mn[r], x[i]);
+                mx[r] = fmaxf(mx[r], x[i]);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            mn[r] = fminf(mn[r], __shfl_xor(mn[r], o));
+            mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], o));
+        }
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            red_mn[wave][r] = mn[r];
+            red_mx[wave][r] = mx[r];
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            asm volatile("" : "+v"(raw[r][h].x), "+v"(raw[r][h].y), "+v"(raw[r][h].z), "+v"(raw[r][h].w));
+    }
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        if (r < nrow) {
+            float lo = 0.0f, hi = 0.0f;
+            for (int w = 0; w < waves_per_group; ++w) {
+                lo = fminf(lo, red_mn[g * waves_per_group + w][r]);
+                hi = fmaxf(hi, red_mx[g * waves_per_group + w][r]);
+            }
+            const float range = hi - lo;
+            const int t = row0 + r;
+            float scale = 0.0f, z = 0.0f;
+            uint32_t w4[4] = {0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u};  // code 0 -> -128
+            uint32_t u4[4] = {0, 0, 0, 0};
+            if (range != 0.0f) {
+                scale = range / 255.0f;
+                z = fminf(fmaxf(rintf(-lo / scale), 0.0f), 255.0f);
+                const float rscale = 1.0f / scale;
+                const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+                smoothed(r);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float qv = sfast ? div_by(x[i], scale, rscale, true) : x[i] / scale;
+                    const float cf = fminf(fmaxf(rintf(qv) + z, 0.0f), 255.0f);
+                    const uint32_t code = (uint32_t)(int)cf;
+                    u4[i / 4] |= code << (8 * (i % 4));
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w4[i] = u4[i] ^ 0x80808080u;  // code - 128 as a signed byte
+            }
+            if (c == r) {
+                a.scale[t] = scale;
+                a.zp[t] = (int32_t)z;
+            }
+            if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)t * a.ldq + c * 16) = make_uint4(u4[0], u4[1], u4[2], u4[3]);
+            *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + t) * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        }
+    }
+}
+
+__global__ void weight_colsum_kernel(const int8_t* wq, int K, int N, int32_t* colsum) {
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    int32_t acc = 0;
+    for (int k = 0; k < K; ++k) acc += wq[(size_t)k * N + n];
+    colsum[n] = acc;
+}
+
 // ---- offline: per-channel magnitudes ----------------------------------------
 __global__ void channel_absmax_f16_kernel(const __half* x, int64_t ldx, int T, int K, float* ax) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -732,6 +876,26 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     return HAQ_OK;
 }
 
+int launch_asym_quant(const __half* x, int64_t ldx, const float* s, int T, int K, int8_t* q_cm, int64_t R, uint8_t* q_rm,
+                      int64_t ldq, float* scale, int32_t* zp, hipStream_t st) {
+    if (T <= 0) return HAQ_OK;
+    const int nchunk = K / 16;
+    int CL = (int)round_up(nchunk, 64);
+    if (CL > QMAX_THREADS) return HAQ_ERR_UNSUPPORTED;  // K > 16384: not built for the asymmetric variant
+    int G = QMAX_THREADS / CL;
+    G = G >= 8 ? 8 : G >= 4 ? 4 : G >= 2 ? 2 : 1;
+    const int RS = QBLOCK_ROWS / G > 4 ? 4 : QBLOCK_ROWS / G;
+    const int threads = CL * G, nb = cdiv(T, RS * G);
+    AsymQuantArgs a{x, ldx, s, T, K, q_cm, R, q_rm, ldq, scale, zp};
+    switch (RS) {
+        case 4: hipLaunchKernelGGL(asym_quant_kernel<4>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+        case 2: hipLaunchKernelGGL(asym_quant_kernel<2>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+        default: hipLaunchKernelGGL(asym_quant_kernel<1>, dim3(nb), dim3(threads), 0, st, a, CL); break;
+    }
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
 }  // namespace haq
 
 using namespace haq;
@@ -789,6 +953,14 @@ int32_t haq_quant_weight(const float* w, const float* s, int32_t K, int32_t N, i
     hipLaunchKernelGGL(weight_col_absmax_kernel, dim3(cdiv(N, 256), ky), dim3(256), 0, st, w, s, K, N, w_scale);
     hipLaunchKernelGGL(weight_codes_kernel, dim3(cdiv(N, 256), K), dim3(256), 0, st, w, s, K, N, (const float*)w_scale, wq);
     hipLaunchKernelGGL(absmax_to_scale_kernel, dim3(cdiv(N, 256)), dim3(256), 0, st, w_scale, N);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int32_t haq_weight_colsum(const int8_t* wq, int32_t K, int32_t N, int32_t* colsum, void* stream) {
+    if (K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_weight_colsum: K=%d N=%d", K, N);
+    if (!wq || !colsum) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_weight_colsum: null buffer");
+    hipLaunchKernelGGL(weight_colsum_kernel, dim3(cdiv(N, 256)), dim3(256), 0, (hipStream_t)stream, wq, K, N, colsum);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

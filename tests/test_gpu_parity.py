@@ -485,3 +485,28 @@ def test_hessian_quantiser_rejects_an_indefinite_matrix():
     H = torch.tensor([[1.0, 2.0], [2.0, 1.0]], dtype=torch.float64, device="cuda:0")
     with pytest.raises(haq.HaqError):
         haq.haq_inverse_cholesky_upper_f64(H)
+
+
+# ------------------------------------------------------------------ asymmetric activation codes (dense linear)
+@pytest.mark.parametrize("T,K,N,act,relu_in", [(16, 768, 3072, "relu", False), (203, 320, 208, "none", True),
+                                                (1, 64, 16, "none", False), (2048, 4096, 1024, "relu", True)])
+def test_linear_asym_bit_exact(T, K, N, act, relu_in):
+    X, _, _ = hi.hidden_states(90 + T, T, K, n_outlier=max(1, K // 200))
+    if relu_in:
+        X = np.maximum(X, 0).astype(np.float16)   # one-sided rows: zero point 0
+    if T > 4:
+        X[3] = 0
+    W = hi.gaussian_weight(90 + T, 0, K, N)
+    s, Wq, sw = offline.quantize_linear(X, W)
+    y_ref, acc_ref, q_ref, sx_ref, zp_ref = oracle.w8a8_linear_asym(X, s, Wq, sw, act, full=True)
+    wq_d = dev(Wq)
+    y, acc, q, sx, zp = haq.haq_w8a8_linear_asym(dev(X), dev(s), haq.haq_pack_weight(wq_d), dev(sw), haq.haq_weight_colsum(wq_d),
+                                                 N, haq.HAQ_ACT_RELU if act == "relu" else haq.HAQ_ACT_NONE, debug=True)
+    assert bits_equal(host(haq.haq_weight_colsum(wq_d)), Wq.astype(np.int32).sum(axis=0, dtype=np.int32))
+    assert bits_equal(host(sx), sx_ref) and bits_equal(host(zp), zp_ref)
+    assert bits_equal(host(q), q_ref), diff_report(host(q), q_ref)
+    assert bits_equal(host(acc), acc_ref), diff_report(host(acc), acc_ref)
+    assert bits_equal(host(y), y_ref)
+    y2 = haq.haq_w8a8_linear_asym(dev(X), dev(s), haq.haq_pack_weight(wq_d), dev(sw), haq.haq_weight_colsum(wq_d), N,
+                                  haq.HAQ_ACT_RELU if act == "relu" else haq.HAQ_ACT_NONE)
+    assert bits_equal(host(y2), y_ref)   # the launch without the debug dump
