@@ -450,6 +450,13 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     float* sh = d.sh ? d.sh : w.sh;
 
     int rc;
+    const bool decode_path = n_host == 0 && decode_supported(T, H, I);
+    if (decode_path && decode_prologue_supported(T, H)) {
+        // few tokens: routing, permutation and token quantisation in one launch
+        if ((rc = launch_decode_prologue((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv,
+                                         (const __half*)x_fp16, ldx, s_in, H, w.q_cm, w.R, d.q, d.sx, w.sx_sorted, st)) != HAQ_OK)
+            return rc;
+    } else {
     if ((rc = launch_route_permute((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv,
                                    w.blk_counts, st)) != HAQ_OK)
         return rc;
@@ -468,8 +475,9 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qa.scale = d.sx;
     qa.scale_dest = w.sx_sorted;
     if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
+    }
 
-    if (n_host == 0 && decode_supported(T, H, I)) {
+    if (decode_path) {
         // few rows per expert: stream every activated expert's weights once
         DecodeArgs da{};
         da.q_cm = w.q_cm;

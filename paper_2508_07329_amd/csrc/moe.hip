@@ -3,6 +3,7 @@
 // combination of the two expert outputs of each token.
 #include "haq_common.h"
 #include "moe.h"
+#include "quant_math.h"
 
 namespace haq {
 
@@ -205,6 +206,185 @@ __global__ void set_tab_kernel(TabAll tab, int E, ExpertTab* tab_dev) {
     if ((int)threadIdx.x < E) tab_dev[threadIdx.x] = tab.e[threadIdx.x];
 }
 
+
+// ---- decode prologue: routing, permutation and token quantisation in one launch ------------------
+// For at most 64 tokens.  Work-group p produces sorted row p (one (token, expert) pair): every
+// work-group repeats the routing of all tokens and the stable counting sort in LDS (a few hundred
+// operations), finds the pair that lands on its row, and quantises that token with the shared
+// smoothing vector (same arithmetic as the activation-quantisation kernels).  Work-group 0 also
+// writes the routing results and the expert table.  NCH = 16-channel chunks per thread.
+struct PrologueArgs {
+    const __half* logits;
+    int64_t ldl;
+    int T, E;
+    ExpertTab* tab_dev;
+    int32_t *idx, *counts, *offsets, *perm, *inv;
+    float* gw;
+    const __half* x;
+    int64_t ldx;
+    const float* s;
+    int H;
+    int8_t* q_cm;
+    int64_t R;
+    int8_t* q_rm;      // optional dense [T x H]
+    int64_t ldq;
+    float* sx_tok;     // optional [T]
+    float* sx_sorted;  // [2T]
+};
+
+constexpr int PRO_THREADS = 256, PRO_MAXP = 128;
+template <int NCH>
+__global__ __launch_bounds__(PRO_THREADS) void decode_prologue_kernel(PrologueArgs a, TabAll tab) {
+    __shared__ int32_t s_idx[PRO_MAXP], s_pos[PRO_MAXP], s_cnt[33], s_off[33], s_src;
+    __shared__ float s_gw[PRO_MAXP], s_red[PRO_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int P = 2 * a.T;
+    if (tid < a.T) {
+        int32_t id2[2];
+        float g2[2];
+        route_token(a.logits + (size_t)tid * a.ldl, a.E, id2, g2);
+        s_idx[2 * tid] = id2[0];
+        s_idx[2 * tid + 1] = id2[1];
+        s_gw[2 * tid] = g2[0];
+        s_gw[2 * tid + 1] = g2[1];
+    }
+    __syncthreads();
+    if (tid < a.E) {
+        int c = 0;
+        for (int r = 0; r < P; ++r) c += (s_idx[r] == tid);
+        s_cnt[tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < a.E; ++e) {
+            s_off[e] = run;
+            run += s_cnt[e];
+        }
+        s_off[a.E] = run;
+    }
+    __syncthreads();
+    if (tid < P) {  // stable: pairs of one expert keep the order of their pair ids
+        const int e = s_idx[tid];
+        int rank = 0;
+        for (int r = 0; r < tid; ++r) rank += (s_idx[r] == e);
+        const int pos = s_off[e] + rank;
+        s_pos[tid] = pos;
+        if (pos == (int)blockIdx.x) s_src = tid;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (tid < a.E) {
+            a.tab_dev[tid] = tab.e[tid];
+            a.counts[tid] = s_cnt[tid];
+        }
+        if (tid <= a.E) a.offsets[tid] = s_off[tid];
+        if (tid < P) {
+            a.idx[tid] = s_idx[tid];
+            a.gw[tid] = s_gw[tid];
+            a.perm[s_pos[tid]] = tid;
+            a.inv[tid] = s_pos[tid];
+        }
+    }
+    // ---- quantise the token of this row
+    const int p = blockIdx.x, t = s_src >> 1;
+    const int nchunk = a.H / 16;
+    const __half* xrow = a.x + (size_t)t * a.ldx;
+    uint4 raw[NCH][2];
+    float sv[NCH][16], rv[NCH][16];
+    bool fast[NCH];
+    float x[16];
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = tid + i * PRO_THREADS;
+        fast[i] = true;
+        raw[i][0] = raw[i][1] = make_uint4(0, 0, 0, 0);
+        if (c < nchunk) {
+            const uint4* px = reinterpret_cast<const uint4*>(xrow + c * 16);
+            raw[i][0] = px[0];
+            raw[i][1] = px[1];
+            if (a.s) fast[i] = load_s16(a.s, c, sv[i], rv[i]);
+        }
+    }
+    auto unpack = [&](int i) {
+        Half8 h0, h1;
+        *reinterpret_cast<uint4*>(&h0) = raw[i][0];
+        *reinterpret_cast<uint4*>(&h1) = raw[i][1];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            x[k] = h2f(h0.v[k]);
+            x[8 + k] = h2f(h1.v[k]);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        if (tid + i * PRO_THREADS < nchunk) {
+            unpack(i);
+            if (!a.s) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k]));
+            } else if (fast[i]) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(div_by(x[k], sv[i][k], rv[i][k], true)));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k] / sv[i][k]));
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    if (lane == 0) s_red[wave] = amax;
+    __syncthreads();
+    float m = 0.0f;
+#pragma unroll
+    for (int w = 0; w < PRO_THREADS / 64; ++w) m = fmaxf(m, s_red[w]);
+    const float scale = m / 127.0f;
+    const float rscale = 1.0f / scale;
+    const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+    if (tid == 0) {
+        a.sx_sorted[p] = scale;
+        if (a.sx_tok) a.sx_tok[t] = scale;
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            asm volatile("" : "+v"(raw[i][h].x), "+v"(raw[i][h].y), "+v"(raw[i][h].z), "+v"(raw[i][h].w));
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = tid + i * PRO_THREADS;
+        if (c < nchunk) {
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (m != 0.0f) {
+                unpack(i);
+                if (fast[i] && sfast) {
+                    float q[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const float y = a.s ? div_by(x[k], sv[i][k], rv[i][k], true) : x[k];
+                        q[k] = div_by(y, scale, rscale, true);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) w[k] = round_pack4(q[4 * k], q[4 * k + 1], q[4 * k + 2], q[4 * k + 3]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const float y = a.s ? x[k] / sv[i][k] : x[k];
+                        float q = rintf(y / scale);
+                        q = fminf(fmaxf(q, -127.0f), 127.0f);
+                        w[k / 4] |= (uint32_t)((int)q & 0xff) << (8 * (k % 4));
+                    }
+                }
+            }
+            const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+            if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)t * a.ldq + c * 16) = v;
+            *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + p) * 16) = v;
+        }
+    }
+}
+
 // out[t] = fp16(g0 * y[inv[2t]] + g1 * y[inv[2t+1]]), 8 channels per thread.
 __global__ void combine_kernel(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H,
                                __half* out, int64_t ldo) {
@@ -248,6 +428,23 @@ int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const 
     const size_t sm = ((size_t)E * PERM_THREADS + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(route_permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, logits, ldl, T, E, tab, tab_dev, idx, gw,
                        counts, offsets, perm, inv);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+bool decode_prologue_supported(int T, int H) { return T >= 1 && 2 * T <= PRO_MAXP && H % 16 == 0 && H / 16 <= 2 * PRO_THREADS; }
+
+int launch_decode_prologue(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
+                           int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                           const __half* x, int64_t ldx, const float* s, int H, int8_t* q_cm, int64_t R, int8_t* q_rm,
+                           float* sx_tok, float* sx_sorted, hipStream_t st) {
+    TabAll tab{};
+    for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
+    PrologueArgs a{logits, ldl, T, E, tab_dev, idx, counts, offsets, perm, inv, gw, x, ldx, s, H, q_cm, R, q_rm, H, sx_tok, sx_sorted};
+    if (H / 16 <= PRO_THREADS)
+        hipLaunchKernelGGL(decode_prologue_kernel<1>, dim3(2 * T), dim3(PRO_THREADS), 0, st, a, tab);
+    else
+        hipLaunchKernelGGL(decode_prologue_kernel<2>, dim3(2 * T), dim3(PRO_THREADS), 0, st, a, tab);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
