@@ -13,6 +13,7 @@
 // partial sums are added through LDS.
 #include "haq_common.h"
 #include "moe.h"
+#include "quant_math.h"
 
 namespace haq {
 
@@ -148,36 +149,76 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(Decode
 }
 
 // ---- requantisation of the intermediate with known partial maxima ------------------------
-// One work-group per sorted row: reduce the row's partial maxima, then round h / s_mid / scale.
-__global__ __launch_bounds__(256) void decode_requant_kernel(DecodeArgs a) {
-    __shared__ float red[4];
+// One work-group per sorted row, one thread per 16-channel chunk (as many threads as the row
+// has chunks, up to 1024): reduce the row's partial maxima, then round h / s_mid / scale; the
+// division by the row scale goes through its reciprocal (quant_math.h).
+constexpr int RQ_THREADS = 1024;
+__global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a) {
+    __shared__ float red[RQ_THREADS / 64];
     const int pos = blockIdx.x;
     int e = 0;
     while (e + 1 < a.E && pos >= a.offsets[e + 1]) ++e;
     const float* s = a.tab[e].s_mid;
-    const int tid = threadIdx.x, nu = a.I / 32;
+    const int tid = threadIdx.x, nu = a.I / 32, nthr = blockDim.x, nwave = nthr >> 6;
+    const __half* hrow = a.mid + (size_t)pos * a.I;
+    // the row's halves and smoothing entries are fetched before the maximum is known
+    const int nchunk = a.I / 16;
+    uint4 r0 = make_uint4(0, 0, 0, 0), r1 = r0;
+    float sv[16];
+    const bool single = nchunk <= nthr;  // one chunk per thread: keep it in registers
+    if (single && tid < nchunk) {
+        const uint4* px = reinterpret_cast<const uint4*>(hrow + tid * 16);
+        r0 = px[0];
+        r1 = px[1];
+        const float4* ps = reinterpret_cast<const float4*>(s + tid * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 v = ps[i];
+            sv[4 * i] = v.x;
+            sv[4 * i + 1] = v.y;
+            sv[4 * i + 2] = v.z;
+            sv[4 * i + 3] = v.w;
+        }
+    }
     float m = 0.0f;
-    for (int i = tid; i < nu; i += 256) m = fmaxf(m, a.pmax[(size_t)pos * nu + i]);
+    for (int i = tid; i < nu; i += nthr) m = fmaxf(m, a.pmax[(size_t)pos * nu + i]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if ((tid & 63) == 0) red[tid >> 6] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    m = 0.0f;
+    for (int w = 0; w < nwave; ++w) m = fmaxf(m, red[w]);
     const float scale = m / 127.0f;
+    const float rscale = 1.0f / scale;
+    const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
     if (tid == 0) a.sh[pos] = scale;
-    const __half* hrow = a.mid + (size_t)pos * a.I;
-    for (int c = tid; c < a.I / 16; c += 256) {
+    for (int c = tid; c < nchunk; c += nthr) {
         uint32_t w[4] = {0, 0, 0, 0};
         if (m != 0.0f) {
-            const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
-            const uint4 r0 = px[0], r1 = px[1];
+            if (!single) {
+                const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
+                r0 = px[0];
+                r1 = px[1];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sv[i] = s[c * 16 + i];
+            }
             const __half* h0 = reinterpret_cast<const __half*>(&r0);
             const __half* h1 = reinterpret_cast<const __half*>(&r1);
+            if (sfast) {
+                float q[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float x = h2f(i < 8 ? h0[i] : h1[i - 8]);
-                const float y = x / s[c * 16 + i];
-                w[i / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (i % 4));
+                for (int i = 0; i < 16; ++i) {
+                    const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
+                    q[i] = div_by(y, scale, rscale, true);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
+                    w[i / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (i % 4));
+                }
             }
         }
         const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
@@ -267,7 +308,11 @@ int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int ne = a.E < P ? a.E : P;  // at most 2T experts can hold rows
     const dim3 g1(a.I / 32, ne, nrb), g2(a.H / 32, ne, nrb);
     hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
-    hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(256), 0, st, a);
+    {
+        const int nchunk = a.I / 16;
+        const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
+        hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(thr), 0, st, a);
+    }
     hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
