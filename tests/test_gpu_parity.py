@@ -309,6 +309,34 @@ def test_moe_mixtral_decode(layer, b):
     _check_moe(_mixtral_case(wl, layer), layer["dev_experts"], tokens)
 
 
+@pytest.mark.parametrize("b", [1, 8])
+def test_moe_mixtral_decode_graph_replay(layer, b):
+    """The launch configuration bench.py times for decode: the call captured once into a graph and
+    replayed.  Every replay (with eager work on other inputs in between, which dirties the shared
+    workspace) must give the oracle's output."""
+    wl = {w.T: w for w in hi.MIXTRAL_DECODE}[b]
+    case = _mixtral_case(wl, layer)
+    other = _mixtral_case({w.T: w for w in hi.MIXTRAL_DECODE}[64], layer)
+    idx, gw = oracle.route_top2(case["logits"])
+    ref = oracle.moe_ffn(case["X"], idx, gw, case["s_in"], case["experts"])
+    X, logits = dev(case["X"]), dev(case["logits"])
+    Xo, Lo = dev(other["X"]), dev(other["logits"])
+    ws = torch.empty(haq.haq_moe_workspace_bytes(64, wl.H, wl.I, wl.E), dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((b, wl.H), dtype=torch.float16, device="cuda:0")
+    haq.haq_moe_w8a8_ffn(X, logits, layer["dev_s_in"], layer["dev_experts"], wl.I, out=out, workspace=ws)  # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        haq.haq_moe_w8a8_ffn(X, logits, layer["dev_s_in"], layer["dev_experts"], wl.I, out=out, workspace=ws)
+    for rep in range(4):
+        out.zero_()
+        haq.haq_moe_w8a8_ffn(Xo, Lo, layer["dev_s_in"], layer["dev_experts"], wl.I, workspace=ws)  # eager, same workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert bits_equal(host(out), ref), f"replay {rep}: {diff_report(host(out), ref)}"
+
+
 def test_moe_mixtral_offload_four_of_eight_resident(layer):
     """256 tokens, experts 4-7 in pinned host memory and streamed through 2 staging slots."""
     wl = hi.MIXTRAL_OFFLOAD
