@@ -638,10 +638,22 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     // misses whose slot is not in use by an earlier expert of this call are copied right away
     for (int k = 0; k < n_order; ++k)
         if (!hit[k] && prev_user[k] < 0 && (rc = issue_copy(k)) != HAQ_OK) return rc;
-    // device-resident experts compute while the first copies are in flight
+    // Device-resident experts, and cached ones whose slot nobody evicts later in this call, compute as
+    // one grouped launch while the first copies are in flight.
+    bool grouped[32] = {};
+    for (int k = 0; k < n_order; ++k) {
+        bool evicted_later = false;
+        for (int k2 = k + 1; k2 < n_order; ++k2) evicted_later = evicted_later || prev_user[k2] == k;
+        if (hit[k] && !evicted_later) {
+            grouped[k] = true;
+            resident[n_res++] = order[k];
+            res_rows += ctx->counts_host[order[k]];
+        }
+    }
     if (n_res > 0 && (rc = run_experts(resident, n_res, res_rows)) != HAQ_OK) return rc;
     for (int k = 0; k < n_order; ++k) {
         const int e = order[k];
+        if (grouped[k]) continue;
         if (!hit[k]) {
             if (!issued[k]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
             HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[k], 0));
