@@ -27,6 +27,24 @@ int launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
     return HAQ_OK;
 }
 
+// 128 x 128 tiles (wave tile 64 x 64) for problems whose 128 x 256 tiling would leave half of the
+// work-group slots empty: twice the tiles, 49 KB of LDS, three work-groups per CU.
+constexpr int SMALL_TILE_LIMIT = 256;  // 128 x 256 tiles that would not even give every CU one work-group
+constexpr int BN_S = 128, MINB_S = 3;
+using ShapeS = GemmShape<BM, BN_S, WAVES_M, WAVES_N, STAGES>;
+int launch_small(const GemmArgs& a, dim3 grid, hipStream_t st) {
+    auto kern = gemm_i8_kernel<BM, BN_S, WAVES_M, WAVES_N, STAGES, MINB_S, EPI_LINEAR, false>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ShapeS::LDS_BYTES);
+    });
+    HAQ_CHECK_HIP(attr_err);
+    hipLaunchKernelGGL(kern, grid, dim3(ShapeS::THREADS), ShapeS::LDS_BYTES, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
 }  // namespace
 
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
@@ -34,6 +52,10 @@ int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
     // upper bound on the M tiles: exact for one matrix; rows/BM plus one partial tile per group otherwise
     const int mt = a.offsets ? a.max_rows / BM + a.n_sel : cdiv(a.M, BM);
     if (mt <= 0 || ntn <= 0) return HAQ_OK;
+    if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg && mt * ntn <= SMALL_TILE_LIMIT) {
+        const int ntn_s = cdiv(a.N, BN_S);
+        return launch_small(a, dim3((unsigned)round_up((int64_t)mt * ntn_s, 8)), st);
+    }
     const dim3 grid((unsigned)round_up((int64_t)mt * ntn, 8));
     if (epi == EPI_SWIGLU) return launch_one<EPI_SWIGLU, false>(a, grid, st);
     if (epi == EPI_LINEAR_ASYM) return a.acc_dbg ? launch_one<EPI_LINEAR_ASYM, true>(a, grid, st) : launch_one<EPI_LINEAR_ASYM, false>(a, grid, st);
