@@ -113,3 +113,10 @@ def test_select_experts_host_function_matches_oracle():
         ref = oracle.select_experts(L, top_k, supp, path_stats, [list(enumerate(f)) for f in expert_freq])
         got = haq.haq_select_experts(L, E, top_k, supp, path_stats, expert_freq)
         assert got == ref, (trial, path_stats, expert_freq, top_k, supp)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
