@@ -131,7 +131,7 @@ def test_linear_opt125m_config():
 
 
 @pytest.mark.parametrize("T,K,N,act", [(300, 832, 1040, "relu"), (1, 64, 16, "none"), (257, 1024, 272, "none"),
-                                        (513, 2048, 768, "relu")])
+                                        (513, 2048, 768, "relu"), (5, 32768, 48, "none"), (130, 65536, 16, "relu")])
 def test_linear_ragged_shapes(T, K, N, act):
     X, _, _ = hi.hidden_states(T + K, T, K, n_outlier=3)
     _linear_case(X, hi.gaussian_weight(T + K, 0, K, N), act)
