@@ -242,6 +242,20 @@ int32_t haq_hessian_quant_weight(const void* x_fp16, int64_t ldx, int32_t T, con
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Algorithm 1 for one linear layer, on this device: step 1 (haq_smoothing_search:
+ * the smoothing vector s by grid search on the calibration activations), step 2
+ * (haq_hessian_quant_weight on the weight folded with that s), step 3 (the GPU
+ * keeps the int8 codes: pack them with haq_pack_weight).  Outputs: s [K] device,
+ * wq int8 [K x N] device, w_scale [N] device, losses [n_e] host, *best host.
+ * Same constraints as the two calls it chains; synchronises the stream.
+ * losses and best must not be NULL.                                          */
+size_t haq_quantize_layer_workspace_bytes(int32_t T, int32_t K, int32_t N, int32_t n_e);
+int32_t haq_quantize_layer(const void* x_fp16, int64_t ldx, int32_t T, const float* w, int32_t K, int32_t N,
+                           const double* exponents, int32_t n_e, int32_t use_weight, double percdamp, float* s,
+                           int8_t* wq, float* w_scale, double* losses, int32_t* best, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Top-2 routed SwiGLU expert FFN with W8A8 experts.
  *
  * Per token t: top-2 experts by router logit (lowest index wins ties); gate

@@ -25,6 +25,7 @@ __all__ = [
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
+    "haq_quantize_layer_workspace_bytes", "haq_quantize_layer",
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
@@ -45,6 +46,7 @@ EXPORTED_SYMBOLS = [
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
+    "haq_quantize_layer_workspace_bytes", "haq_quantize_layer",
 ]
 
 
@@ -78,7 +80,8 @@ def lib() -> C.CDLL:
         L.haq_last_error.restype = C.c_char_p
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
                   "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes", "haq_hessian_quant_workspace_bytes",
-                  "haq_inverse_cholesky_workspace_bytes", "haq_linear_asym_workspace_bytes"):
+                  "haq_inverse_cholesky_workspace_bytes", "haq_linear_asym_workspace_bytes",
+                  "haq_quantize_layer_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -460,3 +463,28 @@ def haq_w8a8_linear_asym(x, s, w_packed, w_scale, w_colsum, N: int, act: int = H
                                       T, K, N, act, _ptr(y), C.c_int64(y.stride(0)), _ptr(acc), _ptr(q), _ptr(sx), _ptr(zp),
                                       _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
     return (y, acc, q, sx, zp) if debug else y
+
+
+# ---- Algorithm 1 for one linear layer ------------------------------------------------------------
+def haq_quantize_layer_workspace_bytes(T: int, K: int, N: int, n_e: int) -> int:
+    return int(lib().haq_quantize_layer_workspace_bytes(T, K, N, n_e))
+
+
+def haq_quantize_layer(x, w, exponents, use_weight: bool = False, percdamp: float = 0.01, *, workspace=None):
+    """Smoothing search, then Hessian-aware quantisation with the chosen vector.
+    Returns (s [K], wq int8 [K,N], w_scale [N], losses: list[float], best: int)."""
+    T, K = x.shape
+    N = w.shape[1]
+    n_e = len(exponents)
+    grid = (C.c_double * n_e)(*[float(e) for e in exponents])
+    losses = (C.c_double * n_e)()
+    best = C.c_int32(-1)
+    s = torch.empty((K,), dtype=torch.float32, device=x.device)
+    wq = torch.empty((K, N), dtype=torch.int8, device=x.device)
+    sw = torch.empty((N,), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = _ws(haq_quantize_layer_workspace_bytes(T, K, N, n_e), x.device)
+    _check(lib().haq_quantize_layer(_ptr(x), C.c_int64(x.stride(0)), T, _ptr(w), K, N, grid, n_e, int(bool(use_weight)),
+                                    C.c_double(percdamp), _ptr(s), _ptr(wq), _ptr(sw), losses, C.byref(best), _ptr(workspace),
+                                    C.c_size_t(workspace.numel()), _stream()))
+    return s, wq, sw, list(losses), int(best.value)

@@ -514,4 +514,25 @@ int32_t haq_hessian_quant_weight(const void* x_fp16, int64_t ldx, int32_t T, con
     return HAQ_OK;
 }
 
+size_t haq_quantize_layer_workspace_bytes(int32_t T, int32_t K, int32_t N, int32_t n_e) {
+    const size_t a = haq_smoothing_search_workspace_bytes(T, K, N, n_e), b = haq_hessian_quant_workspace_bytes(K, N);
+    return a > b ? a : b;
+}
+
+int32_t haq_quantize_layer(const void* x_fp16, int64_t ldx, int32_t T, const float* w, int32_t K, int32_t N,
+                           const double* exponents, int32_t n_e, int32_t use_weight, double percdamp, float* s,
+                           int8_t* wq, float* w_scale, double* losses, int32_t* best, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    if (!s || !wq || !w_scale) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quantize_layer: null output");
+    if (T <= 0 || K <= 0 || N <= 0 || n_e <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quantize_layer: T=%d K=%d N=%d n_e=%d", T, K, N, n_e);
+    if (workspace_bytes < haq_quantize_layer_workspace_bytes(T, K, N, n_e))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_quantize_layer: workspace of %zu bytes needed, got %zu", haq_quantize_layer_workspace_bytes(T, K, N, n_e),
+                 workspace_bytes);
+    // step 1: smoothing vector by grid search; step 2: Hessian-aware quantisation of the folded weight;
+    // step 3 on this device is to keep the int8 codes (the caller packs them for the MFMA kernels)
+    int rc = haq_smoothing_search(x_fp16, ldx, w, T, K, N, exponents, n_e, use_weight, losses, best, s, workspace, workspace_bytes, stream);
+    if (rc != HAQ_OK) return rc;
+    return haq_hessian_quant_weight(x_fp16, ldx, T, w, s, K, N, percdamp, wq, w_scale, workspace, workspace_bytes, stream);
+}
+
 }  // extern "C"

@@ -538,3 +538,21 @@ def test_linear_asym_bit_exact(T, K, N, act, relu_in):
     y2 = haq.haq_w8a8_linear_asym(dev(X), dev(s), haq.haq_pack_weight(wq_d), dev(sw), haq.haq_weight_colsum(wq_d), N,
                                   haq.HAQ_ACT_RELU if act == "relu" else haq.HAQ_ACT_NONE)
     assert bits_equal(host(y2), y_ref)   # the launch without the debug dump
+
+
+# ------------------------------------------------------------------ Algorithm 1 for one layer (search, then Hessian-aware codes)
+@pytest.mark.parametrize("name", ["tiles_and_tails", "opt125m_linear"])
+def test_quantize_layer_matches_oracle_composition(name):
+    X, W = _search_case(name)
+    if name == "opt125m_linear":
+        X = np.concatenate([X, _correlated(95, 496, X.shape[1], 24)])   # more rows than the 16 of the config
+    grid = [0.0, 0.25, 0.5, 0.75, 1.0]
+    losses_ref, best_ref, s_ref = oracle.smoothing_search(X, W, grid)
+    Wq_ref, sw_ref = oracle.hessian_quant_weight(X, W, s_ref, 0.01)
+    s, wq, sw, losses, best = haq.haq_quantize_layer(dev(X), dev(W), grid)
+    assert best == best_ref and np.array_equal(np.asarray(losses), losses_ref)
+    assert bits_equal(host(s), s_ref) and bits_equal(host(sw), sw_ref)
+    assert bits_equal(host(wq), Wq_ref), diff_report(host(wq), Wq_ref)
+    # and the layer it produces runs on the hot path as the oracle's does
+    y = haq.haq_w8a8_linear(dev(X), s, haq.haq_pack_weight(wq), sw, W.shape[1])
+    assert bits_equal(host(y), oracle.w8a8_linear(X, s_ref, Wq_ref, sw_ref))
