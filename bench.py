@@ -36,7 +36,7 @@ PEAK_FP64_TFLOPS = 78.6  # vector fp64 FMA
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
 # of the committed summary profiles/gemm_i8_kernel__opt6.7b_ffn.md and only applies to that workload.
-GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.876e8
+GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.856e+08
 
 
 def _events(torch, n):
