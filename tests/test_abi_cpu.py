@@ -120,3 +120,18 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_algorithm2_reproduces_the_resident_set_of_the_offload_workload():
+    """The offload workload keeps experts 0-3 resident: that is Algorithm 2 on one layer applied to the
+    popularity the workload draws its routing from (stage I: the most likely activation path, stage II: the
+    next two experts by popularity; equal popularities keep index order)."""
+    import itertools
+
+    import haq_inputs as hi
+    wl = hi.MIXTRAL_OFFLOAD
+    pop = list(hi.OFFLOAD_POPULARITY[:wl.E])
+    path_stats = [[((a, b), pop[a] * pop[b]) for a, b in itertools.combinations(range(wl.E), 2)]]
+    sel = haq.haq_select_experts(1, wl.E, 2, 2, path_stats, [pop])
+    assert sel == [[0, 1, 2, 3]] and sorted(sel[0]) == sorted(wl.resident)
+    assert sel == oracle.select_experts(1, 2, 2, path_stats, [list(enumerate(pop))])
