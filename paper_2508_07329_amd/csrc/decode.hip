@@ -28,13 +28,19 @@ constexpr int GU_WAVES = 4;    // gate/up: 64 packed channels (32 gate + 32 up) 
 constexpr int DN_WAVES = 8;    // down: 32 channels per work-group, K split 8 ways
 constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave (two operands each)
 constexpr int DN_DEPTH = 14;
+constexpr int GU_DEPTH2 = 5;   // the same with two row blocks per work-group (twice the token fragments)
+constexpr int DN_DEPTH2 = 9;
 
-// blockIdx.y enumerates the experts that hold rows, in index order (the grid has min(E, 2T)
-// of them: with one token only two experts can be active, and work-groups that find nothing
-// to do would still cost dispatch slots).  Returns -1 past the last active expert.
-__device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, int j) {
+// blockIdx.y enumerates the experts of one class, in index order: NRB = 1: experts with 1..32 rows,
+// NRB = 2: experts with 33..64 rows (one work-group then carries two blocks of 32 rows against the same
+// weight fragments, so that the weights of every activated expert are streamed exactly once).  The grid
+// has min(E, 2T) of them; returns -1 past the last one (those work-groups come last in dispatch order).
+template <int NRB>
+__device__ __forceinline__ int nth_expert_of_class(const int32_t* offsets, int E, int j) {
     for (int e = 0; e < E; ++e) {
-        if (offsets[e + 1] > offsets[e]) {
+        const int rows = offsets[e + 1] - offsets[e];
+        const bool match = NRB == 1 ? (rows > 0 && rows <= 32) : rows > 32;
+        if (match) {
             if (j == 0) return e;
             --j;
         }
@@ -43,16 +49,14 @@ __device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, 
 }
 
 // ---- gate / up projections + SwiGLU + per-unit row maxima of h / s_mid ---------------
-// Work-group (unit, e, rb) handles rows [32*rb, 32*rb + 32) of expert e; row blocks past the
-// expert's rows leave at once (rb is the slowest grid dimension, so those empty work-groups
-// come after all the streaming ones instead of taking slots between them).
+// Work-group (unit, j): unit of 64 packed channels of the j-th expert of the class; all its rows.
+template <int NRB, int DEPTH>
 __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
     __shared__ int part[GU_WAVES][2][16][64];
     __shared__ float wmax[GU_WAVES][32];
-    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y), unit = blockIdx.x, rb = blockIdx.z;
+    const int e = nth_expert_of_class<NRB>(a.offsets, a.E, blockIdx.y), unit = blockIdx.x;
     if (e < 0) return;
-    const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
-    if (m <= 0) return;
+    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = a.tab[e];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -60,91 +64,105 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(Decode
     const int cpw = nchunk / GU_WAVES;  // chunks per wave (even)
     const int c0 = wave * cpw + hi;     // this lane's first chunk; it advances by 2 per MFMA
     const int64_t npad = a.Npad13;
-    // running pointers to the next k-step to fetch (gate fragment; the up fragment is 512 bytes further)
+    // running pointers to the next k-step to fetch (gate fragment; the up fragment is 512 bytes further;
+    // the token rows of the second row block are 32 rows = 512 bytes further)
     const int8_t* pw = t.w13 + ((size_t)c0 * npad + unit * 64 + l32) * 16;
     const size_t wstep = (size_t)2 * npad * 16;
     const int8_t* px = a.q_cm + ((size_t)c0 * a.R + lo + l32) * 16;
     const size_t xstep = (size_t)2 * a.R * 16;
 
-    v16i accg, accu;
+    v16i accg[NRB], accu[NRB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) accg[r] = accu[r] = 0;
+    for (int b = 0; b < NRB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accg[b][r] = accu[b][r] = 0;
 
-    // rolling prefetch: GU_DEPTH k-steps of fragments are always in flight.  Straight-line groups of
-    // GU_DEPTH steps (fill, steady state, drain), then a plain loop for what is left.
+    // rolling prefetch: DEPTH k-steps of fragments are always in flight.  Straight-line groups of
+    // DEPTH steps (fill, steady state, drain), then a plain loop for what is left.
     const int nks = cpw / 2;
-    const int ngroups = nks / GU_DEPTH;
-    auto fetch = [&](v4i& g, v4i& u, v4i& x) {
-        g = gload16(pw);
-        u = gload16(pw + 512);
-        x = gload16(px);
+    const int ngroups = nks / DEPTH;
+    struct Frag {
+        v4i g, u, x[NRB];
+    };
+    auto fetch = [&](Frag& f) {
+        f.g = gload16(pw);
+        f.u = gload16(pw + 512);
+#pragma unroll
+        for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
         pw += wstep;
         px += xstep;
     };
-    if (ngroups > 0) {
-        v4i fg[GU_DEPTH], fu[GU_DEPTH], fx[GU_DEPTH];
+    auto mac = [&](const Frag& f) {
 #pragma unroll
-        for (int i = 0; i < GU_DEPTH; ++i) fetch(fg[i], fu[i], fx[i]);
+        for (int b = 0; b < NRB; ++b) {
+            accg[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.g, f.x[b], accg[b], 0, 0, 0);
+            accu[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.u, f.x[b], accu[b], 0, 0, 0);
+        }
+    };
+    if (ngroups > 0) {
+        Frag fr[DEPTH];
+#pragma unroll
+        for (int i = 0; i < DEPTH; ++i) fetch(fr[i]);
         for (int grp = 0; grp + 1 < ngroups; ++grp) {
 #pragma unroll
-            for (int i = 0; i < GU_DEPTH; ++i) {
-                const v4i g = fg[i], u = fu[i], x = fx[i];
-                fetch(fg[i], fu[i], fx[i]);
-                accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(g, x, accg, 0, 0, 0);
-                accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(u, x, accu, 0, 0, 0);
+            for (int i = 0; i < DEPTH; ++i) {
+                const Frag f = fr[i];
+                fetch(fr[i]);
+                mac(f);
             }
         }
 #pragma unroll
-        for (int i = 0; i < GU_DEPTH; ++i) {
-            accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(fg[i], fx[i], accg, 0, 0, 0);
-            accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(fu[i], fx[i], accu, 0, 0, 0);
-        }
+        for (int i = 0; i < DEPTH; ++i) mac(fr[i]);
     }
-    for (int k = ngroups * GU_DEPTH; k < nks; ++k) {
-        v4i g, u, x;
-        fetch(g, u, x);
-        accg = __builtin_amdgcn_mfma_i32_32x32x32_i8(g, x, accg, 0, 0, 0);
-        accu = __builtin_amdgcn_mfma_i32_32x32x32_i8(u, x, accu, 0, 0, 0);
+    for (int k = ngroups * DEPTH; k < nks; ++k) {
+        Frag f;
+        fetch(f);
+        mac(f);
     }
-    // exact int32 reduction over the K split
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        part[wave][0][r][lane] = accg[r];
-        part[wave][1][r][lane] = accu[r];
-    }
-    __syncthreads();
-    // wave w finishes registers 4w..4w+3: channels 8w + 4*hi + 0..3 of the unit, token row l32
+    // wave w finishes registers 4w..4w+3: channels 8w + 4*hi + 0..3 of the unit, token row l32 of a row block
     const int ch = unit * 32 + 8 * wave + 4 * hi;
     const float4 s1 = *reinterpret_cast<const float4*>(t.sw1 + ch);
     const float4 s3 = *reinterpret_cast<const float4*>(t.sw3 + ch);
     const float4 sm = *reinterpret_cast<const float4*>(t.s_mid + ch);
     const float s1v[4] = {s1.x, s1.y, s1.z, s1.w}, s3v[4] = {s3.x, s3.y, s3.z, s3.w}, smv[4] = {sm.x, sm.y, sm.z, sm.w};
-    const bool live = l32 < m;
-    const float sx = live ? a.sx[lo + l32] : 0.0f;
-    __half hv[4];
-    float ymax = 0.0f;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        int g = 0, u = 0;
+    for (int b = 0; b < NRB; ++b) {
+        if (b > 0) __syncthreads();  // part and wmax are reused
+        // exact int32 reduction over the K split
 #pragma unroll
-        for (int w = 0; w < GU_WAVES; ++w) {
-            g += part[w][0][4 * wave + q][lane];
-            u += part[w][1][4 * wave + q][lane];
+        for (int r = 0; r < 16; ++r) {
+            part[wave][0][r][lane] = accg[b][r];
+            part[wave][1][r][lane] = accu[b][r];
         }
-        const float gf = dequant(g, sx, s1v[q]), uf = dequant(u, sx, s3v[q]);
-        hv[q] = f2h(silu(gf) * uf);
-        ymax = fmaxf(ymax, fabsf(h2f(hv[q]) / smv[q]));
-    }
-    if (live) *reinterpret_cast<uint2*>(a.mid + (size_t)(lo + l32) * a.I + ch) = *reinterpret_cast<const uint2*>(hv);
-    ymax = fmaxf(ymax, __shfl_xor(ymax, 32));
-    if (hi == 0) wmax[wave][l32] = ymax;
-    __syncthreads();
-    // one partial row maximum of |h / s_mid| per (row, unit): reduced by the requantisation kernel
-    if (tid < 32 && tid < m) {
-        float v = 0.0f;
+        __syncthreads();
+        const int row = 32 * b + l32;
+        const bool live = row < m;
+        const float sx = live ? a.sx[lo + row] : 0.0f;
+        __half hv[4];
+        float ymax = 0.0f;
 #pragma unroll
-        for (int w = 0; w < GU_WAVES; ++w) v = fmaxf(v, wmax[w][tid]);
-        a.pmax[(size_t)(lo + tid) * (a.I / 32) + unit] = v;
+        for (int q = 0; q < 4; ++q) {
+            int g = 0, u = 0;
+#pragma unroll
+            for (int w = 0; w < GU_WAVES; ++w) {
+                g += part[w][0][4 * wave + q][lane];
+                u += part[w][1][4 * wave + q][lane];
+            }
+            const float gf = dequant(g, sx, s1v[q]), uf = dequant(u, sx, s3v[q]);
+            hv[q] = f2h(silu(gf) * uf);
+            ymax = fmaxf(ymax, fabsf(h2f(hv[q]) / smv[q]));
+        }
+        if (live) *reinterpret_cast<uint2*>(a.mid + (size_t)(lo + row) * a.I + ch) = *reinterpret_cast<const uint2*>(hv);
+        ymax = fmaxf(ymax, __shfl_xor(ymax, 32));
+        if (hi == 0) wmax[wave][l32] = ymax;
+        __syncthreads();
+        // one partial row maximum of |h / s_mid| per (row, unit): reduced by the requantisation kernel
+        if (tid < 32 && 32 * b + tid < m) {
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < GU_WAVES; ++w) v = fmaxf(v, wmax[w][tid]);
+            a.pmax[(size_t)(lo + 32 * b + tid) * (a.I / 32) + unit] = v;
+        }
     }
 }
 
@@ -228,12 +246,12 @@ __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a
 }
 
 // ---- down projection ---------------------------------------------------------------------
+template <int NRB, int DEPTH>
 __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
     __shared__ int part[DN_WAVES][16][64];
-    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y), unit = blockIdx.x, rb = blockIdx.z;
+    const int e = nth_expert_of_class<NRB>(a.offsets, a.E, blockIdx.y), unit = blockIdx.x;
     if (e < 0) return;
-    const int lo = a.offsets[e] + rb * 32, m = a.offsets[e + 1] - lo;
-    if (m <= 0) return;
+    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = a.tab[e];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -246,55 +264,70 @@ __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArg
     const int8_t* px = a.hq_cm + ((size_t)c0 * a.R + lo + l32) * 16;
     const size_t xstep = (size_t)2 * a.R * 16;
 
-    v16i acc;
+    v16i acc[NRB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    for (int b = 0; b < NRB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0;
 
     const int nks = cpw / 2;
-    const int ngroups = nks / DN_DEPTH;
-    auto fetch = [&](v4i& w, v4i& x) {
-        w = gload16(pw);
-        x = gload16(px);
+    const int ngroups = nks / DEPTH;
+    struct Frag {
+        v4i w, x[NRB];
+    };
+    auto fetch = [&](Frag& f) {
+        f.w = gload16(pw);
+#pragma unroll
+        for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
         pw += wstep;
         px += xstep;
     };
-    if (ngroups > 0) {
-        v4i fw[DN_DEPTH], fx[DN_DEPTH];
+    auto mac = [&](const Frag& f) {
 #pragma unroll
-        for (int i = 0; i < DN_DEPTH; ++i) fetch(fw[i], fx[i]);
+        for (int b = 0; b < NRB; ++b) acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w, f.x[b], acc[b], 0, 0, 0);
+    };
+    if (ngroups > 0) {
+        Frag fr[DEPTH];
+#pragma unroll
+        for (int i = 0; i < DEPTH; ++i) fetch(fr[i]);
         for (int grp = 0; grp + 1 < ngroups; ++grp) {
 #pragma unroll
-            for (int i = 0; i < DN_DEPTH; ++i) {
-                const v4i w = fw[i], x = fx[i];
-                fetch(fw[i], fx[i]);
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
+            for (int i = 0; i < DEPTH; ++i) {
+                const Frag f = fr[i];
+                fetch(fr[i]);
+                mac(f);
             }
         }
 #pragma unroll
-        for (int i = 0; i < DN_DEPTH; ++i) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fx[i], acc, 0, 0, 0);
+        for (int i = 0; i < DEPTH; ++i) mac(fr[i]);
     }
-    for (int k = ngroups * DN_DEPTH; k < nks; ++k) {
-        v4i w, x;
-        fetch(w, x);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, acc, 0, 0, 0);
+    for (int k = ngroups * DEPTH; k < nks; ++k) {
+        Frag f;
+        fetch(f);
+        mac(f);
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[r];
-    __syncthreads();
     // wave w finishes registers 2w, 2w+1: channels 8*(r/4) + 4*hi + r%4 of the unit
-    const bool live = l32 < m;
-    const float sh = live ? a.sh[lo + l32] : 0.0f;
     const int r0 = 2 * wave;
     const int ch = unit * 32 + 8 * (r0 / 4) + 4 * hi + (r0 % 4);
-    __half hv[2];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        int v = 0;
+    for (int b = 0; b < NRB; ++b) {
+        if (b > 0) __syncthreads();  // part is reused
 #pragma unroll
-        for (int w = 0; w < DN_WAVES; ++w) v += part[w][r0 + q][lane];
-        hv[q] = f2h(dequant(v, sh, t.sw2[ch + q]));
+        for (int r = 0; r < 16; ++r) part[wave][r][lane] = acc[b][r];
+        __syncthreads();
+        const int row = 32 * b + l32;
+        const bool live = row < m;
+        const float sh = live ? a.sh[lo + row] : 0.0f;
+        __half hv[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            int v = 0;
+#pragma unroll
+            for (int w = 0; w < DN_WAVES; ++w) v += part[w][r0 + q][lane];
+            hv[q] = f2h(dequant(v, sh, t.sw2[ch + q]));
+        }
+        if (live) *reinterpret_cast<uint32_t*>(a.y + (size_t)(lo + row) * a.H + ch) = *reinterpret_cast<const uint32_t*>(hv);
     }
-    if (live) *reinterpret_cast<uint32_t*>(a.y + (size_t)(lo + l32) * a.H + ch) = *reinterpret_cast<const uint32_t*>(hv);
 }
 
 }  // namespace
@@ -303,17 +336,20 @@ bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 3
 
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
-    // an expert holds at most T rows: one work-group per (unit, block of 32 rows)
-    const int nrb = cdiv(T, 32);
+    // an expert holds at most T <= 64 rows: experts with up to 32 rows take the kernels with one row block,
+    // the others (possible only when T > 32) the kernels with two; every expert's weights are streamed once
     const int ne = a.E < P ? a.E : P;  // at most 2T experts can hold rows
-    const dim3 g1(a.I / 32, ne, nrb), g2(a.H / 32, ne, nrb);
-    hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
+    const int ne2 = T > 32 ? (a.E < P / 33 ? a.E : P / 33) : 0;  // experts with more than 32 rows: at most 2T / 33
+    const dim3 g1(a.I / 32, ne), g2(a.H / 32, ne);
+    hipLaunchKernelGGL((decode_gate_up_kernel<1, GU_DEPTH>), g1, dim3(GU_WAVES * 64), 0, st, a);
+    if (ne2 > 0) hipLaunchKernelGGL((decode_gate_up_kernel<2, GU_DEPTH2>), dim3(a.I / 32, ne2), dim3(GU_WAVES * 64), 0, st, a);
     {
         const int nchunk = a.I / 16;
         const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
         hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(thr), 0, st, a);
     }
-    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL((decode_down_kernel<1, DN_DEPTH>), g2, dim3(DN_WAVES * 64), 0, st, a);
+    if (ne2 > 0) hipLaunchKernelGGL((decode_down_kernel<2, DN_DEPTH2>), dim3(a.H / 32, ne2), dim3(DN_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

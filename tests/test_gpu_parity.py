@@ -241,6 +241,17 @@ def test_moe_small_decode_path_bit_exact(T, H, I, E):
     _check_moe(offline.small_moe(seed=40 + T, T=T, H=H, I=I, E=E))
 
 
+def test_moe_decode_path_experts_with_more_than_32_rows():
+    """Weight-streaming path with skewed routing: expert 0 takes every token (64 rows: two row blocks in
+    one pass), another one more than 32, the rest few or none."""
+    m = offline.small_moe(seed=44, T=64, H=256, I=512, E=8, routing="popularity")
+    m["logits"][:, 0] = 50                      # everybody's first choice
+    m["logits"][:40, 3] = 40                    # 40 tokens' second choice
+    m["logits"][:, 6] = -100                    # nobody's
+    counts = _check_moe(m)
+    assert counts[0] == 64 and 40 <= counts[3] <= 64 and counts[6] == 0 and 0 < counts[1] <= 32
+
+
 def test_moe_small_skewed_routing_and_empty_expert():
     m = offline.small_moe(seed=31, T=64, H=128, I=192, E=8, routing="popularity")
     m["logits"][:, 5] = -100  # nobody picks expert 5
