@@ -31,16 +31,12 @@ constexpr int DN_DEPTH = 14;
 constexpr int GU_DEPTH2 = 5;   // the same with two row blocks per work-group (twice the token fragments)
 constexpr int DN_DEPTH2 = 9;
 
-// blockIdx.y enumerates the experts of one class, in index order: NRB = 1: experts with 1..32 rows,
-// NRB = 2: experts with 33..64 rows (one work-group then carries two blocks of 32 rows against the same
-// weight fragments, so that the weights of every activated expert are streamed exactly once).  The grid
-// has min(E, 2T) of them; returns -1 past the last one (those work-groups come last in dispatch order).
-template <int NRB>
-__device__ __forceinline__ int nth_expert_of_class(const int32_t* offsets, int E, int j) {
+// blockIdx.y enumerates the experts that hold rows, in index order (the grid has min(E, 2T) of
+// them: with one token only two experts can be active, and work-groups that find nothing to do
+// would still cost dispatch slots).  Returns -1 past the last active expert.
+__device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, int j) {
     for (int e = 0; e < E; ++e) {
-        const int rows = offsets[e + 1] - offsets[e];
-        const bool match = NRB == 1 ? (rows > 0 && rows <= 32) : rows > 32;
-        if (match) {
+        if (offsets[e + 1] > offsets[e]) {
             if (j == 0) return e;
             --j;
         }
@@ -49,13 +45,11 @@ __device__ __forceinline__ int nth_expert_of_class(const int32_t* offsets, int E
 }
 
 // ---- gate / up projections + SwiGLU + per-unit row maxima of h / s_mid ---------------
-// Work-group (unit, j): unit of 64 packed channels of the j-th expert of the class; all its rows.
+// Work-group (unit, j): unit of 64 packed channels of the j-th active expert, all its rows: NRB = 1
+// for up to 32 rows, NRB = 2 for 33..64 (two blocks of 32 rows against the same weight fragments, so
+// that the weights of every activated expert are streamed exactly once).
 template <int NRB, int DEPTH>
-__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
-    __shared__ int part[GU_WAVES][2][16][64];
-    __shared__ float wmax[GU_WAVES][32];
-    const int e = nth_expert_of_class<NRB>(a.offsets, a.E, blockIdx.y), unit = blockIdx.x;
-    if (e < 0) return;
+__device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int unit, int (*part)[2][16][64], float (*wmax)[32]) {
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = a.tab[e];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -166,6 +160,17 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(Decode
     }
 }
 
+__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
+    __shared__ int part[GU_WAVES][2][16][64];
+    __shared__ float wmax[GU_WAVES][32];
+    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
+    if (e < 0) return;
+    if (a.offsets[e + 1] - a.offsets[e] > 32)  // uniform over the work-group
+        gate_up_body<2, GU_DEPTH2>(a, e, blockIdx.x, part, wmax);
+    else
+        gate_up_body<1, GU_DEPTH>(a, e, blockIdx.x, part, wmax);
+}
+
 // ---- requantisation of the intermediate with known partial maxima ------------------------
 // One work-group per sorted row, one thread per 16-channel chunk (as many threads as the row
 // has chunks, up to 1024): reduce the row's partial maxima, then round h / s_mid / scale; the
@@ -247,10 +252,7 @@ __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a
 
 // ---- down projection ---------------------------------------------------------------------
 template <int NRB, int DEPTH>
-__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
-    __shared__ int part[DN_WAVES][16][64];
-    const int e = nth_expert_of_class<NRB>(a.offsets, a.E, blockIdx.y), unit = blockIdx.x;
-    if (e < 0) return;
+__device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, int (*part)[16][64]) {
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = a.tab[e];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -330,26 +332,31 @@ __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArg
     }
 }
 
+__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
+    __shared__ int part[DN_WAVES][16][64];
+    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
+    if (e < 0) return;
+    if (a.offsets[e + 1] - a.offsets[e] > 32)  // uniform over the work-group
+        down_body<2, DN_DEPTH2>(a, e, blockIdx.x, part);
+    else
+        down_body<1, DN_DEPTH>(a, e, blockIdx.x, part);
+}
+
 }  // namespace
 
 bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 32) == 0 && I % (DN_WAVES * 32) == 0; }
 
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
-    // an expert holds at most T <= 64 rows: experts with up to 32 rows take the kernels with one row block,
-    // the others (possible only when T > 32) the kernels with two; every expert's weights are streamed once
     const int ne = a.E < P ? a.E : P;  // at most 2T experts can hold rows
-    const int ne2 = T > 32 ? (a.E < P / 33 ? a.E : P / 33) : 0;  // experts with more than 32 rows: at most 2T / 33
     const dim3 g1(a.I / 32, ne), g2(a.H / 32, ne);
-    hipLaunchKernelGGL((decode_gate_up_kernel<1, GU_DEPTH>), g1, dim3(GU_WAVES * 64), 0, st, a);
-    if (ne2 > 0) hipLaunchKernelGGL((decode_gate_up_kernel<2, GU_DEPTH2>), dim3(a.I / 32, ne2), dim3(GU_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
     {
         const int nchunk = a.I / 16;
         const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
         hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(thr), 0, st, a);
     }
-    hipLaunchKernelGGL((decode_down_kernel<1, DN_DEPTH>), g2, dim3(DN_WAVES * 64), 0, st, a);
-    if (ne2 > 0) hipLaunchKernelGGL((decode_down_kernel<2, DN_DEPTH2>), dim3(a.H / 32, ne2), dim3(DN_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
