@@ -286,8 +286,9 @@ def haq_ctx_destroy(ctx) -> None:
 
 
 def haq_moe_w8a8_ffn(x, logits, s_in, experts: list[ExpertWeights], I: int, *, ctx=None, out=None, workspace=None,
-                     debug: bool = False):
-    """x fp16 [T,H], logits fp16 [T,E] -> out fp16 [T,H] (and a MoeDebug when debug=True)."""
+                     debug=False):
+    """x fp16 [T,H], logits fp16 [T,E] -> out fp16 [T,H] (and a MoeDebug when debug is set: True asks for
+    every intermediate, a tuple of field names for those only -- the others stay None)."""
     T, H = x.shape
     E = len(experts)
     dev = x.device
@@ -305,9 +306,13 @@ def haq_moe_w8a8_ffn(x, logits, s_in, experts: list[ExpertWeights], I: int, *, c
         P = 2 * T
         i32, f32, f16, i8 = torch.int32, torch.float32, torch.float16, torch.int8
         mk = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
-        dbg = MoeDebug(mk((T, 2), i32), mk((T, 2), f32), mk((E,), i32), mk((E + 1,), i32), mk((P,), i32), mk((P,), i32),
-                       mk((T, H), i8), mk((T,), f32), mk((P, I), f16), mk((P, I), i8), mk((P,), f32), mk((P, H), f16))
-        dbg_c = _MoeDebug(*[getattr(dbg, n).data_ptr() for n in _DBG_FIELDS])
+        spec = (((T, 2), i32), ((T, 2), f32), ((E,), i32), ((E + 1,), i32), ((P,), i32), ((P,), i32),
+                ((T, H), i8), ((T,), f32), ((P, I), f16), ((P, I), i8), ((P,), f32), ((P, H), f16))
+        want = _DBG_FIELDS if debug is True else tuple(debug)
+        if set(want) - set(_DBG_FIELDS):
+            raise ValueError(f"unknown debug fields {sorted(set(want) - set(_DBG_FIELDS))}")
+        dbg = MoeDebug(*[mk(*sp) if n in want else None for n, sp in zip(_DBG_FIELDS, spec)])
+        dbg_c = _MoeDebug(*[getattr(dbg, n).data_ptr() if n in want else None for n in _DBG_FIELDS])
     _check(lib().haq_moe_w8a8_ffn(ctx, _ptr(x), C.c_int64(x.stride(0)), _ptr(logits), C.c_int64(logits.stride(0)),
                                   _ptr(s_in), descs, T, H, I, E, 2, _ptr(y), C.c_int64(y.stride(0)),
                                   C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),

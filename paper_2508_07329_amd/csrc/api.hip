@@ -451,7 +451,11 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
 
     int rc;
     const bool decode_path = n_host == 0 && decode_supported(T, H, I);
-    if (decode_path && decode_prologue_supported(T, H)) {
+    // one or two tokens, and none of the intermediate outputs the fused kernels keep on chip is asked for
+    const bool tiny_path = decode_path && decode_tiny_supported(T, H, I) && !d.q && !d.sx && !d.hq && !d.sh;
+    if (tiny_path) {
+        // routing and token quantisation happen inside the gate/up launch below
+    } else if (decode_path && decode_prologue_supported(T, H)) {
         // few tokens: routing, permutation and token quantisation in one launch
         if ((rc = launch_decode_prologue((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv,
                                          (const __half*)x_fp16, ldx, s_in, H, w.q_cm, w.R, d.q, d.sx, w.sx_sorted, st)) != HAQ_OK)
@@ -496,7 +500,12 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         da.hq_rm = d.hq;
         da.sh = sh;
         da.y = y;
-        if ((rc = launch_decode(da, T, st)) != HAQ_OK) return rc;
+        if (tiny_path)
+            rc = launch_decode_tiny(da, (const __half*)logits_fp16, ldl, (const __half*)x_fp16, ldx, s_in, T, tab, idx, gw, counts,
+                                    offsets, perm, inv, w.tab, st);
+        else
+            rc = launch_decode(da, T, st);
+        if (rc != HAQ_OK) return rc;
         return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
     }
 

@@ -14,6 +14,7 @@
 #include "haq_common.h"
 #include "moe.h"
 #include "quant_math.h"
+#include "routing.h"
 
 namespace haq {
 
@@ -48,10 +49,15 @@ __device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, 
 // Work-group (unit, j): unit of 64 packed channels of the j-th active expert, all its rows: NRB = 1
 // for up to 32 rows, NRB = 2 for 33..64 (two blocks of 32 rows against the same weight fragments, so
 // that the weights of every activated expert are streamed exactly once).
-template <int NRB, int DEPTH>
-__device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int unit, int (*part)[2][16][64], float (*wmax)[32]) {
-    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
-    const ExpertTab& t = a.tab[e];
+//
+// XLDS: the token codes and their scales do not come from memory but from LDS (rows of H bytes at
+// xl, scales at sxl), where `prep` -- called once the first weight fragments are in flight --
+// leaves them; lanes past the last row read the last row (their results are dropped).
+template <int NRB, int DEPTH, bool XLDS, class Prep>
+__device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTab& t, int lo, int m, int unit,
+                                             int (*part)[2][16][64], float (*wmax)[32], const int8_t* xl, const float* sxl,
+                                             Prep&& prep) {
+    static_assert(!XLDS || NRB == 1, "the LDS variant carries one row block");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int nchunk = a.H / 16;
@@ -62,14 +68,10 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int uni
     // the token rows of the second row block are 32 rows = 512 bytes further)
     const int8_t* pw = t.w13 + ((size_t)c0 * npad + unit * 64 + l32) * 16;
     const size_t wstep = (size_t)2 * npad * 16;
-    const int8_t* px = a.q_cm + ((size_t)c0 * a.R + lo + l32) * 16;
-    const size_t xstep = (size_t)2 * a.R * 16;
+    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.H + c0 * 16 : a.q_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    const size_t xstep = XLDS ? 32 : (size_t)2 * a.R * 16;
 
     v16i accg[NRB], accu[NRB];
-#pragma unroll
-    for (int b = 0; b < NRB; ++b)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) accg[b][r] = accu[b][r] = 0;
 
     // rolling prefetch: DEPTH k-steps of fragments are always in flight.  Straight-line groups of
     // DEPTH steps (fill, steady state, drain), then a plain loop for what is left.
@@ -81,22 +83,38 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int uni
     auto fetch = [&](Frag& f) {
         f.g = gload16(pw);
         f.u = gload16(pw + 512);
-#pragma unroll
-        for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
         pw += wstep;
-        px += xstep;
-    };
-    auto mac = [&](const Frag& f) {
+        if constexpr (!XLDS) {
 #pragma unroll
-        for (int b = 0; b < NRB; ++b) {
-            accg[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.g, f.x[b], accg[b], 0, 0, 0);
-            accu[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.u, f.x[b], accu[b], 0, 0, 0);
+            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
+            px += xstep;
         }
     };
+    auto mac = [&](const Frag& f) {
+        if constexpr (XLDS) {
+            const v4i xv = *reinterpret_cast<const v4i*>(px);
+            px += xstep;
+            accg[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.g, xv, accg[0], 0, 0, 0);
+            accu[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.u, xv, accu[0], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int b = 0; b < NRB; ++b) {
+                accg[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.g, f.x[b], accg[b], 0, 0, 0);
+                accu[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.u, f.x[b], accu[b], 0, 0, 0);
+            }
+        }
+    };
+    Frag fr[DEPTH];
     if (ngroups > 0) {
-        Frag fr[DEPTH];
 #pragma unroll
         for (int i = 0; i < DEPTH; ++i) fetch(fr[i]);
+    }
+    prep();
+#pragma unroll
+    for (int b = 0; b < NRB; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accg[b][r] = accu[b][r] = 0;
+    if (ngroups > 0) {
         for (int grp = 0; grp + 1 < ngroups; ++grp) {
 #pragma unroll
             for (int i = 0; i < DEPTH; ++i) {
@@ -113,6 +131,7 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int uni
         fetch(f);
         mac(f);
     }
+    if constexpr (XLDS) __syncthreads();  // the codes may share LDS with `part`
     // wave w finishes registers 4w..4w+3: channels 8w + 4*hi + 0..3 of the unit, token row l32 of a row block
     const int ch = unit * 32 + 8 * wave + 4 * hi;
     const float4 s1 = *reinterpret_cast<const float4*>(t.sw1 + ch);
@@ -131,7 +150,7 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, int e, int uni
         __syncthreads();
         const int row = 32 * b + l32;
         const bool live = row < m;
-        const float sx = live ? a.sx[lo + row] : 0.0f;
+        const float sx = live ? (XLDS ? sxl[row] : a.sx[lo + row]) : 0.0f;
         __half hv[4];
         float ymax = 0.0f;
 #pragma unroll
@@ -165,10 +184,66 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(Decode
     __shared__ float wmax[GU_WAVES][32];
     const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
     if (e < 0) return;
-    if (a.offsets[e + 1] - a.offsets[e] > 32)  // uniform over the work-group
-        gate_up_body<2, GU_DEPTH2>(a, e, blockIdx.x, part, wmax);
+    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
+    if (m > 32)  // uniform over the work-group
+        gate_up_body<2, GU_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {});
     else
-        gate_up_body<1, GU_DEPTH>(a, e, blockIdx.x, part, wmax);
+        gate_up_body<1, GU_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {});
+}
+
+// One or two tokens: routing, the stable grouping of the pairs and the quantisation of the
+// expert's token rows are repeated by every work-group (cheap next to the 256 KB of weights it
+// streams, and hidden behind its first weight fragments), so the layer needs no launch before
+// this one.  Work-group (0, 0) leaves the routing results for the kernels that follow.
+struct TinyArgs {
+    const __half* logits;
+    int64_t ldl;
+    const __half* x;
+    int64_t ldx;
+    const float* s;  // smoothing vector of the layer input (null: all ones)
+    int T;
+    int32_t *idx, *counts, *offsets, *perm, *inv;
+    float* gw;
+    ExpertTab* tab_dev;
+};
+
+template <int NCH>
+__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_tiny_gate_up_kernel(DecodeArgs a, TinyArgs r, TabAll tab) {
+    __shared__ int part[GU_WAVES][2][16][64];  // the token codes live here until the K loop is over
+    __shared__ float wmax[GU_WAVES][32];
+    __shared__ RouteLds rt;
+    __shared__ float s_red[GU_WAVES], s_sx[2];
+    const int tid = threadIdx.x;
+    const int P = 2 * r.T;
+    route_in_lds(r.logits, r.ldl, r.T, a.E, rt);
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        if (tid < a.E) {
+            r.tab_dev[tid] = tab.e[tid];
+            r.counts[tid] = rt.cnt[tid];
+        }
+        if (tid <= a.E) r.offsets[tid] = rt.off[tid];
+        if (tid < P) {
+            r.idx[tid] = rt.idx[tid];
+            r.gw[tid] = rt.gw[tid];
+            r.perm[rt.pos[tid]] = tid;
+            r.inv[tid] = rt.pos[tid];
+        }
+    }
+    const int e = nth_active_expert(rt.off, a.E, blockIdx.y);
+    if (e < 0) return;
+    const int lo = rt.off[e], m = rt.cnt[e];  // m <= 2: one pair per token at most
+    int8_t* xq = reinterpret_cast<int8_t*>(part);
+    gate_up_body<1, GU_DEPTH, true>(a, tab.e[e], lo, m, blockIdx.x, part, wmax, xq, s_sx, [&] {
+#pragma nounroll
+        for (int row = 0; row < m; ++row) {
+            const int tok = rt.src[lo + row] >> 1;
+            const float scale = quantise_row<GU_WAVES * 64, NCH>(r.x + (size_t)tok * r.ldx, r.s, a.H / 16, s_red, [&](int c, uint4 v) {
+                *reinterpret_cast<uint4*>(xq + (size_t)row * a.H + c * 16) = v;
+            });
+            if (tid == 0) s_sx[row] = scale;
+        }
+        __syncthreads();
+    });
 }
 
 // ---- requantisation of the intermediate with known partial maxima ------------------------
@@ -216,45 +291,24 @@ __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a
     const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
     if (tid == 0) a.sh[pos] = scale;
     for (int c = tid; c < nchunk; c += nthr) {
-        uint32_t w[4] = {0, 0, 0, 0};
-        if (m != 0.0f) {
-            if (!single) {
-                const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
-                r0 = px[0];
-                r1 = px[1];
+        if (!single && m != 0.0f) {
+            const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
+            r0 = px[0];
+            r1 = px[1];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sv[i] = s[c * 16 + i];
-            }
-            const __half* h0 = reinterpret_cast<const __half*>(&r0);
-            const __half* h1 = reinterpret_cast<const __half*>(&r1);
-            if (sfast) {
-                float q[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
-                    q[i] = div_by(y, scale, rscale, true);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
-                    w[i / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (i % 4));
-                }
-            }
+            for (int i = 0; i < 16; ++i) sv[i] = s[c * 16 + i];
         }
-        const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+        const uint4 v = requant_chunk(r0, r1, sv, m, scale, rscale, sfast);
         *reinterpret_cast<uint4*>(a.hq_cm + ((size_t)c * a.R + pos) * 16) = v;
         if (a.hq_rm) *reinterpret_cast<uint4*>(a.hq_rm + (size_t)pos * a.I + c * 16) = v;
     }
 }
 
 // ---- down projection ---------------------------------------------------------------------
-template <int NRB, int DEPTH>
-__device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, int (*part)[16][64]) {
-    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
-    const ExpertTab& t = a.tab[e];
+template <int NRB, int DEPTH, bool XLDS, class Prep>
+__device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& t, int lo, int m, int unit, int (*part)[16][64],
+                                          const int8_t* xl, const float* shl, Prep&& prep) {
+    static_assert(!XLDS || NRB == 1, "the LDS variant carries one row block");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int nchunk = a.I / 16;
@@ -263,8 +317,8 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, 
     const int64_t npad = a.Npad2;
     const int8_t* pw = t.w2 + ((size_t)c0 * npad + unit * 32 + l32) * 16;  // next k-step to fetch
     const size_t wstep = (size_t)2 * npad * 16;
-    const int8_t* px = a.hq_cm + ((size_t)c0 * a.R + lo + l32) * 16;
-    const size_t xstep = (size_t)2 * a.R * 16;
+    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.I + c0 * 16 : a.hq_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    const size_t xstep = XLDS ? 32 : (size_t)2 * a.R * 16;
 
     v16i acc[NRB];
 #pragma unroll
@@ -279,19 +333,30 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, 
     };
     auto fetch = [&](Frag& f) {
         f.w = gload16(pw);
-#pragma unroll
-        for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
         pw += wstep;
-        px += xstep;
+        if constexpr (!XLDS) {
+#pragma unroll
+            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
+            px += xstep;
+        }
     };
     auto mac = [&](const Frag& f) {
+        if constexpr (XLDS) {
+            const v4i xv = *reinterpret_cast<const v4i*>(px);
+            px += xstep;
+            acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w, xv, acc[0], 0, 0, 0);
+        } else {
 #pragma unroll
-        for (int b = 0; b < NRB; ++b) acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w, f.x[b], acc[b], 0, 0, 0);
+            for (int b = 0; b < NRB; ++b) acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w, f.x[b], acc[b], 0, 0, 0);
+        }
     };
+    Frag fr[DEPTH];
     if (ngroups > 0) {
-        Frag fr[DEPTH];
 #pragma unroll
         for (int i = 0; i < DEPTH; ++i) fetch(fr[i]);
+    }
+    prep();
+    if (ngroups > 0) {
         for (int grp = 0; grp + 1 < ngroups; ++grp) {
 #pragma unroll
             for (int i = 0; i < DEPTH; ++i) {
@@ -308,6 +373,7 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, 
         fetch(f);
         mac(f);
     }
+    if constexpr (XLDS) __syncthreads();  // the codes may share LDS with `part`
     // wave w finishes registers 2w, 2w+1: channels 8*(r/4) + 4*hi + r%4 of the unit
     const int r0 = 2 * wave;
     const int ch = unit * 32 + 8 * (r0 / 4) + 4 * hi + (r0 % 4);
@@ -319,7 +385,7 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, int e, int unit, 
         __syncthreads();
         const int row = 32 * b + l32;
         const bool live = row < m;
-        const float sh = live ? a.sh[lo + row] : 0.0f;
+        const float sh = live ? (XLDS ? shl[row] : a.sh[lo + row]) : 0.0f;
         __half hv[2];
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -336,13 +402,89 @@ __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArg
     __shared__ int part[DN_WAVES][16][64];
     const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
     if (e < 0) return;
-    if (a.offsets[e + 1] - a.offsets[e] > 32)  // uniform over the work-group
-        down_body<2, DN_DEPTH2>(a, e, blockIdx.x, part);
+    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
+    if (m > 32)  // uniform over the work-group
+        down_body<2, DN_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
     else
-        down_body<1, DN_DEPTH>(a, e, blockIdx.x, part);
+        down_body<1, DN_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
+}
+
+// One or two tokens: every work-group requantises the expert's one or two rows of the
+// intermediate itself (partial row maxima from the gate/up kernel, the arithmetic of
+// decode_requant_kernel) while its first weight fragments are in flight, so no launch sits
+// between the two projections.
+__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_tiny_down_kernel(DecodeArgs a, TabAll tab) {
+    __shared__ int part[DN_WAVES][16][64];  // the intermediate's codes live here until the K loop is over
+    __shared__ float s_red[DN_WAVES], s_sh[2];
+    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
+    if (e < 0) return;
+    const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
+    const ExpertTab& t = tab.e[e];
+    int8_t* xq = reinterpret_cast<int8_t*>(part);
+    down_body<1, DN_DEPTH, true>(a, t, lo, m, blockIdx.x, part, xq, s_sh, [&] {
+        const int tid = threadIdx.x, nu = a.I / 32, nchunk = a.I / 16;
+        for (int row = 0; row < m; ++row) {
+            const int pos = lo + row;
+            float mx = 0.0f;
+            for (int i = tid; i < nu; i += DN_WAVES * 64) mx = fmaxf(mx, a.pmax[(size_t)pos * nu + i]);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            __syncthreads();  // an earlier use of s_red is over
+            if ((tid & 63) == 0) s_red[tid >> 6] = mx;
+            __syncthreads();
+            mx = 0.0f;
+#pragma unroll
+            for (int w = 0; w < DN_WAVES; ++w) mx = fmaxf(mx, s_red[w]);
+            const float scale = mx / 127.0f;
+            const float rscale = 1.0f / scale;
+            const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+            if (tid == 0) s_sh[row] = scale;
+            const __half* hrow = a.mid + (size_t)pos * a.I;
+            for (int c = tid; c < nchunk; c += DN_WAVES * 64) {
+                uint4 r0 = make_uint4(0, 0, 0, 0), r1 = r0;
+                float sv[16];
+                if (mx != 0.0f) {
+                    const uint4* px = reinterpret_cast<const uint4*>(hrow + c * 16);
+                    r0 = px[0];
+                    r1 = px[1];
+                    const float4* ps = reinterpret_cast<const float4*>(t.s_mid + c * 16);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float4 v = ps[i];
+                        sv[4 * i] = v.x;
+                        sv[4 * i + 1] = v.y;
+                        sv[4 * i + 2] = v.z;
+                        sv[4 * i + 3] = v.w;
+                    }
+                }
+                *reinterpret_cast<uint4*>(xq + (size_t)row * a.I + c * 16) = requant_chunk(r0, r1, sv, mx, scale, rscale, sfast);
+            }
+        }
+        __syncthreads();
+    });
 }
 
 }  // namespace
+
+bool decode_tiny_supported(int T, int H, int I) { return decode_supported(T, H, I) && T <= 2 && H <= 8192 && I <= 16384; }
+
+int launch_decode_tiny(const DecodeArgs& a, const __half* logits, int64_t ldl, const __half* x, int64_t ldx, const float* s, int T,
+                       const ExpertTab* tab_host, int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm,
+                       int32_t* inv, ExpertTab* tab_dev, hipStream_t st) {
+    TabAll tab{};
+    for (int e = 0; e < a.E; ++e) tab.e[e] = tab_host[e];
+    const TinyArgs r{logits, ldl, x, ldx, s, T, idx, counts, offsets, perm, inv, gw, tab_dev};
+    const int P = 2 * T;
+    const int ne = a.E < P ? a.E : P;
+    const dim3 g1(a.I / 32, ne), g2(a.H / 32, ne);
+    if (a.H / 16 <= GU_WAVES * 64)
+        hipLaunchKernelGGL(decode_tiny_gate_up_kernel<1>, g1, dim3(GU_WAVES * 64), 0, st, a, r, tab);
+    else
+        hipLaunchKernelGGL(decode_tiny_gate_up_kernel<2>, g1, dim3(GU_WAVES * 64), 0, st, a, r, tab);
+    hipLaunchKernelGGL(decode_tiny_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a, tab);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
 
 bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 32) == 0 && I % (DN_WAVES * 32) == 0; }
 

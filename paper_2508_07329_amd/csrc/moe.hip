@@ -4,47 +4,11 @@
 #include "haq_common.h"
 #include "moe.h"
 #include "quant_math.h"
+#include "routing.h"
 
 namespace haq {
 
 namespace {
-
-// Top-2 by logit (lowest index wins ties); gate weights are the softmax over all experts,
-// renormalised over the two.  The sum runs over the experts in index order so that every
-// implementation rounds alike.
-__device__ __forceinline__ void route_token(const __half* l, int E, int32_t* idx, float* gw) {
-    int i0 = 0;
-    float l0 = h2f(l[0]);
-    for (int e = 1; e < E; ++e) {
-        const float v = h2f(l[e]);
-        if (v > l0) {
-            l0 = v;
-            i0 = e;
-        }
-    }
-    int i1 = (i0 == 0) ? 1 : 0;
-    float l1 = h2f(l[i1]);
-    for (int e = 0; e < E; ++e) {
-        const float v = h2f(l[e]);
-        if (e != i0 && v > l1) {
-            l1 = v;
-            i1 = e;
-        }
-    }
-    float z = 0.0f;
-    for (int e = 0; e < E; ++e) z += exp_spec(h2f(l[e]) - l0);
-    const float p0 = exp_spec(l0 - l0) / z;
-    const float p1 = exp_spec(l1 - l0) / z;
-    const float d = p0 + p1;
-    idx[0] = i0;
-    idx[1] = i1;
-    gw[0] = p0 / d;
-    gw[1] = p1 / d;
-}
-
-struct TabAll {
-    ExpertTab e[32];
-};
 
 // One work-group does the whole routing side: router top-2 for every token, then a stable
 // counting sort of the P = 2T pairs by expert (thread i owns a contiguous run of pair ids, so
@@ -232,156 +196,36 @@ struct PrologueArgs {
     float* sx_sorted;  // [2T]
 };
 
-constexpr int PRO_THREADS = 256, PRO_MAXP = 128;
+constexpr int PRO_THREADS = 256, PRO_MAXP = ROUTE_LDS_MAXP;
 template <int NCH>
 __global__ __launch_bounds__(PRO_THREADS) void decode_prologue_kernel(PrologueArgs a, TabAll tab) {
-    __shared__ int32_t s_idx[PRO_MAXP], s_pos[PRO_MAXP], s_cnt[33], s_off[33], s_src;
-    __shared__ float s_gw[PRO_MAXP], s_red[PRO_THREADS / 64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ RouteLds r;
+    __shared__ float s_red[PRO_THREADS / 64];
+    const int tid = threadIdx.x;
     const int P = 2 * a.T;
-    if (tid < a.T) {
-        int32_t id2[2];
-        float g2[2];
-        route_token(a.logits + (size_t)tid * a.ldl, a.E, id2, g2);
-        s_idx[2 * tid] = id2[0];
-        s_idx[2 * tid + 1] = id2[1];
-        s_gw[2 * tid] = g2[0];
-        s_gw[2 * tid + 1] = g2[1];
-    }
-    __syncthreads();
-    if (tid < a.E) {
-        int c = 0;
-        for (int r = 0; r < P; ++r) c += (s_idx[r] == tid);
-        s_cnt[tid] = c;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int e = 0; e < a.E; ++e) {
-            s_off[e] = run;
-            run += s_cnt[e];
-        }
-        s_off[a.E] = run;
-    }
-    __syncthreads();
-    if (tid < P) {  // stable: pairs of one expert keep the order of their pair ids
-        const int e = s_idx[tid];
-        int rank = 0;
-        for (int r = 0; r < tid; ++r) rank += (s_idx[r] == e);
-        const int pos = s_off[e] + rank;
-        s_pos[tid] = pos;
-        if (pos == (int)blockIdx.x) s_src = tid;
-    }
-    __syncthreads();
+    route_in_lds(a.logits, a.ldl, a.T, a.E, r);
     if (blockIdx.x == 0) {
         if (tid < a.E) {
             a.tab_dev[tid] = tab.e[tid];
-            a.counts[tid] = s_cnt[tid];
+            a.counts[tid] = r.cnt[tid];
         }
-        if (tid <= a.E) a.offsets[tid] = s_off[tid];
+        if (tid <= a.E) a.offsets[tid] = r.off[tid];
         if (tid < P) {
-            a.idx[tid] = s_idx[tid];
-            a.gw[tid] = s_gw[tid];
-            a.perm[s_pos[tid]] = tid;
-            a.inv[tid] = s_pos[tid];
+            a.idx[tid] = r.idx[tid];
+            a.gw[tid] = r.gw[tid];
+            a.perm[r.pos[tid]] = tid;
+            a.inv[tid] = r.pos[tid];
         }
     }
     // ---- quantise the token of this row
-    const int p = blockIdx.x, t = s_src >> 1;
-    const int nchunk = a.H / 16;
-    const __half* xrow = a.x + (size_t)t * a.ldx;
-    uint4 raw[NCH][2];
-    float sv[NCH][16], rv[NCH][16];
-    bool fast[NCH];
-    float x[16];
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int c = tid + i * PRO_THREADS;
-        fast[i] = true;
-        raw[i][0] = raw[i][1] = make_uint4(0, 0, 0, 0);
-        if (c < nchunk) {
-            const uint4* px = reinterpret_cast<const uint4*>(xrow + c * 16);
-            raw[i][0] = px[0];
-            raw[i][1] = px[1];
-            if (a.s) fast[i] = load_s16(a.s, c, sv[i], rv[i]);
-        }
-    }
-    auto unpack = [&](int i) {
-        Half8 h0, h1;
-        *reinterpret_cast<uint4*>(&h0) = raw[i][0];
-        *reinterpret_cast<uint4*>(&h1) = raw[i][1];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            x[k] = h2f(h0.v[k]);
-            x[8 + k] = h2f(h1.v[k]);
-        }
-    };
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        if (tid + i * PRO_THREADS < nchunk) {
-            unpack(i);
-            if (!a.s) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k]));
-            } else if (fast[i]) {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(div_by(x[k], sv[i][k], rv[i][k], true)));
-            } else {
-#pragma unroll
-                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k] / sv[i][k]));
-            }
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
-    if (lane == 0) s_red[wave] = amax;
-    __syncthreads();
-    float m = 0.0f;
-#pragma unroll
-    for (int w = 0; w < PRO_THREADS / 64; ++w) m = fmaxf(m, s_red[w]);
-    const float scale = m / 127.0f;
-    const float rscale = 1.0f / scale;
-    const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+    const int p = blockIdx.x, t = r.src[p] >> 1;
+    const float scale = quantise_row<PRO_THREADS, NCH>(a.x + (size_t)t * a.ldx, a.s, a.H / 16, s_red, [&](int c, uint4 v) {
+        if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)t * a.ldq + c * 16) = v;
+        *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + p) * 16) = v;
+    });
     if (tid == 0) {
         a.sx_sorted[p] = scale;
         if (a.sx_tok) a.sx_tok[t] = scale;
-    }
-#pragma unroll
-    for (int i = 0; i < NCH; ++i)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            asm volatile("" : "+v"(raw[i][h].x), "+v"(raw[i][h].y), "+v"(raw[i][h].z), "+v"(raw[i][h].w));
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int c = tid + i * PRO_THREADS;
-        if (c < nchunk) {
-            uint32_t w[4] = {0, 0, 0, 0};
-            if (m != 0.0f) {
-                unpack(i);
-                if (fast[i] && sfast) {
-                    float q[16];
-#pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        const float y = a.s ? div_by(x[k], sv[i][k], rv[i][k], true) : x[k];
-                        q[k] = div_by(y, scale, rscale, true);
-                    }
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) w[k] = round_pack4(q[4 * k], q[4 * k + 1], q[4 * k + 2], q[4 * k + 3]);
-                } else {
-#pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        const float y = a.s ? x[k] / sv[i][k] : x[k];
-                        float q = rintf(y / scale);
-                        q = fminf(fmaxf(q, -127.0f), 127.0f);
-                        w[k / 4] |= (uint32_t)((int)q & 0xff) << (8 * (k % 4));
-                    }
-                }
-            }
-            const uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
-            if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)t * a.ldq + c * 16) = v;
-            *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + p) * 16) = v;
-        }
     }
 }
 

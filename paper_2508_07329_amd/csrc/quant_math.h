@@ -56,7 +56,7 @@ __device__ __forceinline__ bool load_s16(const float* s, int c, float (&sv)[16],
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         rv[i] = 1.0f / sv[i];
-        fast = fast && safe_divisor(sv[i]);
+        fast = fast & safe_divisor(sv[i]);  // no short circuit: branch-free
     }
     return fast;
 }
@@ -74,5 +74,130 @@ __device__ __forceinline__ uint32_t round_pack4(float q0, float q1, float q2, fl
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
 }
 
+// One row of Q(s^-1 x) by a whole work-group of NT threads (NCH 16-channel chunks per thread, so up
+// to NT * NCH chunks): raw halves stay in registers between the absmax reduction and the rounding.
+// `red` is LDS scratch of NT / 64 floats; `store(chunk, codes)` receives each finished chunk.  Every
+// thread of the work-group must call it; returns the row scale absmax / 127.
+template <int NT, int NCH, class Store>
+__device__ __forceinline__ float quantise_row(const __half* xrow, const float* s, int nchunk, float* red, Store&& store) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint4 raw[NCH][2];
+    float sv[NCH][16], rv[NCH][16];
+    bool fast[NCH];
+    float x[16];
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = tid + i * NT;
+        fast[i] = true;
+        raw[i][0] = raw[i][1] = make_uint4(0, 0, 0, 0);
+        if (c < nchunk) {
+            const uint4* px = reinterpret_cast<const uint4*>(xrow + c * 16);
+            raw[i][0] = px[0];
+            raw[i][1] = px[1];
+            if (s) fast[i] = load_s16(s, c, sv[i], rv[i]);
+        }
+    }
+    auto unpack = [&](int i) {
+        Half8 h0, h1;
+        *reinterpret_cast<uint4*>(&h0) = raw[i][0];
+        *reinterpret_cast<uint4*>(&h1) = raw[i][1];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            x[k] = h2f(h0.v[k]);
+            x[8 + k] = h2f(h1.v[k]);
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        if (tid + i * NT < nchunk) {
+            unpack(i);
+            if (!s) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k]));
+            } else if (fast[i]) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(div_by(x[k], sv[i][k], rv[i][k], true)));
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) amax = fmaxf(amax, fabsf(x[k] / sv[i][k]));
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    __syncthreads();  // an earlier use of `red` is over
+    if (lane == 0) red[wave] = amax;
+    __syncthreads();
+    float m = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) m = fmaxf(m, red[w]);
+    const float scale = m / 127.0f;
+    const float rscale = 1.0f / scale;
+    const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+    // keeps the compiler from recomputing (and holding) the quotients of the first pass
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            asm volatile("" : "+v"(raw[i][h].x), "+v"(raw[i][h].y), "+v"(raw[i][h].z), "+v"(raw[i][h].w));
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int c = tid + i * NT;
+        if (c < nchunk) {
+            uint32_t w[4] = {0, 0, 0, 0};
+            if (m != 0.0f) {
+                unpack(i);
+                if (fast[i] && sfast) {
+                    float q[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const float y = s ? div_by(x[k], sv[i][k], rv[i][k], true) : x[k];
+                        q[k] = div_by(y, scale, rscale, true);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) w[k] = round_pack4(q[4 * k], q[4 * k + 1], q[4 * k + 2], q[4 * k + 3]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const float y = s ? x[k] / sv[i][k] : x[k];
+                        w[k / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (k % 4));
+                    }
+                }
+            }
+            store(c, make_uint4(w[0], w[1], w[2], w[3]));
+        }
+    }
+    return scale;
+}
+
+// One 16-channel chunk of the requantised intermediate: codes of (h / s_mid) / scale with the
+// row's absmax m already known (scale = m / 127, rscale = 1 / scale, sfast: the reciprocal path
+// is valid for this scale).
+__device__ __forceinline__ uint4 requant_chunk(uint4 r0, uint4 r1, const float (&sv)[16], float m, float scale, float rscale,
+                                               bool sfast) {
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (m != 0.0f) {
+        const __half* h0 = reinterpret_cast<const __half*>(&r0);
+        const __half* h1 = reinterpret_cast<const __half*>(&r1);
+        if (sfast) {
+            float q[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
+                q[i] = div_by(y, scale, rscale, true);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float y = h2f(i < 8 ? h0[i] : h1[i - 8]) / sv[i];
+                w[i / 4] |= (uint32_t)(code_of(y, scale) & 0xff) << (8 * (i % 4));
+            }
+        }
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
 
 }  // namespace haq

@@ -1,0 +1,101 @@
+// Router arithmetic and the in-LDS routing of short batches, shared by the kernels that route
+// inside a larger launch (top-2 softmax gating, then the stable grouping of pairs by expert).
+#pragma once
+#include "haq_common.h"
+
+namespace haq {
+
+struct TabAll {  // the expert table as a kernel argument
+    ExpertTab e[32];
+};
+
+#ifdef __HIPCC__
+// Top-2 by logit (lowest index wins ties); gate weights are the softmax over all experts,
+// renormalised over the two.  The sum runs over the experts in index order so that every
+// implementation rounds alike.  All logits of the token (E <= 32) are fetched into registers with
+// independent loads first, so the serial comparisons and the sum wait for memory once.
+__device__ __forceinline__ void route_token(const __half* l, int E, int32_t* idx, float* gw) {
+    float v[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) v[e] = h2f(l[e < E ? e : E - 1]);
+    int i0 = 0;
+    float l0 = v[0];
+#pragma unroll
+    for (int e = 1; e < 32; ++e) {
+        if (e < E && v[e] > l0) {
+            l0 = v[e];
+            i0 = e;
+        }
+    }
+    int i1 = (i0 == 0) ? 1 : 0;
+    float l1 = (i0 == 0) ? v[1] : v[0];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        if (e < E && e != i0 && v[e] > l1) {
+            l1 = v[e];
+            i1 = e;
+        }
+    }
+    float z = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 32; ++e)
+        if (e < E) z += exp_spec(v[e] - l0);
+    const float p0 = exp_spec(l0 - l0) / z;
+    const float p1 = exp_spec(l1 - l0) / z;
+    const float d = p0 + p1;
+    idx[0] = i0;
+    idx[1] = i1;
+    gw[0] = p0 / d;
+    gw[1] = p1 / d;
+}
+
+// Routing of T <= 64 tokens and the stable counting sort of their P = 2T pairs by expert, done by
+// one work-group of at least 128 threads entirely in LDS (a few hundred operations, cheap enough
+// for every work-group of a launch to repeat): idx/gw by pair id, cnt/off by expert, pos = sorted
+// row of a pair, src = pair of a sorted row.  Ends with a barrier.
+constexpr int ROUTE_LDS_MAXP = 128;
+struct RouteLds {
+    int32_t idx[ROUTE_LDS_MAXP], pos[ROUTE_LDS_MAXP], src[ROUTE_LDS_MAXP], cnt[33], off[33];
+    float gw[ROUTE_LDS_MAXP];
+};
+__device__ __forceinline__ void route_in_lds(const __half* logits, int64_t ldl, int T, int E, RouteLds& r) {
+    const int tid = threadIdx.x;
+    const int P = 2 * T;
+    if (tid < T) {
+        int32_t id2[2];
+        float g2[2];
+        route_token(logits + (size_t)tid * ldl, E, id2, g2);
+        r.idx[2 * tid] = id2[0];
+        r.idx[2 * tid + 1] = id2[1];
+        r.gw[2 * tid] = g2[0];
+        r.gw[2 * tid + 1] = g2[1];
+    }
+    __syncthreads();
+    if (tid < E) {
+        int c = 0;
+        for (int p = 0; p < P; ++p) c += (r.idx[p] == tid);
+        r.cnt[tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            r.off[e] = run;
+            run += r.cnt[e];
+        }
+        r.off[E] = run;
+    }
+    __syncthreads();
+    if (tid < P) {  // stable: pairs of one expert keep the order of their pair ids
+        const int e = r.idx[tid];
+        int rank = 0;
+        for (int p = 0; p < tid; ++p) rank += (r.idx[p] == e);
+        const int pos = r.off[e] + rank;
+        r.pos[tid] = pos;
+        r.src[pos] = tid;
+    }
+    __syncthreads();
+}
+#endif
+
+}  // namespace haq

@@ -241,6 +241,39 @@ def test_moe_small_decode_path_bit_exact(T, H, I, E):
     _check_moe(offline.small_moe(seed=40 + T, T=T, H=H, I=I, E=E))
 
 
+@pytest.mark.parametrize("T,H,I,E,same_experts", [(1, 128, 512, 8, False), (2, 128, 512, 8, False), (2, 256, 768, 4, True),
+                                                   (2, 4352, 512, 8, False), (1, 4224, 256, 2, False)])
+def test_moe_one_or_two_tokens_fused_launches(T, H, I, E, same_experts):
+    """One or two tokens without the on-chip intermediates asked for: routing and token quantisation run
+    inside the gate/up launch and the requantisation inside the down launch.  Everything this path still
+    writes (routing results, h, per-pair y, output) must equal the oracle bit for bit; H > 4096 takes
+    the two-chunks-per-thread variant of the in-kernel token quantisation."""
+    m = offline.small_moe(seed=70 + T + H, T=T, H=H, I=I, E=E)
+    if same_experts:  # both tokens to the same two experts: two rows per expert
+        m["logits"][:, 1] = 30
+        m["logits"][:, 2] = 20
+    X, logits, s_in, experts = m["X"], m["logits"], m["s_in"], m["experts"]
+    dev_experts = upload_experts(experts)
+    want = ("topk_idx", "topk_w", "counts", "offsets", "perm", "inv", "mid_fp16", "y_fp16")
+    idx_ref, gw_ref = oracle.route_top2(logits)
+    counts, offsets, perm, inv = oracle.permute(idx_ref, E)
+    if same_experts:
+        assert counts[1] == 2 and counts[2] == 2
+    out_ref, mid_ref, _, _, y_ref = oracle.moe_ffn(X, idx_ref, gw_ref, s_in, experts, tokens=np.arange(T, dtype=np.int32), dumps=True)
+    pos = inv[(2 * np.arange(T)[:, None] + np.arange(2)[None, :]).ravel()]
+    for rep in range(2):  # the second call finds the workspace and caches as the first left them
+        out, d = haq.haq_moe_w8a8_ffn(dev(X), dev(logits), dev(s_in), dev_experts, I, debug=want)
+        torch.cuda.synchronize()
+        assert d.q is None and d.hq is None
+        assert bits_equal(host(d.topk_idx), idx_ref) and bits_equal(host(d.topk_w), gw_ref)
+        assert bits_equal(host(d.counts), counts) and bits_equal(host(d.offsets), offsets)
+        assert bits_equal(host(d.perm), perm) and bits_equal(host(d.inv), inv)
+        for name, g, c in (("mid", host(d.mid_fp16)[pos], mid_ref), ("y", host(d.y_fp16)[pos], y_ref), ("out", host(out), out_ref)):
+            assert bits_equal(g, c), f"{name} (call {rep}): {diff_report(g, c)}"
+    plain = haq.haq_moe_w8a8_ffn(dev(X), dev(logits), None if s_in is None else dev(s_in), dev_experts, I)
+    assert bits_equal(host(plain), out_ref)
+
+
 def test_moe_decode_path_experts_with_more_than_32_rows():
     """Weight-streaming path with skewed routing: expert 0 takes every token (64 rows: two row blocks in
     one pass), another one more than 32, the rest few or none."""
