@@ -24,6 +24,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef const __attribute__((address_space(1))) v4i* gptr_v4i;
 __device__ __forceinline__ v4i gload16(const int8_t* p) { return *(gptr_v4i)(uintptr_t)p; }
+// weights are read once: streamed past the caches so that the token rows every work-group re-reads stay in L2
+__device__ __forceinline__ v4i gload16_stream(const int8_t* p) { return __builtin_nontemporal_load((gptr_v4i)(uintptr_t)p); }
 
 constexpr int GU_WAVES = 4;    // gate/up: 64 packed channels (32 gate + 32 up) per work-group
 constexpr int DN_WAVES = 8;    // down: 32 channels per work-group, K split 8 ways
@@ -68,7 +70,9 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
     // the token rows of the second row block are 32 rows = 512 bytes further)
     const int8_t* pw = t.w13 + ((size_t)c0 * npad + unit * 64 + l32) * 16;
     const size_t wstep = (size_t)2 * npad * 16;
-    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.H + c0 * 16 : a.q_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    // lanes past the expert's last row re-read that row (their results are dropped): fewer distinct lines
+    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.H + c0 * 16 : a.q_cm + ((size_t)c0 * a.R + lo + min(l32, m - 1)) * 16;
+    const int xb1 = (min(32 + l32, m - 1) - min(l32, m - 1)) * 16;  // second row block, relative to the first
     const size_t xstep = XLDS ? 32 : (size_t)2 * a.R * 16;
 
     v16i accg[NRB], accu[NRB];
@@ -81,12 +85,12 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
         v4i g, u, x[NRB];
     };
     auto fetch = [&](Frag& f) {
-        f.g = gload16(pw);
-        f.u = gload16(pw + 512);
+        f.g = gload16_stream(pw);
+        f.u = gload16_stream(pw + 512);
         pw += wstep;
         if constexpr (!XLDS) {
 #pragma unroll
-            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
+            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + xb1 * b);
             px += xstep;
         }
     };
@@ -317,7 +321,8 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
     const int64_t npad = a.Npad2;
     const int8_t* pw = t.w2 + ((size_t)c0 * npad + unit * 32 + l32) * 16;  // next k-step to fetch
     const size_t wstep = (size_t)2 * npad * 16;
-    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.I + c0 * 16 : a.hq_cm + ((size_t)c0 * a.R + lo + l32) * 16;
+    const int8_t* px = XLDS ? xl + (size_t)min(l32, m - 1) * a.I + c0 * 16 : a.hq_cm + ((size_t)c0 * a.R + lo + min(l32, m - 1)) * 16;
+    const int xb1 = (min(32 + l32, m - 1) - min(l32, m - 1)) * 16;  // second row block, relative to the first
     const size_t xstep = XLDS ? 32 : (size_t)2 * a.R * 16;
 
     v16i acc[NRB];
@@ -332,11 +337,11 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
         v4i w, x[NRB];
     };
     auto fetch = [&](Frag& f) {
-        f.w = gload16(pw);
+        f.w = gload16_stream(pw);
         pw += wstep;
         if constexpr (!XLDS) {
 #pragma unroll
-            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + 512 * b);
+            for (int b = 0; b < NRB; ++b) f.x[b] = gload16(px + xb1 * b);
             px += xstep;
         }
     };
