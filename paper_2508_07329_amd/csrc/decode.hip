@@ -28,11 +28,13 @@ __device__ __forceinline__ v4i gload16(const int8_t* p) { return *(gptr_v4i)(uin
 __device__ __forceinline__ v4i gload16_stream(const int8_t* p) { return __builtin_nontemporal_load((gptr_v4i)(uintptr_t)p); }
 
 constexpr int GU_WAVES = 4;    // gate/up: 64 packed channels (32 gate + 32 up) per work-group
-constexpr int DN_WAVES = 8;    // down: 32 channels per work-group, K split 8 ways
+constexpr int DN_WAVES = 8;    // down with one or two tokens: 32 channels per work-group, K split 8 ways, one work-group per CU
+constexpr int DNG_WAVES = 4;   // down, 3..64 tokens: three smaller work-groups per CU, so that one's epilogue and
+constexpr int DNG_WGS = 3;     // start-up overlap the others' streaming
+constexpr int DNG_DEPTH = 14, DNG_DEPTH2 = 9;
 constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave (two operands each)
 constexpr int DN_DEPTH = 14;
 constexpr int GU_DEPTH2 = 5;   // the same with two row blocks per work-group (twice the token fragments)
-constexpr int DN_DEPTH2 = 9;
 
 // blockIdx.y enumerates the experts that hold rows, in index order (the grid has min(E, 2T) of
 // them: with one token only two experts can be active, and work-groups that find nothing to do
@@ -309,14 +311,15 @@ __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a
 }
 
 // ---- down projection ---------------------------------------------------------------------
-template <int NRB, int DEPTH, bool XLDS, class Prep>
+// NW waves split K; wave w finishes 16 / NW of the 16 accumulator registers.
+template <int NW, int NRB, int DEPTH, bool XLDS, class Prep>
 __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& t, int lo, int m, int unit, int (*part)[16][64],
                                           const int8_t* xl, const float* shl, Prep&& prep) {
     static_assert(!XLDS || NRB == 1, "the LDS variant carries one row block");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int nchunk = a.I / 16;
-    const int cpw = nchunk / DN_WAVES;
+    const int cpw = nchunk / NW;
     const int c0 = wave * cpw + hi;
     const int64_t npad = a.Npad2;
     const int8_t* pw = t.w2 + ((size_t)c0 * npad + unit * 32 + l32) * 16;  // next k-step to fetch
@@ -379,9 +382,14 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
         mac(f);
     }
     if constexpr (XLDS) __syncthreads();  // the codes may share LDS with `part`
-    // wave w finishes registers 2w, 2w+1: channels 8*(r/4) + 4*hi + r%4 of the unit
-    const int r0 = 2 * wave;
+    // register r holds channel 8*(r/4) + 4*hi + r%4 of the unit; wave w finishes registers RPW*w .. RPW*w + RPW-1
+    constexpr int RPW = 16 / NW;
+    static_assert(RPW == 2 || RPW == 4, "4 or 8 waves");
+    const int r0 = RPW * wave;
     const int ch = unit * 32 + 8 * (r0 / 4) + 4 * hi + (r0 % 4);
+    float sw[RPW];
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) sw[q] = t.sw2[ch + q];
 #pragma unroll
     for (int b = 0; b < NRB; ++b) {
         if (b > 0) __syncthreads();  // part is reused
@@ -391,27 +399,33 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
         const int row = 32 * b + l32;
         const bool live = row < m;
         const float sh = live ? (XLDS ? shl[row] : a.sh[lo + row]) : 0.0f;
-        __half hv[2];
+        __half hv[RPW];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < RPW; ++q) {
             int v = 0;
 #pragma unroll
-            for (int w = 0; w < DN_WAVES; ++w) v += part[w][r0 + q][lane];
-            hv[q] = f2h(dequant(v, sh, t.sw2[ch + q]));
+            for (int w = 0; w < NW; ++w) v += part[w][r0 + q][lane];
+            hv[q] = f2h(dequant(v, sh, sw[q]));
         }
-        if (live) *reinterpret_cast<uint32_t*>(a.y + (size_t)(lo + row) * a.H + ch) = *reinterpret_cast<const uint32_t*>(hv);
+        if (live) {
+            __half* dst = a.y + (size_t)(lo + row) * a.H + ch;
+            if constexpr (RPW == 2)
+                *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(hv);
+            else
+                *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(hv);
+        }
     }
 }
 
-__global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_down_kernel(DecodeArgs a) {
-    __shared__ int part[DN_WAVES][16][64];
+__global__ __launch_bounds__(DNG_WAVES * 64, DNG_WGS) void decode_down_kernel(DecodeArgs a) {
+    __shared__ int part[DNG_WAVES][16][64];
     const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
     if (e < 0) return;
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     if (m > 32)  // uniform over the work-group
-        down_body<2, DN_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
+        down_body<DNG_WAVES, 2, DNG_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
     else
-        down_body<1, DN_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
+        down_body<DNG_WAVES, 1, DNG_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {});
 }
 
 // One or two tokens: every work-group requantises the expert's one or two rows of the
@@ -426,7 +440,7 @@ __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_tiny_down_kernel(Deco
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = tab.e[e];
     int8_t* xq = reinterpret_cast<int8_t*>(part);
-    down_body<1, DN_DEPTH, true>(a, t, lo, m, blockIdx.x, part, xq, s_sh, [&] {
+    down_body<DN_WAVES, 1, DN_DEPTH, true>(a, t, lo, m, blockIdx.x, part, xq, s_sh, [&] {
         const int tid = threadIdx.x, nu = a.I / 32, nchunk = a.I / 16;
         for (int row = 0; row < m; ++row) {
             const int pos = lo + row;
@@ -491,7 +505,7 @@ int launch_decode_tiny(const DecodeArgs& a, const __half* logits, int64_t ldl, c
     return HAQ_OK;
 }
 
-bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 32) == 0 && I % (DN_WAVES * 32) == 0; }
+bool decode_supported(int T, int H, int I) { return T <= 64 && H % (GU_WAVES * 32) == 0 && I % (DN_WAVES * 32) == 0 && I % (DNG_WAVES * 32) == 0; }
 
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
@@ -503,7 +517,7 @@ int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
         const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
         hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(thr), 0, st, a);
     }
-    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DNG_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
