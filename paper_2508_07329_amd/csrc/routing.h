@@ -50,16 +50,18 @@ __device__ __forceinline__ void route_token(const __half* l, int E, int32_t* idx
 }
 
 // Routing of T <= 64 tokens and the stable counting sort of their P = 2T pairs by expert, done by
-// one work-group of at least 128 threads entirely in LDS (a few hundred operations, cheap enough
-// for every work-group of a launch to repeat): idx/gw by pair id, cnt/off by expert, pos = sorted
-// row of a pair, src = pair of a sorted row.  Ends with a barrier.
+// one work-group of at least 128 threads entirely in LDS (cheap enough for every work-group of a
+// launch to repeat): idx/gw by pair id, cnt/off by expert, pos = sorted row of a pair, src = pair
+// of a sorted row.  Thread p holds pair p; its rank among the pairs of the same expert is the
+// number of lower lanes of its wave that vote for that expert, plus all of wave 0's for a pair of
+// wave 1.  Ends with a barrier.
 constexpr int ROUTE_LDS_MAXP = 128;
 struct RouteLds {
-    int32_t idx[ROUTE_LDS_MAXP], pos[ROUTE_LDS_MAXP], src[ROUTE_LDS_MAXP], cnt[33], off[33];
+    int32_t idx[ROUTE_LDS_MAXP], pos[ROUTE_LDS_MAXP], src[ROUTE_LDS_MAXP], cnt[33], off[33], wcnt[2][32];
     float gw[ROUTE_LDS_MAXP];
 };
 __device__ __forceinline__ void route_in_lds(const __half* logits, int64_t ldl, int T, int E, RouteLds& r) {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int P = 2 * T;
     if (tid < T) {
         int32_t id2[2];
@@ -71,26 +73,23 @@ __device__ __forceinline__ void route_in_lds(const __half* logits, int64_t ldl, 
         r.gw[2 * tid + 1] = g2[1];
     }
     __syncthreads();
-    if (tid < E) {
-        int c = 0;
-        for (int p = 0; p < P; ++p) c += (r.idx[p] == tid);
-        r.cnt[tid] = c;
+    const int my_e = tid < P ? r.idx[tid] : -1;
+    int my_rank = 0;
+    for (int e = 0; e < E; ++e) {
+        const unsigned long long votes = __ballot(my_e == e);
+        if (my_e == e) my_rank = __popcll(votes & ((1ull << lane) - 1ull));
+        if (lane == 0 && wave < 2) r.wcnt[wave][e] = __popcll(votes);
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid <= E) {  // thread e: count of expert e and the sum of the counts before it
         int run = 0;
-        for (int e = 0; e < E; ++e) {
-            r.off[e] = run;
-            run += r.cnt[e];
-        }
-        r.off[E] = run;
+        for (int e = 0; e < tid; ++e) run += r.wcnt[0][e] + r.wcnt[1][e];
+        r.off[tid] = run;
+        if (tid < E) r.cnt[tid] = r.wcnt[0][tid] + r.wcnt[1][tid];
     }
     __syncthreads();
-    if (tid < P) {  // stable: pairs of one expert keep the order of their pair ids
-        const int e = r.idx[tid];
-        int rank = 0;
-        for (int p = 0; p < tid; ++p) rank += (r.idx[p] == e);
-        const int pos = r.off[e] + rank;
+    if (tid < P) {
+        const int pos = r.off[my_e] + my_rank + (wave == 1 ? r.wcnt[0][my_e] : 0);
         r.pos[tid] = pos;
         r.src[pos] = tid;
     }
