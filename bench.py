@@ -131,13 +131,12 @@ def bench_ffn(args, torch, haq, hi):
     for i in range(args.steps):
         haq.haq_quant_act_packed(X, s1, q_packed=q1, row_scale=sx1)
         ev[2 * n_gemm * i].record()
-        haq.haq_gemm_w8a8_packed(q1, sx1, w1p, sw1, T, K, F, haq.HAQ_ACT_RELU, out=h,
-                                 out_hint=haq.HAQ_OUT_CACHED if two else haq.HAQ_OUT_STREAMED)  # as the library's own calls
+        haq.haq_gemm_w8a8_packed(q1, sx1, w1p, sw1, T, K, F, haq.HAQ_ACT_RELU, out=h)
         ev[2 * n_gemm * i + 1].record()
         if two:
             haq.haq_quant_act_packed(h, s2, q_packed=q2, row_scale=sx2)
             ev[2 * n_gemm * i + 2].record()
-            haq.haq_gemm_w8a8_packed(q2, sx2, w2p, sw2, T, F, K, haq.HAQ_ACT_NONE, out=y, out_hint=haq.HAQ_OUT_STREAMED)
+            haq.haq_gemm_w8a8_packed(q2, sx2, w2p, sw2, T, F, K, haq.HAQ_ACT_NONE, out=y)
             ev[2 * n_gemm * i + 3].record()
     torch.cuda.synchronize()
     gemm_ms = [ev[2 * j].elapsed_time(ev[2 * j + 1]) for j in range(n_gemm * args.steps)]

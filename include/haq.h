@@ -41,10 +41,6 @@ extern "C" {
 
 #define HAQ_ACT_NONE 0
 #define HAQ_ACT_RELU 1
-/* what happens to a GEMM output next (haq_gemm_w8a8_packed): read again soon by another
- * kernel (ordinary stores) or not (non-temporal stores, which leave the operand tiles in L2) */
-#define HAQ_OUT_CACHED 0
-#define HAQ_OUT_STREAMED 1
 
 #define HAQ_LOC_DEVICE 0      /* expert weights live in HBM */
 #define HAQ_LOC_HOST_PINNED 1 /* expert weights live in pinned host memory and are streamed in */
@@ -118,17 +114,14 @@ size_t haq_linear_workspace_bytes(int32_t T, int32_t K, int32_t N);
  * haq_packed_act_bytes(T, K) = K * R.
  * haq_quant_act_packed: Q(s^-1 X) as in haq_smooth_quant_act, codes written in
  *   the packed layout.  haq_gemm_w8a8_packed: int8 GEMM + dequantise + activation
- *   on such codes; row_scale [T], y fp16 [T x N]; acc_dbg optional; out_hint is
- *   HAQ_OUT_CACHED or HAQ_OUT_STREAMED (a performance hint only: haq_w8a8_ffn
- *   uses CACHED for the intermediate and STREAMED for the output, haq_w8a8_linear
- *   STREAMED).                                                                   */
+ *   on such codes; row_scale [T], y fp16 [T x N]; acc_dbg optional.            */
 int64_t haq_packed_act_rows(int32_t T);
 size_t haq_packed_act_bytes(int32_t T, int32_t K);
 int32_t haq_quant_act_packed(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K,
                              int8_t* q_packed, float* row_scale, void* stream);
 int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, const int8_t* w_packed,
                              const float* w_scale, int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16,
-                             int64_t ldy, int32_t* acc_dbg, int32_t out_hint, void* stream);
+                             int64_t ldy, int32_t* acc_dbg, void* stream);
 int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const int8_t* w_packed,
                         const float* w_scale, int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16,
                         int64_t ldy, int32_t* acc_dbg, int8_t* q_dbg, float* sx_dbg, void* workspace,

@@ -18,7 +18,7 @@ __all__ = [
     "haq_linear_workspace_bytes", "haq_w8a8_linear", "haq_packed_act_rows", "haq_packed_act_bytes",
     "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ffn_workspace_bytes", "haq_w8a8_ffn",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
-    "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU", "HAQ_OUT_CACHED", "HAQ_OUT_STREAMED",
+    "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
@@ -29,7 +29,6 @@ __all__ = [
 ]
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
-HAQ_OUT_CACHED, HAQ_OUT_STREAMED = 0, 1
 HAQ_LOC_DEVICE, HAQ_LOC_HOST_PINNED = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -218,10 +217,10 @@ def haq_quant_act_packed(x, s, *, q_packed=None, row_scale=None):
 
 
 def haq_gemm_w8a8_packed(q_packed, row_scale, w_packed, w_scale, T: int, K: int, N: int, act: int = HAQ_ACT_NONE, *,
-                         out=None, out_hint: int = HAQ_OUT_CACHED):
+                         out=None):
     y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=q_packed.device)
     _check(lib().haq_gemm_w8a8_packed(_ptr(q_packed), _ptr(row_scale), _ptr(w_packed), _ptr(w_scale), T, K, N, act,
-                                      _ptr(y), C.c_int64(y.stride(0)), None, out_hint, _stream()))
+                                      _ptr(y), C.c_int64(y.stride(0)), None, _stream()))
     return y
 
 

@@ -125,7 +125,7 @@ int quant_packed(const void* x_fp16, int64_t ldx, const float* s, int T, int K, 
 }
 
 int gemm_packed(const int8_t* q_cm, const float* sx, const int8_t* w_packed, const float* w_scale, int T, int K, int N,
-                int act, void* y_fp16, int64_t ldy, int32_t* acc_dbg, bool stream_out, hipStream_t st) {
+                int act, void* y_fp16, int64_t ldy, int32_t* acc_dbg, hipStream_t st) {
     GemmArgs ga{};
     ga.A = q_cm;
     ga.R = padded_rows(T);
@@ -140,7 +140,6 @@ int gemm_packed(const int8_t* q_cm, const float* sx, const int8_t* w_packed, con
     ga.Y = (__half*)y_fp16;
     ga.ldy = ldy;
     ga.acc_dbg = acc_dbg;
-    ga.stream_out = stream_out;
     return launch_gemm(ga, EPI_LINEAR, st);
 }
 
@@ -215,7 +214,7 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
     int rc = quant_packed(x_fp16, ldx, s, T, K, w.q_cm, w.sx, q_dbg, st);
     if (rc != HAQ_OK) return rc;
     if (sx_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(sx_dbg, w.sx, (size_t)T * sizeof(float), hipMemcpyDeviceToDevice, st));
-    return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, true, st);
+    return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, st);
 }
 
 size_t haq_linear_asym_workspace_bytes(int32_t T, int32_t K, int32_t N) {
@@ -265,7 +264,6 @@ int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, co
     ga.acc_dbg = acc_dbg;
     ga.zp = zp;
     ga.colsum = w_colsum;
-    ga.stream_out = true;
     return launch_gemm(ga, EPI_LINEAR_ASYM, st);
 }
 
@@ -298,9 +296,9 @@ int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int
     __half* h = h_dbg_fp16 ? (__half*)h_dbg_fp16 : w.h;
     int rc = quant_packed(x_fp16, ldx, s1, T, K, w.q1, w.sx1, nullptr, st);
     if (rc != HAQ_OK) return rc;
-    if ((rc = gemm_packed(w.q1, w.sx1, w1_packed, w1_scale, T, K, F, act, h, F, nullptr, false, st)) != HAQ_OK) return rc;
+    if ((rc = gemm_packed(w.q1, w.sx1, w1_packed, w1_scale, T, K, F, act, h, F, nullptr, st)) != HAQ_OK) return rc;
     if ((rc = quant_packed(h, F, s2, T, F, w.q2, w.sx2, nullptr, st)) != HAQ_OK) return rc;
-    return gemm_packed(w.q2, w.sx2, w2_packed, w2_scale, T, F, N, HAQ_ACT_NONE, y_fp16, ldy, nullptr, true, st);
+    return gemm_packed(w.q2, w.sx2, w2_packed, w2_scale, T, F, N, HAQ_ACT_NONE, y_fp16, ldy, nullptr, st);
 }
 
 int64_t haq_packed_act_rows(int32_t T) { return T < 0 ? 0 : padded_rows(T); }
@@ -320,17 +318,15 @@ int32_t haq_quant_act_packed(const void* x_fp16, int64_t ldx, const float* s, in
 
 int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, const int8_t* w_packed, const float* w_scale,
                              int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg,
-                             int32_t out_hint, void* stream) {
+                             void* stream) {
     if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: T=%d K=%d N=%d", T, K, N);
     if (K % 64 != 0 || N % 16 != 0) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: K=%d must be a multiple of 64, N=%d of 16", K, N);
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: act=%d", act);
-    if (out_hint != HAQ_OUT_CACHED && out_hint != HAQ_OUT_STREAMED) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: out_hint=%d", out_hint);
     if (T == 0) return HAQ_OK;
     if (!q_packed || !row_scale || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: null buffer");
     if (ldy < N || ldy % 8 != 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: ldy=%lld (multiple of 8)", (long long)ldy);
     if (!aligned16(q_packed) || !aligned16(w_packed) || !aligned16(y_fp16)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: pointers must be 16-byte aligned");
-    return gemm_packed(q_packed, row_scale, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, out_hint == HAQ_OUT_STREAMED,
-                       (hipStream_t)stream);
+    return gemm_packed(q_packed, row_scale, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, (hipStream_t)stream);
 }
 
 int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out) {

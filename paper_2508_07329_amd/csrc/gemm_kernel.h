@@ -351,17 +351,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
             const int c8 = (lane % LANES_PER_ROW) * 8;
             const int orow = tc.m0 + wm * WM + i * 32 + r2, ocol = out_n0 + c8;
             const uint4 v = *reinterpret_cast<const uint4*>(stage + r2 * PITCH + c8 * 2);
-            if (orow < tc.m_end && ocol < out_n) {
-                __half* dst = a.Y + (size_t)orow * a.ldy + ocol;
-                if (a.stream_out) {
-                    // nobody re-reads this output soon: stored past the caches, which keeps the operand
-                    // tiles that other work-groups re-read in L2
-                    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-                    __builtin_nontemporal_store(*reinterpret_cast<const u4*>(&v), reinterpret_cast<u4*>(dst));
-                } else {
-                    *reinterpret_cast<uint4*>(dst) = v;
-                }
-            }
+            if (orow < tc.m_end && ocol < out_n) *reinterpret_cast<uint4*>(a.Y + (size_t)orow * a.ldy + ocol) = v;
         }
         HAQ_CFENCE();
     }

@@ -133,7 +133,6 @@ struct GemmArgs {
     __half* Y;
     int64_t ldy;
     int32_t* acc_dbg;  // optional dense [rows x N]
-    bool stream_out;   // Y is not read again by the next kernel: store it with non-temporal stores
     // asymmetric activation codes (EPI_LINEAR_ASYM): A holds code - 128; the accumulator is corrected by
     // (128 - zp[row]) * colsum[channel] before it is dequantised
     const int32_t* zp;      // [rows]
