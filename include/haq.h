@@ -351,7 +351,12 @@ size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
  * H % 64 == 0, I % 64 == 0.  Host-resident experts that the call activates and
  * the context's cache does not hold are copied into its slots with
  * hipMemcpyAsync on its side stream while resident experts compute; results
- * are identical to the all-resident call.                                    */
+ * are identical to the all-resident call.
+ * Launch shapes (same results on every path): more than 64 tokens or any
+ * host-resident expert -> grouped tiled GEMMs; up to 64 tokens, all experts
+ * resident, H % 128 == 0 and I % 256 == 0 -> weight-streaming kernels (five
+ * launches); one or two tokens with H <= 8192, I <= 16384 and none of q, sx, hq,
+ * sh asked for in dbg -> three launches (those four stay on chip on that path). */
 int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl,
                          const float* s_in, const haq_expert_desc* experts_host, int32_t T, int32_t H, int32_t I,
                          int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg_host,
