@@ -4,7 +4,7 @@
 // relieve memory bandwidth).
 //
 // Weight fragments go straight from global memory into MFMA operand registers
-// (no LDS: nothing is reused): with the chunk-major layout a lane's 16 bytes are
+// (no LDS, and non-temporal loads: nothing is reused): with the chunk-major layout a lane's 16 bytes are
 // one output channel's 16 consecutive k, lanes 0-31 cover 32 neighbouring
 // channels (512 contiguous bytes) and lanes 32-63 the next k chunk.  The weights
 // are the first MFMA operand, the (few) token rows the second, so a lane ends up
