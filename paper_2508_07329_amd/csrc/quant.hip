@@ -423,22 +423,28 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
                 x[8 + i] = h2f(h1.v[i]);
             }
         };
+        // quotients x / s of the slab stay in registers from the reduction to the rounding
+        float y[RS][16];
         float amax[RS];
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
             float m = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) y[r][i] = 0.0f;
             if (src_cur[r] >= 0) {
                 unpack(r);
                 if (!s) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i]));
+                    for (int i = 0; i < 16; ++i) y[r][i] = x[i];
                 } else if (fast) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(div_by(x[i], sv[i], rv[i], true)));
+                    for (int i = 0; i < 16; ++i) y[r][i] = div_by(x[i], sv[i], rv[i], true);
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(x[i] / sv[i]));
+                    for (int i = 0; i < 16; ++i) y[r][i] = x[i] / sv[i];
                 }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(y[r][i]));
             }
             amax[r] = m;
         }
@@ -456,14 +462,6 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
         QCFENCE();
         __builtin_amdgcn_s_barrier();
         QCFENCE();
-        // the rounding pass recomputes x / s from the raw halves; the empty asm keeps the
-        // compiler from carrying the quotients of the first pass across the barrier
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                asm volatile("" : "+v"(raw[r][h].x), "+v"(raw[r][h].y), "+v"(raw[r][h].z), "+v"(raw[r][h].w));
-        }
         uint4 code[RS];
         float scale[RS];
 #pragma unroll
@@ -477,24 +475,15 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
                 const float rscale = 1.0f / scale[r];
                 const bool sfast = scale[r] >= 0x1p-100f && scale[r] <= 0x1p100f;
                 if (m != 0.0f) {
-                    unpack(r);
-                    if (fast && sfast) {  // the common case: both divisions through reciprocals
+                    if (sfast) {  // the common case: the division through the reciprocal
                         float q[16];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float y = s ? div_by(x[i], sv[i], rv[i], true) : x[i];
-                            q[i] = div_by(y, scale[r], rscale, true);
-                        }
+                        for (int i = 0; i < 16; ++i) q[i] = div_by(y[r][i], scale[r], rscale, true);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
                     } else {
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float y = s ? x[i] / sv[i] : x[i];
-                            float q = rintf(y / scale[r]);
-                            q = fminf(fmaxf(q, -127.0f), 127.0f);
-                            w[i / 4] |= (uint32_t)((int)q & 0xff) << (8 * (i % 4));
-                        }
+                        for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[r][i], scale[r]) & 0xff) << (8 * (i % 4));
                     }
                 }
             }
