@@ -301,21 +301,27 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_reg_kernel(QuantArg
     }
 }
 
-#define QWAIT_VMCNT0() __builtin_amdgcn_s_waitcnt((0 & 0xF) | ((0 >> 4) << 14) | (0x7 << 4) | (0xF << 8))
-#define QWAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
-#define QCFENCE() asm volatile("" ::: "memory")
 
 // Pipelined single pass for K <= 16 * QMAX_THREADS.  Thread (g, c) owns one 16-channel chunk
 // (reciprocals of the smoothing vector formed once per work-group) and walks over a run of
-// slabs of RS rows per row group.  The halves of the next slab travel global -> LDS (16 B per lane,
-// no registers) while the current slab is reduced and rounded; a thread only ever reads back
-// the LDS slots its own wave's loads filled, so the only barrier is the one of the row
-// maximum.  Every row is read from memory once.
+// slabs of RS rows per row group; the halves of the next slab are fetched into registers while
+// the current slab is reduced and rounded.  Every row is read from memory once.
+//
+// The chunk-major output keeps the 16 bytes of consecutive rows of one chunk side by side, so a
+// thread that stored its own codes would write 16 bytes per row, 64 different cache lines per store
+// instruction (measured: a third of the kernel's time).  The codes of up to QSTAGE rows are therefore
+// staged in LDS and written out transposed: eight neighbouring lanes write the 16-byte pieces of
+// eight consecutive rows of one chunk, i.e. whole 128-byte lines when the rows are aligned.
+constexpr int QSTAGE = 8;
+__host__ __device__ inline int qstage_rows(int slab) { return slab > QSTAGE ? slab : QSTAGE; }
+// row pitch of the staging area in bytes: 8 (mod 16) pieces of 16 bytes, so that the transposed
+// reads of eight rows x eight chunks spread evenly over the banks
+__host__ __device__ inline int qstage_pitch(int nchunk) { return (nchunk + ((24 - nchunk % 16) % 16)) * 16; }
+
 template <int RS>
 __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArgs a, int CL) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t qlds[];
     const int nthr = blockDim.x;
-    float* red = reinterpret_cast<float*>(qlds + (size_t)2 * RS * 2 * nthr * 16);  // [2][QMAX_THREADS / 64][RS]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = tid % CL, g = tid / CL;
@@ -323,6 +329,8 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
     const int waves_per_group = CL >> 6;
     const int nchunk = a.K / 16;
     const int slab = G * RS;
+    const int srows = qstage_rows(slab), pitch = qstage_pitch(nchunk);
+    float* red = reinterpret_cast<float*>(qlds + (size_t)srows * pitch);  // [2][QMAX_THREADS / 64][RS]
     // Slabs per work-group: the grid is fixed (one work-group per CU); every group (expert)
     // is cut into runs of `nit` slabs, so no work-group does more than nit slabs whatever the
     // group sizes are, and sum_e ceil(slabs_e / nit) <= total / nit + groups <= grid.
@@ -362,6 +370,7 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
         row0 = blockIdx.x * brows;
         row_end = a.T;
     }
+    if (row0 >= row_end) return;  // uniform over the work-group
     const bool active = c < nchunk;
     float sv[16], rv[16];
     bool fast = true;
@@ -376,53 +385,28 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
             if (active && it < nit && row < row_end) src[r] = a.gather ? (a.gather[row] >> 1) : row;
         }
     };
-    auto issue = [&](int buf, const int (&src)[RS]) {
+    auto fetch = [&](const int (&src)[RS], uint4 (&raw)[RS][2]) {
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
+            raw[r][0] = raw[r][1] = make_uint4(0, 0, 0, 0);
             if (src[r] >= 0) {
-                const __half* p = a.x + (size_t)src[r] * a.ldx + c * 16;
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(uintptr_t)(p + 8 * h),
-                        (__attribute__((address_space(3))) void*)(qlds + ((size_t)((buf * RS + r) * 2 + h) * nthr + wave * 64) * 16),
-                        16, 0, 0);
+                const uint4* px = reinterpret_cast<const uint4*>(a.x + (size_t)src[r] * a.ldx + c * 16);
+                raw[r][0] = px[0];
+                raw[r][1] = px[1];
             }
         }
     };
     int src[RS], src_nxt[RS];
+    uint4 raw[RS][2], raw_nxt[RS][2];
     source(0, src);
-    issue(0, src);
+    fetch(src, raw);
     source(1, src_nxt);
-    QWAIT_VMCNT0();  // slab 0 is in LDS
-    QCFENCE();
-    float x[16];
+    int staged = 0;          // rows in the staging area (uniform)
+    int stage_t0 = row0;     // output row of its first row
     for (int it = 0; it < nit; ++it) {
         const int base = row0 + it * slab;
         if (base >= row_end) break;  // uniform over the work-group
-        uint4 raw[RS][2];
-#pragma unroll
-        for (int r = 0; r < RS; ++r)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                raw[r][h] = *reinterpret_cast<const uint4*>(qlds + ((size_t)(((it & 1) * RS + r) * 2 + h) * nthr + tid) * 16);
-        issue((it + 1) & 1, src_nxt);  // lands while this slab is reduced and rounded
-        int src_cur[RS];
-#pragma unroll
-        for (int r = 0; r < RS; ++r) src_cur[r] = src[r];
-#pragma unroll
-        for (int r = 0; r < RS; ++r) src[r] = src_nxt[r];
-        source(it + 2, src_nxt);
-        auto unpack = [&](int r) {
-            Half8 h0, h1;
-            *reinterpret_cast<uint4*>(&h0) = raw[r][0];
-            *reinterpret_cast<uint4*>(&h1) = raw[r][1];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                x[i] = h2f(h0.v[i]);
-                x[8 + i] = h2f(h1.v[i]);
-            }
-        };
+        fetch(src_nxt, raw_nxt);  // arrives while this slab is reduced and rounded
         // quotients x / s of the slab stay in registers from the reduction to the rounding
         float y[RS][16];
         float amax[RS];
@@ -431,8 +415,16 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
             float m = 0.0f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) y[r][i] = 0.0f;
-            if (src_cur[r] >= 0) {
-                unpack(r);
+            if (src[r] >= 0) {
+                float x[16];
+                Half8 h0, h1;
+                *reinterpret_cast<uint4*>(&h0) = raw[r][0];
+                *reinterpret_cast<uint4*>(&h1) = raw[r][1];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    x[i] = h2f(h0.v[i]);
+                    x[8 + i] = h2f(h1.v[i]);
+                }
                 if (!s) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) y[r][i] = x[i];
@@ -458,56 +450,63 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
 #pragma unroll
             for (int r = 0; r < RS; ++r) redp[wave * RS + r] = amax[r];
         }
-        QWAIT_LGKM0();
-        QCFENCE();
-        __builtin_amdgcn_s_barrier();
-        QCFENCE();
-        uint4 code[RS];
-        float scale[RS];
+        __syncthreads();
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
-            uint32_t w[4] = {0, 0, 0, 0};
-            scale[r] = 0.0f;
-            if (src_cur[r] >= 0) {
+            if (src[r] >= 0) {
+                uint32_t w[4] = {0, 0, 0, 0};
                 float m = 0.0f;
                 for (int w2 = 0; w2 < waves_per_group; ++w2) m = fmaxf(m, redp[(g * waves_per_group + w2) * RS + r]);
-                scale[r] = m / 127.0f;
-                const float rscale = 1.0f / scale[r];
-                const bool sfast = scale[r] >= 0x1p-100f && scale[r] <= 0x1p100f;
+                const float scale = m / 127.0f;
+                const float rscale = 1.0f / scale;
+                const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
                 if (m != 0.0f) {
                     if (sfast) {  // the common case: the division through the reciprocal
                         float q[16];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) q[i] = div_by(y[r][i], scale[r], rscale, true);
+                        for (int i = 0; i < 16; ++i) q[i] = div_by(y[r][i], scale, rscale, true);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
                     } else {
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[r][i], scale[r]) & 0xff) << (8 * (i % 4));
+                        for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[r][i], scale) & 0xff) << (8 * (i % 4));
                     }
                 }
-            }
-            code[r] = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-        // the next slab has had the whole arithmetic phase to arrive, and the stores of the
-        // previous slab are long acknowledged: this wait costs nothing, and the stores below
-        // are not waited for until one slab later
-        QWAIT_VMCNT0();
-        QCFENCE();
-#pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            if (src_cur[r] >= 0) {
+                const uint4 code = make_uint4(w[0], w[1], w[2], w[3]);
                 const int t = base + g * RS + r;
                 if (c == r) {
-                    if (a.scale_dest) a.scale_dest[t] = scale[r];
-                    if (a.scale) a.scale[src_cur[r]] = scale[r];
+                    if (a.scale_dest) a.scale_dest[t] = scale;
+                    if (a.scale) a.scale[src[r]] = scale;
                 }
-                if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)src_cur[r] * a.ldq + c * 16) = code[r];
-                if (a.q_cm) *reinterpret_cast<uint4*>(a.q_cm + ((size_t)c * a.R + t) * 16) = code[r];
+                if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)src[r] * a.ldq + c * 16) = code;
+                *reinterpret_cast<uint4*>(qlds + (size_t)(staged + g * RS + r) * pitch + c * 16) = code;
             }
         }
+        staged += slab;
+        const bool last = it + 1 == nit || base + slab >= row_end;
+        if (staged + slab > srows || last) {
+            __syncthreads();  // the staged codes are complete
+            if (a.q_cm) {
+                const int nrow = min(staged, row_end - stage_t0);
+                for (int i = tid; i < nchunk * srows; i += nthr) {
+                    const int row = i % srows, ch = i / srows;
+                    if (row < nrow)
+                        *reinterpret_cast<uint4*>(a.q_cm + ((size_t)ch * a.R + stage_t0 + row) * 16) =
+                            *reinterpret_cast<const uint4*>(qlds + (size_t)row * pitch + ch * 16);
+                }
+            }
+            stage_t0 += staged;
+            staged = 0;
+            if (!last) __syncthreads();  // the staging area may be overwritten
+        }
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            src[r] = src_nxt[r];
+            raw[r][0] = raw_nxt[r][0];
+            raw[r][1] = raw_nxt[r][1];
+        }
+        source(it + 2, src_nxt);
     }
-    QWAIT_VMCNT0();  // nothing may still be writing LDS when the work-group retires
 }
 
 
@@ -761,13 +760,13 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
             n_cu = v > 64 ? v : 256;
         }
         if (rows / (LRS * G) >= 4 * n_cu) {
-            const size_t lds = (size_t)2 * LRS * 2 * threads * 16 + 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
+            const size_t red_bytes = 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
+            const size_t lds = (size_t)qstage_rows(LRS * G) * qstage_pitch(nchunk) + red_bytes;
             static std::once_flag once;
             static hipError_t attr_err = hipSuccess;
-            std::call_once(once, [&] {
-                attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               2 * LRS * 2 * QMAX_THREADS * 16 + 2 * (QMAX_THREADS / 64) * LRS * (int)sizeof(float));
+            std::call_once(once, [&] {  // the largest case: one row group, QMAX_THREADS chunks
+                attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               QSTAGE * qstage_pitch(QMAX_THREADS) + (int)red_bytes);
             });
             HAQ_CHECK_HIP(attr_err);
             hipLaunchKernelGGL(smooth_quant_lds_kernel<LRS>, dim3(n_cu), dim3(threads), lds, st, a, CL);
