@@ -747,9 +747,9 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
     // with per-expert groups every group may end in a partial block: T/8 + E is an upper bound
     const int blocks = a.tab ? a.max_rows / QBLOCK_ROWS + a.n_sel : cdiv(a.T, QBLOCK_ROWS);
     if (nchunk <= CL) {
-        // one chunk per thread.  With enough rows to give every CU several slabs, the
-        // pipelined kernel (2 rows per row group per slab, next slab in flight through LDS),
-        // one work-group per CU
+        // one chunk per thread.  With enough rows to give every CU a slab, the pipelined kernel
+        // (2 rows per row group per slab, next slab in flight, transposed write-out), one
+        // work-group per CU
         constexpr int LRS = 2;
         const int rows = a.tab ? a.max_rows : a.T;
         static int n_cu = 0;
@@ -759,7 +759,7 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
             HAQ_CHECK_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, devid));
             n_cu = v > 64 ? v : 256;
         }
-        if (rows / (LRS * G) >= 4 * n_cu) {
+        if (rows / (LRS * G) >= n_cu) {
             const size_t red_bytes = 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
             const size_t lds = (size_t)qstage_rows(LRS * G) * qstage_pitch(nchunk) + red_bytes;
             static std::once_flag once;
