@@ -131,8 +131,11 @@ def test_linear_opt125m_config():
 
 
 @pytest.mark.parametrize("T,K,N,act", [(300, 832, 1040, "relu"), (1, 64, 16, "none"), (257, 1024, 272, "none"),
-                                        (513, 2048, 768, "relu"), (5, 32768, 48, "none"), (130, 65536, 16, "relu")])
+                                        (513, 2048, 768, "relu"), (5, 32768, 48, "none"), (130, 65536, 16, "relu"),
+                                        (4101, 128, 32, "relu"), (2051, 4096, 64, "none")])
 def test_linear_ragged_shapes(T, K, N, act):
+    """The last two are long enough for the pipelined quantisation kernel (its transposed write-out of the
+    packed codes ends in a partial block of rows)."""
     X, _, _ = hi.hidden_states(T + K, T, K, n_outlier=3)
     _linear_case(X, hi.gaussian_weight(T + K, 0, K, N), act)
 
@@ -229,8 +232,10 @@ def _check_moe(m, dev_experts=None, tokens=None, ctx=None):
 
 
 @pytest.mark.parametrize("T,H,I,E", [(37, 128, 320, 8), (1, 128, 192, 8), (300, 256, 576, 8), (9, 128, 192, 2),
-                                      (530, 192, 448, 4), (257, 128, 192, 8), (700, 128, 192, 32)])
+                                      (530, 192, 448, 4), (257, 128, 192, 8), (700, 128, 192, 32), (2100, 128, 256, 8)])
 def test_moe_small_everything_bit_exact(T, H, I, E):
+    """(The 2100-token case is long enough for the pipelined quantisation kernel on both the gathered token
+    rows and the per-expert requantisation, with expert groups that start at unaligned rows.)"""
     _check_moe(offline.small_moe(seed=20 + T, T=T, H=H, I=I, E=E))
 
 
