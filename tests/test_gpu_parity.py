@@ -279,6 +279,34 @@ def test_moe_one_or_two_tokens_fused_launches(T, H, I, E, same_experts):
     assert bits_equal(host(plain), out_ref)
 
 
+def test_moe_one_or_two_tokens_fused_launches_agree_with_the_five_launch_path():
+    """Many random small layers (expert counts 2..32, tied logits included): the three-launch path for one or
+    two tokens must give the bits of the five-launch path, which the other tests pin to the oracle."""
+    rng = np.random.default_rng(77)
+    for case in range(40):
+        T = int(rng.integers(1, 3))
+        E = int(rng.choice([2, 3, 8, 17, 32]))
+        H = int(rng.choice([128, 256, 640]))
+        I = int(rng.choice([256, 512, 1280]))
+        X = dev((rng.standard_normal((T, H)) * rng.choice([0.01, 1.0, 30.0])).astype(np.float16))
+        logits_h = rng.standard_normal((T, E)).astype(np.float16)
+        if case % 4 == 0:
+            logits_h[:] = logits_h[:, :1]  # every expert tied: the lowest indices win
+        logits = dev(logits_h)
+        s_in = dev(np.exp(rng.normal(0, 1, H)).astype(F32))
+        g = torch.Generator(device="cuda:0").manual_seed(case)
+        r8 = lambda n: torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda:0", generator=g)
+        rf = lambda n, lo, hi: torch.rand(n, device="cuda:0", generator=g) * (hi - lo) + lo
+        experts = [haq.ExpertWeights(r8(haq.haq_packed_bytes(H, 2 * I)), r8(haq.haq_packed_bytes(I, H)), rf(I, 1e-3, 2e-3),
+                                     rf(I, 1e-3, 2e-3), rf(H, 1e-3, 2e-3), rf(I, 0.5, 2.0)) for _ in range(E)]
+        fused = haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I)
+        general, d = haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I, debug=True)
+        torch.cuda.synchronize()
+        assert torch.equal(fused.view(torch.int16), general.view(torch.int16)), f"case {case}: T={T} E={E} H={H} I={I}"
+        if case % 4 == 0:
+            assert host(d.topk_idx).tolist() == [[0, 1]] * T
+
+
 def test_moe_decode_path_experts_with_more_than_32_rows():
     """Weight-streaming path with skewed routing: expert 0 takes every token (64 rows: two row blocks in
     one pass), another one more than 32, the rest few or none."""
