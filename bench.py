@@ -37,6 +37,9 @@ PEAK_FP64_TFLOPS = 78.6  # vector fp64 FMA
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
 # of the committed summary profiles/gemm_i8_kernel__opt6.7b_ffn.md and only applies to that workload.
 GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.856e+08
+# The same for one call of the decode layer (all its kernels; reads only, the writes are a few MB), from
+# profiles/decode_kernels__mixtral_decode.md: within 0.3-2 % of the algorithmic weight bytes.
+DECODE_TRAFFIC_BYTES = {"moe_decode_b1": 3.55e+08, "moe_decode_b8": 1.063e+09, "moe_decode_b64": 1.440e+09}
 
 
 def _events(torch, n):
@@ -297,7 +300,8 @@ def bench_moe(args, torch, haq, hi):
         res.update(metric="MoE layer tokens/s (decode)", value=T / sec, unit="tokens/s")
         res["roofline"] = {"bound": "hbm", "kernel": "whole layer (expert weight streaming dominates)",
                            "achieved": w_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                           "frac": w_bytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": None}
+                           "frac": w_bytes / sec / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": w_bytes,
+                           "traffic": DECODE_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per layer call"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = _moe_cpu_baseline(hi, wl, X_h, logits_h, prefill, res["unit"])
     return res
