@@ -221,8 +221,9 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_tiny_gate_up_kernel(D
     __shared__ float s_red[GU_WAVES], s_sx[2];
     const int tid = threadIdx.x;
     const int P = 2 * r.T;
-    route_in_lds(r.logits, r.ldl, r.T, a.E, rt);
-    if (blockIdx.x == 0 && blockIdx.y == 0) {
+    const bool writer = blockIdx.x == 0 && blockIdx.y == 0;  // leaves the routing results (gate weights included)
+    route_in_lds(r.logits, r.ldl, r.T, a.E, rt, writer);
+    if (writer) {
         if (tid < a.E) {
             r.tab_dev[tid] = tab.e[tid];
             r.counts[tid] = rt.cnt[tid];

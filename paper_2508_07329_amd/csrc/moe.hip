@@ -203,7 +203,7 @@ __global__ __launch_bounds__(PRO_THREADS) void decode_prologue_kernel(PrologueAr
     __shared__ float s_red[PRO_THREADS / 64];
     const int tid = threadIdx.x;
     const int P = 2 * a.T;
-    route_in_lds(a.logits, a.ldl, a.T, a.E, r);
+    route_in_lds(a.logits, a.ldl, a.T, a.E, r, blockIdx.x == 0);  // only work-group 0 writes the gate weights
     if (blockIdx.x == 0) {
         if (tid < a.E) {
             a.tab_dev[tid] = tab.e[tid];
