@@ -35,6 +35,8 @@ constexpr int DNG_DEPTH = 14, DNG_DEPTH2 = 9;
 constexpr int GU_DEPTH = 8;    // k-steps of weight fragments in flight per wave (two operands each)
 constexpr int DN_DEPTH = 14;
 constexpr int GU_DEPTH2 = 5;   // the same with two row blocks per work-group (twice the token fragments)
+constexpr int GU_DEPTH_TINY = 5;  // one or two tokens: four work-groups per CU (128 registers), so that the units of two
+                                  // experts (896 work-groups at the Mixtral shape) are all resident at once
 
 // blockIdx.y enumerates the experts that hold rows, in index order (the grid has min(E, 2T) of
 // them: with one token only two experts can be active, and work-groups that find nothing to do
@@ -214,7 +216,7 @@ struct TinyArgs {
 };
 
 template <int NCH>
-__global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_tiny_gate_up_kernel(DecodeArgs a, TinyArgs r, TabAll tab) {
+__global__ __launch_bounds__(GU_WAVES * 64, 4) void decode_tiny_gate_up_kernel(DecodeArgs a, TinyArgs r, TabAll tab) {
     __shared__ int part[GU_WAVES][2][16][64];  // the token codes live here until the K loop is over
     __shared__ float wmax[GU_WAVES][32];
     __shared__ RouteLds rt;
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_tiny_gate_up_kernel(D
     if (e < 0) return;
     const int lo = rt.off[e], m = rt.cnt[e];  // m <= 2: one pair per token at most
     int8_t* xq = reinterpret_cast<int8_t*>(part);
-    gate_up_body<1, GU_DEPTH, true>(a, tab.e[e], lo, m, blockIdx.x, part, wmax, xq, s_sx, [&] {
+    gate_up_body<1, GU_DEPTH_TINY, true>(a, tab.e[e], lo, m, blockIdx.x, part, wmax, xq, s_sx, [&] {
 #pragma nounroll
         for (int row = 0; row < m; ++row) {
             const int tok = rt.src[lo + row] >> 1;
