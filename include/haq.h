@@ -339,6 +339,17 @@ int32_t haq_ctx_cache_invalidate(haq_ctx* ctx);
  * input (index) order.  selected is [num_layers x (top_k + supplement_k)] in
  * order of selection, padded with -1; n_selected [num_layers].  All host.    */
 int32_t haq_offload_n_critical(double t_e, double latency_cpu, double latency_gpu, int64_t* n_critical);
+/* haq_lru_plan (Section III.C.1c, cache fill and LRU replacement): one call's look-ups in an
+ * expert cache of n_slots slots, on the caller's copy of the cache state.  slot_keys [n_slots]
+ * (in/out) is the key held by each slot, 0 for an empty one; slot_ticks [n_slots] (in/out) the
+ * time each slot was last used; *tick (in/out) the clock.  keys [n_keys] are the requests in
+ * order (non-zero, distinct).  For request k: hit[k] = 1 if a slot holds the key (no transfer);
+ * else it takes the first empty slot, else the least recently used one.  slot_of[k] is its slot;
+ * prev_user[k] is the earlier request of this same batch whose slot it takes over, or -1.
+ * haq_moe_w8a8_ffn plans with this function and takes the new state over only after every copy
+ * and launch of the call has been enqueued.  All host; n_slots, n_keys <= 32.                */
+int32_t haq_lru_plan(int32_t n_slots, uint64_t* slot_keys, uint64_t* slot_ticks, uint64_t* tick, const uint64_t* keys,
+                     int32_t n_keys, int32_t* slot_of, int32_t* hit, int32_t* prev_user);
 int32_t haq_select_experts(int32_t num_layers, int32_t experts_per_layer, int32_t top_k, int32_t supplement_k,
                            const int32_t* path_offsets, const int32_t* path_experts, int32_t path_len,
                            const double* path_freq, const double* expert_freq, int32_t* selected,

@@ -21,7 +21,7 @@ __all__ = [
     "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
-    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
+    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -42,7 +42,7 @@ EXPORTED_SYMBOLS = [
     "haq_ctx_destroy",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
-    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts",
+    "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -371,6 +371,19 @@ def haq_ctx_cache_stats(ctx):
 
 def haq_ctx_cache_invalidate(ctx):
     _check(lib().haq_ctx_cache_invalidate(ctx))
+
+
+def haq_lru_plan(slot_keys: list, slot_ticks: list, tick: int, keys: list):
+    """One batch of look-ups on a copy of an LRU cache's state.  Returns (slot_of, hit, prev_user, slot_keys,
+    slot_ticks, tick) with the state after the batch."""
+    n_slots, n = len(slot_keys), len(keys)
+    sk = (C.c_uint64 * n_slots)(*slot_keys)
+    stk = (C.c_uint64 * n_slots)(*slot_ticks)
+    tk = C.c_uint64(tick)
+    kk = (C.c_uint64 * max(1, n))(*keys)
+    so, hi, pu = (C.c_int32 * max(1, n))(), (C.c_int32 * max(1, n))(), (C.c_int32 * max(1, n))()
+    _check(lib().haq_lru_plan(n_slots, sk, stk, C.byref(tk), kk, n, so, hi, pu))
+    return list(so)[:n], [bool(h) for h in list(hi)[:n]], list(pu)[:n], list(sk), list(stk), int(tk.value)
 
 
 def haq_offload_n_critical(t_e: float, latency_cpu: float, latency_gpu: float):

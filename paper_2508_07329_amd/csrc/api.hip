@@ -413,6 +413,9 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: ldx=%lld ldl=%lld ldo=%lld", (long long)ldx, (long long)ldl, (long long)ldo);
     if (!aligned16(x_fp16) || !aligned16(out_fp16) || (s_in && !aligned16(s_in)))
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: pointers must be 16-byte aligned");
+    if (dbg && ((dbg->q && !aligned16(dbg->q)) || (dbg->hq && !aligned16(dbg->hq)) || (dbg->mid_fp16 && !aligned16(dbg->mid_fp16)) ||
+                (dbg->y_fp16 && !aligned16(dbg->y_fp16))))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn: debug buffers q, hq, mid_fp16 and y_fp16 must be 16-byte aligned");
     ExpertTab tab[32];
     int host_expert[32], n_host = 0;
     for (int e = 0; e < E; ++e) {
@@ -581,12 +584,6 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     HAQ_CHECK_HIP(hipMemcpyAsync(ctx->counts_host, counts, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HAQ_CHECK_HIP(hipEventRecord(ctx->routed, st));
     HAQ_CHECK_HIP(hipEventSynchronize(ctx->routed));
-    // slots may still be read by the previous call on another stream
-    if (ctx->used) {
-        HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->call_done, 0));
-        // and a cached expert was copied during an earlier call, possibly issued from another stream
-        HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->call_done, 0));
-    }
     int resident[32], n_res = 0, res_rows = 0;
     bool is_host[32] = {};
     for (int i = 0; i < n_host; ++i) is_host[host_expert[i]] = true;
@@ -595,45 +592,32 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
             resident[n_res++] = e;
             res_rows += ctx->counts_host[e];
         }
-    // Activated host experts in expert order.  Each one looks for its weights in the slots (hit:
-    // nothing to copy); on a miss it takes a free slot, else the least recently used one (cache
-    // fill and LRU replacement of Section III.C.1c).  With more activated host experts than
-    // slots the victim may be a slot handed out earlier in this very call: the copy then waits
-    // for that expert's GEMMs.
+    // Activated host experts in expert order go through the expert cache (Section III.C.1c): a
+    // hit costs no transfer, a miss takes a free slot, else the least recently used one.  With
+    // more activated host experts than slots the victim may be a slot handed out earlier in this
+    // very call: the copy then waits for that expert's GEMMs.  The plan is made on copies of the
+    // cache state; the context only takes it over once every copy and launch of the call is
+    // enqueued, so a call that fails half way never leaves a slot labelled with weights that did
+    // not arrive.
     int order[32], n_order = 0;
     for (int i = 0; i < n_host; ++i)
         if (ctx->counts_host[host_expert[i]] > 0) order[n_order++] = host_expert[i];
-    int slot_of[32], prev_user[32], user_this_call[32];
-    bool hit[32];
-    for (int sl = 0; sl < ctx->n_slots; ++sl) user_this_call[sl] = -1;
-    for (int k = 0; k < n_order; ++k) {
-        const void* key = experts[order[k]].w13;
-        int sl = -1;
-        for (int c = 0; c < ctx->n_slots; ++c)
-            if (ctx->slot_key[c] == key) sl = c;
-        hit[k] = sl >= 0;
-        if (sl < 0) {
-            for (int c = 0; c < ctx->n_slots && sl < 0; ++c)
-                if (!ctx->slot_key[c]) sl = c;
-            if (sl < 0) {
-                sl = 0;
-                for (int c = 1; c < ctx->n_slots; ++c)
-                    if (ctx->slot_tick[c] < ctx->slot_tick[sl]) sl = c;
-            }
-            ctx->misses += 1;
-            ctx->bytes_copied += (int64_t)(ctx->w13_bytes + ctx->w2_bytes);
-        } else {
-            ctx->hits += 1;
-        }
-        slot_of[k] = sl;
-        prev_user[k] = user_this_call[sl];  // >= 0 only after an eviction inside this call
-        user_this_call[sl] = k;
-        ctx->slot_key[sl] = key;
-        ctx->slot_tick[sl] = ++ctx->tick;
-        tab[order[k]].w13 = ctx->slot[sl];
-        tab[order[k]].w2 = ctx->slot[sl] + ctx->w13_bytes;
+    uint64_t keys_l[32], ticks_l[32], tick_l = ctx->tick, req[32];
+    for (int c = 0; c < 32; ++c) {
+        keys_l[c] = (uint64_t)(uintptr_t)ctx->slot_key[c];
+        ticks_l[c] = ctx->slot_tick[c];
     }
-    if ((rc = launch_set_tab(tab, E, w.tab, st)) != HAQ_OK) return rc;
+    for (int k = 0; k < n_order; ++k) req[k] = (uint64_t)(uintptr_t)experts[order[k]].w13;
+    int32_t slot_of[32], prev_user[32], hit[32];
+    if (n_order > 0 && (rc = haq_lru_plan(ctx->n_slots, keys_l, ticks_l, &tick_l, req, n_order, slot_of, hit, prev_user)) != HAQ_OK)
+        return rc;
+    int n_hit = 0;
+    for (int k = 0; k < n_order; ++k) {
+        n_hit += hit[k] ? 1 : 0;
+        tab[order[k]].w13 = ctx->slot[slot_of[k]];
+        tab[order[k]].w2 = ctx->slot[slot_of[k]] + ctx->w13_bytes;
+    }
+
     bool issued[32] = {};
     auto issue_copy = [&](int k) -> int {
         const int e = order[k];
@@ -644,43 +628,107 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         issued[k] = true;
         return HAQ_OK;
     };
-    // misses whose slot is not in use by an earlier expert of this call are copied right away
-    for (int k = 0; k < n_order; ++k)
-        if (!hit[k] && prev_user[k] < 0 && (rc = issue_copy(k)) != HAQ_OK) return rc;
-    // Device-resident experts, and cached ones whose slot nobody evicts later in this call, compute as
-    // one grouped launch while the first copies are in flight.
-    bool grouped[32] = {};
-    for (int k = 0; k < n_order; ++k) {
-        bool evicted_later = false;
-        for (int k2 = k + 1; k2 < n_order; ++k2) evicted_later = evicted_later || prev_user[k2] == k;
-        if (hit[k] && !evicted_later) {
-            grouped[k] = true;
-            resident[n_res++] = order[k];
-            res_rows += ctx->counts_host[order[k]];
+    auto enqueue = [&]() -> int {
+        int r;
+        // slots may still be read by the previous call on another stream
+        if (ctx->used) {
+            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->call_done, 0));
+            // and a cached expert was copied during an earlier call, possibly issued from another stream
+            HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->call_done, 0));
         }
+        if ((r = launch_set_tab(tab, E, w.tab, st)) != HAQ_OK) return r;
+        // misses whose slot is not in use by an earlier expert of this call are copied right away
+        for (int k = 0; k < n_order; ++k)
+            if (!hit[k] && prev_user[k] < 0 && (r = issue_copy(k)) != HAQ_OK) return r;
+        // Device-resident experts, and cached ones whose slot nobody evicts later in this call, compute as
+        // one grouped launch while the first copies are in flight.
+        bool grouped[32] = {};
+        for (int k = 0; k < n_order; ++k) {
+            bool evicted_later = false;
+            for (int k2 = k + 1; k2 < n_order; ++k2) evicted_later = evicted_later || prev_user[k2] == k;
+            if (hit[k] && !evicted_later) {
+                grouped[k] = true;
+                resident[n_res++] = order[k];
+                res_rows += ctx->counts_host[order[k]];
+            }
+        }
+        if (n_res > 0 && (r = run_experts(resident, n_res, res_rows)) != HAQ_OK) return r;
+        for (int k = 0; k < n_order; ++k) {
+            const int e = order[k];
+            if (grouped[k]) continue;
+            if (!hit[k]) {
+                if (!issued[k]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
+                HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[k], 0));
+            }
+            if ((r = run_experts(&e, 1, ctx->counts_host[e])) != HAQ_OK) return r;
+            HAQ_CHECK_HIP(hipEventRecord(ctx->done[k], st));
+            // a later expert of this call that evicts this one may overwrite the slot after these GEMMs
+            for (int k2 = k + 1; k2 < n_order; ++k2) {
+                if (prev_user[k2] != k) continue;
+                HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->done[k], 0));
+                if ((r = issue_copy(k2)) != HAQ_OK) return r;
+                break;
+            }
+        }
+        if ((r = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st)) != HAQ_OK) return r;
+        HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
+        return HAQ_OK;
+    };
+    rc = enqueue();
+    if (rc != HAQ_OK) {
+        // Some copies may have been issued into the slots: nothing the cache says about them can be
+        // trusted any more.  Forget every slot; the next call waits for whatever is still in flight.
+        for (int c = 0; c < 32; ++c) {
+            ctx->slot_key[c] = nullptr;
+            ctx->slot_tick[c] = 0;
+        }
+        (void)hipEventRecord(ctx->call_done, st);
+        ctx->used = true;
+        return rc;
     }
-    if (n_res > 0 && (rc = run_experts(resident, n_res, res_rows)) != HAQ_OK) return rc;
-    for (int k = 0; k < n_order; ++k) {
-        const int e = order[k];
-        if (grouped[k]) continue;
-        if (!hit[k]) {
-            if (!issued[k]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
-            HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[k], 0));
-        }
-        if ((rc = run_experts(&e, 1, ctx->counts_host[e])) != HAQ_OK) return rc;
-        HAQ_CHECK_HIP(hipEventRecord(ctx->done[k], st));
-        // a later expert of this call that evicts this one may overwrite the slot after these GEMMs
-        for (int k2 = k + 1; k2 < n_order; ++k2) {
-            if (prev_user[k2] != k) continue;
-            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->copy_stream, ctx->done[k], 0));
-            if ((rc = issue_copy(k2)) != HAQ_OK) return rc;
-            break;
-        }
+    for (int c = 0; c < 32; ++c) {
+        ctx->slot_key[c] = (const void*)(uintptr_t)keys_l[c];
+        ctx->slot_tick[c] = ticks_l[c];
     }
-    rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
-    HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
+    ctx->tick = tick_l;
+    ctx->hits += n_hit;
+    ctx->misses += n_order - n_hit;
+    ctx->bytes_copied += (int64_t)(n_order - n_hit) * (int64_t)(ctx->w13_bytes + ctx->w2_bytes);
     ctx->used = true;
-    return rc;
+    return HAQ_OK;
+}
+
+int32_t haq_lru_plan(int32_t n_slots, uint64_t* slot_keys, uint64_t* slot_ticks, uint64_t* tick, const uint64_t* keys,
+                     int32_t n_keys, int32_t* slot_of, int32_t* hit, int32_t* prev_user) {
+    if (n_slots < 1 || n_slots > 32 || n_keys < 0 || n_keys > 32) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_lru_plan: n_slots=%d n_keys=%d (both at most 32)", n_slots, n_keys);
+    if (!slot_keys || !slot_ticks || !tick || (n_keys > 0 && (!keys || !slot_of || !hit || !prev_user)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_lru_plan: null buffer");
+    for (int k = 0; k < n_keys; ++k) {
+        if (keys[k] == 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_lru_plan: key %d is 0 (0 marks an empty slot)", k);
+        for (int j = 0; j < k; ++j)
+            if (keys[j] == keys[k]) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_lru_plan: keys %d and %d are equal", j, k);
+    }
+    int user[32];  // request of this call that last took each slot
+    for (int c = 0; c < n_slots; ++c) user[c] = -1;
+    for (int k = 0; k < n_keys; ++k) {
+        int sl = -1;
+        for (int c = 0; c < n_slots && sl < 0; ++c)
+            if (slot_keys[c] == keys[k]) sl = c;
+        hit[k] = sl >= 0;
+        for (int c = 0; c < n_slots && sl < 0; ++c)  // miss: a free slot ...
+            if (slot_keys[c] == 0) sl = c;
+        if (sl < 0) {                                // ... else the one used longest ago
+            sl = 0;
+            for (int c = 1; c < n_slots; ++c)
+                if (slot_ticks[c] < slot_ticks[sl]) sl = c;
+        }
+        slot_of[k] = sl;
+        prev_user[k] = hit[k] ? -1 : user[sl];
+        user[sl] = k;
+        slot_keys[sl] = keys[k];
+        slot_ticks[sl] = ++*tick;
+    }
+    return HAQ_OK;
 }
 
 }  // extern "C"

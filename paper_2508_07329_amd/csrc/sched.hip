@@ -4,6 +4,8 @@
 
 #include <algorithm>
 #include <cmath>
+#include <new>
+#include <numeric>
 #include <vector>
 
 using namespace haq;
@@ -49,33 +51,38 @@ int32_t haq_select_experts(int32_t num_layers, int32_t experts_per_layer, int32_
                 if (e < 0 || e >= experts_per_layer) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_select_experts: expert %d in a path of layer %d", e, l);
             }
     }
+    // Algorithm 2, per layer.  Stage I: lay the layer's paths end to end, most frequent path first
+    // (equal frequencies in input order); the first top_k distinct experts of that sequence are
+    // placed.  Stage II: of the experts not placed yet, the most frequently activated ones (ties
+    // by index) fill the remaining top_k + supplement_k - (placed) positions.
+    try {
+    std::vector<int> paths, rest;
+    std::vector<char> placed((size_t)experts_per_layer);
     for (int l = 0; l < num_layers; ++l) {
         int32_t* sel = selected + (size_t)l * cap;
-        int n = 0;
-        auto has = [&](int e) { return std::find(sel, sel + n, e) != sel + n; };
-        // stage I: the layer's paths from the most frequent down (equal frequencies in input order)
-        std::vector<int> paths;
-        for (int p = path_offsets[l]; p < path_offsets[l + 1]; ++p) paths.push_back(p);
-        std::stable_sort(paths.begin(), paths.end(), [&](int a, int b) { return path_freq[a] > path_freq[b]; });
-        for (int p : paths) {
-            for (int j = 0; j < path_len; ++j) {
-                const int e = path_experts[(size_t)p * path_len + j];
-                if (!has(e) && n < cap) sel[n++] = e;
-                if (n >= top_k) break;
-            }
-            if (n >= top_k) break;
-        }
-        // stage II: the layer's most frequently activated experts not yet placed
-        std::vector<int> order(experts_per_layer);
-        for (int e = 0; e < experts_per_layer; ++e) order[e] = e;
         const double* f = expert_freq + (size_t)l * experts_per_layer;
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return f[a] > f[b]; });
-        for (int e : order) {
-            if (n >= cap) break;
-            if (!has(e)) sel[n++] = e;
+        std::fill(placed.begin(), placed.end(), 0);
+        paths.resize((size_t)(path_offsets[l + 1] - path_offsets[l]));
+        std::iota(paths.begin(), paths.end(), path_offsets[l]);
+        std::stable_sort(paths.begin(), paths.end(), [&](int a, int b) { return path_freq[a] > path_freq[b]; });
+        int n = 0;
+        for (size_t i = 0; i < paths.size() * (size_t)path_len && n < top_k; ++i) {
+            const int e = path_experts[(size_t)paths[i / path_len] * path_len + i % path_len];
+            if (!placed[e]) {
+                placed[e] = 1;
+                sel[n++] = e;
+            }
         }
+        rest.clear();
+        for (int e = 0; e < experts_per_layer; ++e)
+            if (!placed[e]) rest.push_back(e);
+        std::stable_sort(rest.begin(), rest.end(), [&](int a, int b) { return f[a] > f[b]; });
+        for (size_t i = 0; i < rest.size() && n < cap; ++i) sel[n++] = rest[i];
         n_selected[l] = n;
-        for (int i = n; i < cap; ++i) sel[i] = -1;
+        std::fill(sel + n, sel + cap, -1);
+    }
+    } catch (const std::bad_alloc&) {
+        HAQ_FAIL(HAQ_ERR_HIP, "haq_select_experts: out of host memory");
     }
     return HAQ_OK;
 }

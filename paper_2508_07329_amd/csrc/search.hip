@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <limits>
+#include <new>
 #include <vector>
 
 namespace haq {
@@ -248,7 +249,14 @@ int32_t haq_smoothing_search(const void* x_fp16, int64_t ldx, const float* w, in
     HAQ_CHECK_HIP(hipMemsetAsync(ws.aw, 0, (size_t)K * 4, st));
     if ((rc = haq_channel_absmax_f16(x_fp16, ldx, T, K, ws.ax, stream)) != HAQ_OK) return rc;
     if (use_weight && (rc = haq_weight_row_absmax(w, K, N, ws.aw, stream)) != HAQ_OK) return rc;
-    std::vector<float> ax((size_t)K), aw((size_t)K), s_all((size_t)n_e * K);
+    std::vector<float> ax, aw, s_all;  // host staging; no asynchronous copy outlives this function
+    try {
+        ax.resize((size_t)K);
+        aw.resize((size_t)K);
+        s_all.resize((size_t)n_e * K);
+    } catch (const std::bad_alloc&) {
+        HAQ_FAIL(HAQ_ERR_HIP, "haq_smoothing_search: out of host memory");
+    }
     HAQ_CHECK_HIP(hipMemcpyAsync(ax.data(), ws.ax, (size_t)K * 4, hipMemcpyDeviceToHost, st));
     HAQ_CHECK_HIP(hipMemcpyAsync(aw.data(), ws.aw, (size_t)K * 4, hipMemcpyDeviceToHost, st));
     HAQ_CHECK_HIP(hipStreamSynchronize(st));
@@ -256,6 +264,7 @@ int32_t haq_smoothing_search(const void* x_fp16, int64_t ldx, const float* w, in
         if ((rc = haq_smoothing_vector(ax.data(), use_weight ? aw.data() : nullptr, K, exponents[i], s_all.data() + (size_t)i * K)) != HAQ_OK)
             return rc;
     HAQ_CHECK_HIP(hipMemcpyAsync(ws.s_all, s_all.data(), s_all.size() * 4, hipMemcpyHostToDevice, st));
+    HAQ_CHECK_HIP(hipStreamSynchronize(st));  // s_all is pageable host memory: the copy has landed before any return below
 
     if ((rc = haq_reference_matmul_f64(x_fp16, ldx, w, T, K, N, ws.yref, stream)) != HAQ_OK) return rc;
     for (int i = 0; i < n_e; ++i) {
@@ -268,7 +277,7 @@ int32_t haq_smoothing_search(const void* x_fp16, int64_t ldx, const float* w, in
         if ((rc = haq_quant_loss_f64(ws.y, N, ws.yref, T, N, ws.row_sum, ws.losses + i, stream)) != HAQ_OK) return rc;
     }
     HAQ_CHECK_HIP(hipMemcpyAsync(losses, ws.losses, (size_t)n_e * 8, hipMemcpyDeviceToHost, st));
-    HAQ_CHECK_HIP(hipStreamSynchronize(st));  // also keeps s_all alive until its copy has landed
+    HAQ_CHECK_HIP(hipStreamSynchronize(st));
 
     // a candidate replaces the incumbent only if its loss is strictly smaller
     int b = -1;

@@ -135,3 +135,50 @@ def test_algorithm2_reproduces_the_resident_set_of_the_offload_workload():
     sel = haq.haq_select_experts(1, wl.E, 2, 2, path_stats, [pop])
     assert sel == [[0, 1, 2, 3]] and sorted(sel[0]) == sorted(wl.resident)
     assert sel == oracle.select_experts(1, 2, 2, path_stats, [list(enumerate(pop))])
+
+
+def test_lru_plan_follows_a_plain_lru_cache():
+    """The cache planner of the offload path, batch after batch, against the oracle's LRU trace (which is
+    pinned by the textbook reference string): same hits, same final content, and prev_user names exactly
+    the earlier request of the same batch whose slot a request takes over."""
+    rng = np.random.default_rng(11)
+    for n_slots in (1, 2, 3, 5):
+        keys, ticks, tick = [0] * n_slots, [0] * n_slots, 0
+        trace, hits = [], []
+        for _ in range(40):
+            batch = [int(k) for k in rng.permutation(np.arange(1, 9))[:int(rng.integers(0, 7))]]
+            so, hi, pu, keys, ticks, tick = haq.haq_lru_plan(keys, ticks, tick, batch)
+            trace += batch
+            hits += hi
+            last = {}
+            for k, (slot, h, prev) in enumerate(zip(so, hi, pu)):
+                assert 0 <= slot < n_slots
+                assert prev == (-1 if h else last.get(slot, -1))
+                last[slot] = k
+            for slot, k in last.items():
+                assert keys[slot] == batch[k]
+        hit_ref, cache_ref = oracle.lru_trace(trace, n_slots)
+        assert hits == hit_ref
+        assert sorted(k for k in keys if k) == sorted(cache_ref)
+        # least recently used first = ascending last-use time
+        assert [k for _, k in sorted((t, k) for t, k in zip(ticks, keys) if k)] == cache_ref
+    L = haq.lib()
+    two = (C.c_uint64 * 2)(5, 5)
+    st = (C.c_uint64 * 2)()
+    i2 = (C.c_int32 * 2)()
+    assert L.haq_lru_plan(2, st, st, C.byref(C.c_uint64(0)), two, 2, i2, i2, i2) == -1
+    assert "equal" in L.haq_last_error().decode()
+
+
+def test_moe_rejects_misaligned_debug_buffers():
+    L = haq.lib()
+    one = C.c_void_p(16)
+    descs = (binding._ExpertDesc * 2)()
+    for d in descs:
+        d.w13 = d.w2 = d.sw1 = d.sw3 = d.sw2 = d.s_mid = 16
+    for field in ("q", "hq", "mid_fp16", "y_fp16"):
+        dbg = binding._MoeDebug()
+        setattr(dbg, field, 24)
+        rc = L.haq_moe_w8a8_ffn(None, one, C.c_int64(64), one, C.c_int64(8), None, descs, 4, 64, 64, 2, 2, one,
+                                C.c_int64(64), C.byref(dbg), one, C.c_size_t(0), None)
+        assert rc == -1 and "debug buffers" in L.haq_last_error().decode(), field
