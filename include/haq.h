@@ -373,6 +373,26 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
                          int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg_host,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * haq_moe_w8a8_ffn for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * haq_moe_w8a8_ffn with ctx = NULL and dbg = NULL (every expert device resident),
+ * but the scratch memory is an array of 16 MiB built into the library (one per
+ * GPU, held until the process ends) instead of a caller workspace.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ * Limit: haq_moe_workspace_bytes(T, H, I, E) <= 16 MiB (the Mixtral geometry, H =
+ * 4096, I = 14336, 8 experts: up to 104 tokens); larger problems return HAQ_ERR_WORKSPACE and
+ * say how much was needed.  The first call on a device looks the array's address
+ * up (make that call outside graph capture); call with the stream's device current.
+ * All calls on one GPU share the array: calls that overlap on one GPU (two streams, or two host
+ * threads) race; calls on one stream are ordered and safe.  Nothing in the array
+ * has to be cleared between calls: every buffer carved from it is written before
+ * it is read within a call.                                                    */
+int32_t haq_moe_w8a8_ffn_static(const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl,
+                                const float* s_in, const haq_expert_desc* experts_host, int32_t T, int32_t H,
+                                int32_t I, int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@ __all__ = [
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
+    "haq_moe_w8a8_ffn_static",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -43,6 +44,7 @@ EXPORTED_SYMBOLS = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
+    "haq_moe_w8a8_ffn_static",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -318,6 +320,20 @@ def haq_moe_w8a8_ffn(x, logits, s_in, experts: list[ExpertWeights], I: int, *, c
                                   C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),
                                   C.c_size_t(workspace.numel()), _stream()))
     return (y, dbg) if debug else y
+
+
+def haq_moe_w8a8_ffn_static(x, logits, s_in, experts, I: int, *, out):
+    """haq_moe_w8a8_ffn on the library's built-in scratch array: nothing is allocated, so `out` is required."""
+    T, H = x.shape
+    E = len(experts)
+    descs = (_ExpertDesc * E)()
+    for i, e in enumerate(experts):
+        descs[i].w13, descs[i].w2 = e.w13.data_ptr(), e.w2.data_ptr()
+        descs[i].sw1, descs[i].sw3, descs[i].sw2 = e.sw1.data_ptr(), e.sw3.data_ptr(), e.sw2.data_ptr()
+        descs[i].s_mid, descs[i].location = e.s_mid.data_ptr(), e.location
+    _check(lib().haq_moe_w8a8_ffn_static(_ptr(x), C.c_int64(x.stride(0)), _ptr(logits), C.c_int64(logits.stride(0)), _ptr(s_in),
+                                         descs, T, H, I, E, 2, _ptr(out), C.c_int64(out.stride(0)), _stream()))
+    return out
 
 
 # ---- adaptive smoothing (Algorithm 1 step 1) --------------------------------------------

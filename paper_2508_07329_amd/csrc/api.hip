@@ -2,6 +2,7 @@
 // launch sequence of the linear layer and of the routed expert FFN.
 #include <cmath>
 #include <cstdarg>
+#include <mutex>
 #include <new>
 
 #include "haq_common.h"
@@ -147,6 +148,29 @@ int gemm_packed(const int8_t* q_cm, const float* sx, const int8_t* w_packed, con
 }  // namespace haq
 
 using namespace haq;
+
+// Scratch memory of haq_moe_w8a8_ffn_static: one array per GPU, part of the loaded code object
+// (it lives until the process ends).  In host code the name `scratch` is only a handle for the
+// symbol; the array's device address is looked up once per device and kept in g_scratch_ptr.
+#define HAQ_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[HAQ_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[64] = {};
+static std::mutex g_scratch_mutex;
+
+static int static_scratch_address(void** out) {
+    int dev = -1;
+    HAQ_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_static: device ordinal %d outside [0, 64)", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HAQ_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn_static: the scratch array has no device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return HAQ_OK;
+}
 
 // Context of layers with host-resident experts: staging slots in HBM, the copy stream and the
 // events that order copies against the GEMMs that read (and later overwrite) a slot.
@@ -696,6 +720,28 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     ctx->bytes_copied += (int64_t)(n_order - n_hit) * (int64_t)(ctx->w13_bytes + ctx->w2_bytes);
     ctx->used = true;
     return HAQ_OK;
+}
+
+int32_t haq_moe_w8a8_ffn_static(const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl, const float* s_in,
+                                const haq_expert_desc* experts, int32_t T, int32_t H, int32_t I, int32_t E, int32_t top_k,
+                                void* out_fp16, int64_t ldo, void* stream) {
+    if (T < 0 || H <= 0 || I <= 0 || E <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_static: T=%d H=%d I=%d E=%d", T, H, I, E);
+    const size_t need = haq_moe_workspace_bytes(T, H, I, E);
+    if (need > HAQ_STATIC_SCRATCH_BYTES)
+        HAQ_FAIL(HAQ_ERR_WORKSPACE,
+                 "haq_moe_w8a8_ffn_static: T=%d H=%d I=%d E=%d needs %zu bytes of scratch, the built-in array holds %u; use "
+                 "haq_moe_w8a8_ffn with a workspace",
+                 T, H, I, E, need, (unsigned)HAQ_STATIC_SCRATCH_BYTES);
+    if (experts)
+        for (int e = 0; e < E && e < 32; ++e)
+            if (experts[e].location != HAQ_LOC_DEVICE)
+                HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_static: expert %d is not device resident", e);
+    void* ws = nullptr;
+    const int rc = static_scratch_address(&ws);
+    if (rc != HAQ_OK) return rc;
+    // every buffer carved from the scratch is written before it is read within the call: nothing has to be cleared
+    return haq_moe_w8a8_ffn(nullptr, x_fp16, ldx, logits_fp16, ldl, s_in, experts, T, H, I, E, top_k, out_fp16, ldo, nullptr, ws,
+                            HAQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 int32_t haq_lru_plan(int32_t n_slots, uint64_t* slot_keys, uint64_t* slot_ticks, uint64_t* tick, const uint64_t* keys,
