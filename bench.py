@@ -9,12 +9,17 @@ packed once, outside the timed region, by the library's own offline kernels.
 
 Prints ONE JSON line.  `roofline` is for the dominant kernel (the int8 MFMA
 GEMM), timed with events around its launches; `cpu_baseline` is the CPU oracle
-timed on a bounded sample of the same workload.
+timed on a bounded sample of the same workload.  With no --workload the line
+also carries `configs`: one record (time per step, metric, roofline, bounded
+CPU-oracle baseline) for each of the other configurations of the metric -- the
+OPT-125m linear, the Mixtral-shaped layer in prefill (4096 tokens, Zipf
+routing), in decode (1, 8, 64 tokens: HBM GB/s and tokens/s) and with 4 of 8
+experts streamed from host memory; the Mixtral layer is built once for all of them.
 
-Other workloads (--workload): linear (OPT-125m linear), moe_prefill (Mixtral
-layer, 4096 tokens, Zipf routing), moe_decode_b1 / _b8 / _b64, moe_offload, and
-smooth_search and hessian_quant (the offline grid search of the smoothing
-exponent and the Hessian-aware weight quantiser, on fc1 of the default block).
+Single workloads (--workload): ffn, linear, moe_prefill, moe_decode_b1 / _b8 /
+_b64, moe_offload, and smooth_search and hessian_quant (the offline grid search
+of the smoothing exponent and the Hessian-aware weight quantiser, on fc1 of the
+default block).
 """
 from __future__ import annotations
 
@@ -30,8 +35,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5033.0  # dense int8 MFMA, 256 CU x 8192 op/clk x 2.4 GHz
+INT8_OPS_PER_CLOCK = 256 * 8192  # whole chip, per shader clock
 PEAK_HBM_GBS = 8000.0
 PEAK_FP64_TFLOPS = 78.6  # vector fp64 FMA
+# Vector ALU issue rate for plain (unpacked, non-fused) fp32 instructions: 256 CU x 4 SIMD x 16 lanes
+# x 2.4 GHz = 39.3 T lane-instructions/s (the published 157.3 TFLOP/s counts a packed FMA as 4 flop).
+PEAK_VALU_TLANE_INSTR = 256 * 4 * 16 * 2.4e9 / 1e12
+# fp32 vector instructions the activation-quantisation kernels spend per element (two divisions by reused
+# divisors through reciprocals, absmax, rounding, packing; counted from rocprofv3 --pmc SQ_INSTS_VALU x 64
+# lanes / elements, see profiles/): the kernel's ALU floor is this many lane-instructions per element
+QUANT_VALU_PER_ELEMENT = 24.0
 # Fabric-side bytes of one GEMM launch of the default workload (average of fc1 and fc2), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
@@ -49,20 +62,20 @@ def _events(torch, n):
 SETTLE_SECONDS = 0.5
 
 
-def _settle(torch, step):
+def _settle(torch, step, seconds=SETTLE_SECONDS):
     """Part of set-up, before the warm-up steps: the device comes out of idle with low clocks and needs a
     few tens of milliseconds of load before its clocks settle (the same step measures 350 us right after
     idle and 300 us from then on, for as long as the load lasts).  A serving process is never idle
     between steps, so the settled state is the one to measure."""
     t0 = time.perf_counter()
-    while time.perf_counter() - t0 < SETTLE_SECONDS:
+    while time.perf_counter() - t0 < seconds:
         for _ in range(10):
             step()
         torch.cuda.synchronize()
 
 
-def _time_steps(torch, step, steps, warmup):
-    _settle(torch, step)
+def _time_steps(torch, step, steps, warmup, settle=SETTLE_SECONDS):
+    _settle(torch, step, settle)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -73,8 +86,88 @@ def _time_steps(torch, step, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
-def bench_ffn(args, torch, haq, hi):
-    wl = hi.OPT67B_FFN if args.workload == "ffn" else None
+def _stage_times(torch, haq, step, steps):
+    """Average duration of every stage of a block-level call, from the events the library records at its
+    stage boundaries on the launch stream (a second pass of `steps` steps, after the wall-clock one)."""
+    haq.haq_profile_enable(True)
+    try:
+        acc = {}
+        for _ in range(steps):
+            step()
+            for name, ms in haq.haq_profile_read():
+                acc.setdefault(name, []).append(ms)
+    finally:
+        haq.haq_profile_enable(False)
+    return {name: float(np.mean(v)) for name, v in acc.items()}
+
+
+def _quant_record(name, rows, cols, ms):
+    """An activation-quantisation kernel against its two bounds: HBM (3 bytes per element: fp16 in, int8 out)
+    and the vector ALUs (QUANT_VALU_PER_ELEMENT lane-instructions per element)."""
+    el = float(rows) * cols
+    sec = ms * 1e-3
+    return {"kernel": name, "rows": int(rows), "cols": int(cols), "ms": ms,
+            "hbm": {"achieved": 3.0 * el / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": 3.0 * el / sec / 1e9 / PEAK_HBM_GBS},
+            "alu": {"achieved": QUANT_VALU_PER_ELEMENT * el / sec / 1e12, "peak": PEAK_VALU_TLANE_INSTR, "unit": "T lane-instr/s",
+                    "frac": QUANT_VALU_PER_ELEMENT * el / sec / 1e12 / PEAK_VALU_TLANE_INSTR,
+                    "lane_instr_per_element": QUANT_VALU_PER_ELEMENT}}
+
+
+def _mfma_ceiling(torch, haq, data, work_groups, seconds):
+    """Sustained rate of the pure-MFMA loop (operands in registers, no memory traffic) on `data`."""
+    iters = 20000
+    out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)
+    launch = lambda: haq.haq_probe_mfma_i8(data, iters, work_groups, out=out)
+    ev = _events(torch, 2)
+    launch()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    launch()
+    torch.cuda.synchronize()
+    n = max(3, int(seconds / max(time.perf_counter() - t0, 1e-4)))
+    for _ in range(max(1, n // 3)):  # settle
+        launch()
+    ev[0].record()
+    for _ in range(n):
+        launch()
+    ev[1].record()
+    torch.cuda.synchronize()
+    sec = ev[0].elapsed_time(ev[1]) * 1e-3
+    return n * work_groups * 4.0 * iters * 32 * 65536 / sec / 1e12, sec
+
+
+def _fragment_sets(torch, q_packed, R, w_packed, Npad):
+    """24 KiB of operand fragments for the MFMA probe cut out of packed operands of the workload: four sets of
+    2 token + 4 weight fragments, each 32 rows x 32 consecutive k (two neighbouring 16-byte chunks)."""
+    qa = q_packed.view(-1, R, 16)
+    wb = w_packed.view(-1, Npad, 16)
+    g = torch.Generator(device="cpu").manual_seed(0)
+    frags = []
+    for _ in range(4):
+        for src, rows, n in ((qa, R - 256 - 32, 2), (wb, Npad - 32, 4)):
+            for _ in range(n):
+                c = int(torch.randint(0, src.shape[0] // 2, (1,), generator=g)) * 2
+                r = int(torch.randint(0, max(1, rows), (1,), generator=g))
+                frags.append(torch.cat([src[c, r:r + 32].reshape(-1), src[c + 1, r:r + 32].reshape(-1)]))
+    return torch.cat(frags).contiguous()
+
+
+def _clock_mhz_under(torch, haq, launch, n_launches, ticks=300000):
+    """Shader clock while `launch` x n_launches run on the current stream, read by a one-wave probe on a second
+    stream (default priority) that spins for `ticks` periods of the 100 MHz counter."""
+    side = torch.cuda.Stream()
+    out = torch.zeros((2,), dtype=torch.int64, device="cuda:0")
+    torch.cuda.synchronize()
+    for _ in range(n_launches):
+        launch()
+    haq.haq_probe_clock(ticks, out=out, stream=side)
+    torch.cuda.synchronize()
+    c, w = (int(v) for v in out.tolist())
+    return c / max(w, 1) * 100.0
+
+
+def bench_ffn(args, torch, haq, hi, cpu_seconds=10.0):
+    wl = hi.OPT67B_FFN if args.workload in ("ffn", "all") else None
     dev = "cuda:0"
     if wl is not None:
         T, K, F, name = wl.T, wl.H, wl.F, wl.name
@@ -108,10 +201,7 @@ def bench_ffn(args, torch, haq, hi):
     two = W2_h is not None
     if two:
         s2, w2p, sw2 = offline(h, W2_h)
-        ws2 = torch.empty(haq.haq_linear_workspace_bytes(T, F, K), dtype=torch.uint8, device=dev)
         y = torch.empty((T, K), dtype=torch.float16, device=dev)
-
-    if two:
         wsf = torch.empty(haq.haq_ffn_workspace_bytes(T, K, F, K), dtype=torch.uint8, device=dev)
 
     def step():
@@ -125,26 +215,60 @@ def bench_ffn(args, torch, haq, hi):
     n_gemm = 2 if two else 1
     tops = n_gemm * ops_per_gemm / sec / 1e12
 
-    # dominant kernel (int8 GEMM + epilogue), events around each of its launches
+    # dominant kernel (int8 GEMM + epilogue) and the quantisation kernels, events around each launch
     q1, sx1 = haq.haq_quant_act_packed(X, s1)
     if two:
         q2, sx2 = haq.haq_quant_act_packed(h, s2)
-    ev = _events(torch, 2 * n_gemm * args.steps)
+    per = 2 * n_gemm + 1
+    ev = _events(torch, per * args.steps)
     torch.cuda.synchronize()
     for i in range(args.steps):
+        ev[per * i].record()
         haq.haq_quant_act_packed(X, s1, q_packed=q1, row_scale=sx1)
-        ev[2 * n_gemm * i].record()
+        ev[per * i + 1].record()
         haq.haq_gemm_w8a8_packed(q1, sx1, w1p, sw1, T, K, F, haq.HAQ_ACT_RELU, out=h)
-        ev[2 * n_gemm * i + 1].record()
+        ev[per * i + 2].record()
         if two:
             haq.haq_quant_act_packed(h, s2, q_packed=q2, row_scale=sx2)
-            ev[2 * n_gemm * i + 2].record()
+            ev[per * i + 3].record()
             haq.haq_gemm_w8a8_packed(q2, sx2, w2p, sw2, T, F, K, haq.HAQ_ACT_NONE, out=y)
-            ev[2 * n_gemm * i + 3].record()
+            ev[per * i + 4].record()
     torch.cuda.synchronize()
-    gemm_ms = [ev[2 * j].elapsed_time(ev[2 * j + 1]) for j in range(n_gemm * args.steps)]
+    span = lambda j: float(np.mean([ev[per * i + j].elapsed_time(ev[per * i + j + 1]) for i in range(args.steps)]))
+    gemm_ms = [span(1)] + ([span(3)] if two else [])
     gemm_avg = float(np.mean(gemm_ms)) * 1e-3
     achieved = ops_per_gemm / gemm_avg / 1e12
+    quant = [_quant_record("activation quantisation of X (fp16 -> packed int8 + row scales)", T, K, span(0))]
+    if two:
+        quant.append(_quant_record("requantisation of the fp16 intermediate", T, F, span(2)))
+
+    roof = {"bound": "mfma", "kernel": "gemm_i8_kernel (int8 MFMA GEMM + dequant epilogue)",
+            "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
+            "avg_launch_ms": gemm_avg * 1e3, "launch_ms": gemm_ms, "ops_per_launch": ops_per_gemm,
+            "traffic": GEMM_TRAFFIC_BYTES_OPT67B_FFN if wl is not None else None, "traffic_unit": "bytes per launch"}
+    if two and not args.no_ceilings:
+        # the peak at the clock the chip really runs this kernel at, and what the matrix cores sustain on a
+        # pure-MFMA loop (no memory traffic at all) fed with operands of this very workload and with uniform
+        # random codes: the distance from the nominal peak that no kernel design can recover on this data
+        gemm1 = lambda: haq.haq_gemm_w8a8_packed(q1, sx1, w1p, sw1, T, K, F, haq.HAQ_ACT_RELU, out=h)
+        _settle(torch, gemm1, 0.2)
+        mhz = float(np.median([_clock_mhz_under(torch, haq, gemm1, 80) for _ in range(3)]))
+        roof["clock_mhz_under_kernel"] = mhz
+        roof["peak_measured"] = INT8_OPS_PER_CLOCK * mhz * 1e6 / 1e12
+        roof["frac_measured"] = achieved / roof["peak_measured"]
+        R, Npad = int(haq.haq_packed_act_rows(T)), (F + 255) // 256 * 256
+        data_wl = _fragment_sets(torch, q1, R, w1p, Npad)
+        g = torch.Generator(device="cuda:0").manual_seed(1)
+        data_rnd = torch.randint(-127, 128, (24576,), dtype=torch.int8, device=dev, generator=g)
+        ceil = {}
+        for label, data in (("workload_codes", data_wl), ("uniform_random_codes", data_rnd)):
+            for wgs, tag in ((256, "1_wave_per_simd"), (512, "2_waves_per_simd")):
+                v, dur = _mfma_ceiling(torch, haq, data, wgs, 0.5)
+                ceil[f"{label}/{tag}"] = {"TOPs": v, "seconds": dur}
+        best = max(v["TOPs"] for k, v in ceil.items() if k.startswith("workload_codes"))
+        roof["sustained_mfma_ceiling"] = ceil
+        roof["peak_sustained"] = best
+        roof["frac_sustained"] = achieved / best
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -158,7 +282,7 @@ def bench_ffn(args, torch, haq, hi):
             so2 = oracle.smoothing_vector(oracle.col_absmax_f16(h_all), oracle.row_absmax_f32(W2_h), 0.5)
             W2q, swo2 = oracle.quant_weight(W2_h, so2)
         reps, dt = 0, 0.0
-        while dt < 10.0 and reps < 50:  # about 10 s of CPU work
+        while dt < cpu_seconds and reps < 1000:
             t0 = time.perf_counter()
             hh = oracle.w8a8_linear(X_h[rows], so1, W1q, swo1, "relu")
             if two:
@@ -167,7 +291,7 @@ def bench_ffn(args, torch, haq, hi):
             reps += 1
         cpu = {"value": reps * n_gemm * 2.0 * n_rows * K * F / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
                "kind": "oracle",
-               "sample": f"first {n_rows} of {T} token rows through the whole block, {reps} repetitions, {dt:.2f} s"}
+               "sample": f"first {n_rows} of {T} token rows through the whole {'block' if two else 'linear'}, {reps} repetitions, {dt:.2f} s"}
 
     return {
         "metric": "W8A8 expert-FFN int8 TOPS (prefill)", "value": tops, "unit": "TOPS",
@@ -175,31 +299,19 @@ def bench_ffn(args, torch, haq, hi):
         "config": {"workload": name, "tokens": T, "in_features": K, "hidden_features": F, "out_features": n_out,
                    "act": "relu", "smoothing_alpha": 0.5, "gemms_per_step": n_gemm},
         "offline_quantise_and_pack_ms_per_matrix": t_off * 1e3,
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (int8 MFMA GEMM + dequant epilogue)",
-                     "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
-                     "avg_launch_ms": gemm_avg * 1e3, "ops_per_launch": ops_per_gemm,
-                     "traffic": GEMM_TRAFFIC_BYTES_OPT67B_FFN if wl is not None else None, "traffic_unit": "bytes per launch"},
+        "roofline": roof, "other_kernels": quant,
         "cpu_baseline": cpu,
     }
 
 
-def bench_moe(args, torch, haq, hi):
+# ---- the Mixtral-shaped layer: built once, shared by the prefill, decode and offload records -------------
+def build_mixtral(torch, haq, hi, keep_host=False):
+    """Offline quantisation of the layer by the library's own kernels: s_in from 256 calibration tokens and all
+    gate/up matrices, s_mid per expert from the library's own intermediate on the calibration tokens."""
     dev = "cuda:0"
-    if args.workload == "moe_prefill":
-        wl = hi.MIXTRAL_PREFILL
-    elif args.workload == "moe_offload":
-        wl = hi.MIXTRAL_OFFLOAD
-    else:
-        b = int(args.workload.rsplit("b", 1)[1])
-        wl = {w.T: w for w in hi.MIXTRAL_DECODE}[b]
-    T, H, I, E = wl.T, wl.H, wl.I, wl.E
-    cal = hi.MIXTRAL_CALIB
+    wl = cal = hi.MIXTRAL_CALIB
+    H, I, E = wl.H, wl.I, wl.E
     Xc = torch.from_numpy(hi.moe_hidden_states(cal)).to(dev)
-    X_h = hi.moe_hidden_states(wl)
-    logits_h = hi.moe_logits(wl, X_h)
-    X, logits = torch.from_numpy(X_h).to(dev), torch.from_numpy(logits_h).to(dev)
-    # offline: s_in from the calibration tokens and all gate/up matrices; s_mid = 1 smoothing-free start,
-    # then calibrated from the library's own intermediate on the calibration tokens
     ax = haq.haq_channel_absmax_f16(Xc)
     aw = torch.zeros(H, dtype=torch.float32, device=dev)
     from concurrent.futures import ThreadPoolExecutor
@@ -207,7 +319,8 @@ def bench_moe(args, torch, haq, hi):
     with ThreadPoolExecutor(8) as pool:
         host_mats = list(pool.map(lambda ew: hi.moe_weight(wl, *ew), names))
     mats = {ew: torch.from_numpy(m).to(dev) for ew, m in zip(names, host_mats)}
-    del host_mats
+    if not keep_host:
+        host_mats = None
     for e in range(E):
         haq.haq_weight_row_absmax(mats[(e, "w1")], aw)
         haq.haq_weight_row_absmax(mats[(e, "w3")], aw)
@@ -231,94 +344,22 @@ def bench_moe(args, torch, haq, hi):
         st = stage1[e]
         experts.append(haq.ExpertWeights(st.w13, haq.haq_pack_weight(w2q), st.sw1, st.sw3, sw2, s_mid))
     del mats, stage1, dbg
-    ws = torch.empty(haq.haq_moe_workspace_bytes(T, H, I, E), dtype=torch.uint8, device=dev)
-    out = torch.empty((T, H), dtype=torch.float16, device=dev)
-    _, dbg = haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I, debug=True)
-    counts = dbg.counts.cpu().numpy()
-    if args.workload == "moe_offload":
-        return bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out)
-
-    # Inputs of one step.  Decode is bound by reading each activated expert's weights once, and in a
-    # model no weight is touched twice per token; here one layer is replayed, and the 256 MB last-level
-    # cache would keep part of a working set that comes round again too soon.  So a replay walks over
-    # four copies of the layer's weights at distinct addresses (5.6 GB between two reads of the same
-    # bytes), and the single-token step in addition over four tokens (drawn from the 64-token batch of
-    # the same workload family) whose expert pairs are disjoint.
-    pool = [(X, logits)]
-    if T == 1:
-        wl64 = {w.T: w for w in hi.MIXTRAL_DECODE}[64]
-        X64_h = hi.moe_hidden_states(wl64)
-        L64_h = hi.moe_logits(wl64, X64_h)
-        X64, L64 = torch.from_numpy(X64_h).to(dev), torch.from_numpy(L64_h).to(dev)
-        _, d64 = haq.haq_moe_w8a8_ffn(X64, L64, s_in, experts, I, debug=True)
-        pairs = d64.topk_idx.cpu().numpy()
-        chosen, used = [], set()
-        for t in range(64):
-            if not (set(pairs[t].tolist()) & used):
-                chosen.append(t)
-                used |= set(pairs[t].tolist())
-        pool = [(X64[t:t + 1].contiguous(), L64[t:t + 1].contiguous()) for t in chosen]
-    n_sets = 1 if args.workload == "moe_prefill" else 4
-    sets = [experts] + [[haq.ExpertWeights(ex.w13.clone(), ex.w2.clone(), ex.sw1, ex.sw3, ex.sw2, ex.s_mid) for ex in experts]
-                        for _ in range(n_sets - 1)]
-    calls = [(x_i, l_i, ws_i) for ws_i in sets for (x_i, l_i) in pool]
-    outs = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in calls]
     torch.cuda.synchronize()
-    # the launch sequence of one step is captured once and replayed: the decode layer is a handful
-    # of short kernels and would otherwise be bound by host launch overhead
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        for (x_i, l_i, ex_i), o_i in zip(calls, outs):
-            haq.haq_moe_w8a8_ffn(x_i, l_i, s_in, ex_i, I, out=o_i, workspace=ws)
-
-    def step():
-        graph.replay()
-
-    sec = _time_steps(torch, step, args.steps, args.warmup) / len(calls)
-    eager = haq.haq_moe_w8a8_ffn(pool[0][0], pool[0][1], s_in, experts, I)
-    torch.cuda.synchronize()
-    if not torch.equal(eager, outs[0]):
-        raise SystemExit("bench.py: graph replay and eager call disagree")
-    pairs = int(counts.sum())
-    ops = pairs * 2.0 * 3 * H * I
-    n_active = int((counts > 0).sum())
-    w_bytes = n_active * (3.0 * H * I + 4.0 * (2 * I + H + I))
-    prefill = args.workload == "moe_prefill"
-    res = {
-        "ms_per_step": sec * 1e3, "dtype": "int8",
-        "config": {"workload": wl.name, "tokens": T, "hidden": H, "intermediate": I, "experts": E, "top_k": 2,
-                   "pairs_per_expert": counts.tolist(), "activated_experts": n_active,
-                   "launch": "hipGraph replay", "calls_per_replay": len(calls), "weight_copies": n_sets},
-        "tokens_per_s": T / sec, "layer_tops": ops / sec / 1e12, "weight_stream_GBs": w_bytes / sec / 1e9,
-        "cpu_baseline": None,
-    }
-    if prefill:
-        res.update(metric="W8A8 expert-FFN int8 TOPS (prefill)", value=ops / sec / 1e12, unit="TOPS")
-        res["roofline"] = {"bound": "mfma", "kernel": "whole layer (grouped int8 GEMMs dominate)", "achieved": ops / sec / 1e12,
-                           "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": ops / sec / 1e12 / PEAK_INT8_TOPS, "traffic": None}
-    else:
-        res.update(metric="MoE layer tokens/s (decode)", value=T / sec, unit="tokens/s")
-        res["roofline"] = {"bound": "hbm", "kernel": "whole layer (expert weight streaming dominates)",
-                           "achieved": w_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                           "frac": w_bytes / sec / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": w_bytes,
-                           "traffic": DECODE_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per layer call"}
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = _moe_cpu_baseline(hi, wl, X_h, logits_h, prefill, res["unit"])
-    return res
+    return {"s_in": s_in, "experts": experts, "host_mats": host_mats, "sets": None, "oracle": None}
 
 
-def _moe_cpu_baseline(hi, wl, X_h, logits_h, prefill, unit):
-    """The CPU oracle on a bounded sample of the MoE workload.  The oracle gets its own host
-    copy of the layer, quantised offline by the oracle itself (smoothing vectors from 256
-    calibration tokens, alpha 0.5), and runs whole tokens through routing, both expert FFNs
-    and the combination."""
+def oracle_mixtral(hi, host_mats=None):
+    """The CPU oracle's own copy of the layer, quantised offline by the oracle itself (smoothing vectors from
+    the 256 calibration tokens, alpha 0.5)."""
     import oracle
     from concurrent.futures import ThreadPoolExecutor
-    H, I, E = wl.H, wl.I, wl.E
     cal = hi.MIXTRAL_CALIB
-    names = [(e, w) for e in range(E) for w in ("w1", "w3", "w2")]
-    with ThreadPoolExecutor(8) as pool:
-        mats = list(pool.map(lambda ew: hi.moe_weight(wl, *ew), names))
+    H, I, E = cal.H, cal.I, cal.E
+    if host_mats is None:
+        names = [(e, w) for e in range(E) for w in ("w1", "w3", "w2")]
+        with ThreadPoolExecutor(8) as pool:
+            host_mats = list(pool.map(lambda ew: hi.moe_weight(cal, *ew), names))
+    mats = host_mats
     Xc = hi.moe_hidden_states(cal)
     idx_c, _ = oracle.route_top2(hi.moe_logits(cal, Xc))
     aw = np.zeros(H, np.float32)
@@ -339,19 +380,158 @@ def _moe_cpu_baseline(hi, wl, X_h, logits_h, prefill, unit):
         w2q, sw2 = oracle.quant_weight(mats[3 * e + 2], s_mid)
         st = stage1[e]
         experts.append(oracle.Expert(st.w1, st.w3, w2q, st.sw1, st.sw3, sw2, s_mid))
-    del mats, stage1
+    return {"s_in": s_in, "experts": experts}
+
+
+def _moe_workload(hi, name):
+    if name == "moe_prefill":
+        return hi.MIXTRAL_PREFILL
+    if name == "moe_offload":
+        return hi.MIXTRAL_OFFLOAD
+    return {w.T: w for w in hi.MIXTRAL_DECODE}[int(name.rsplit("b", 1)[1])]
+
+
+def bench_moe(args, torch, haq, hi, workload, layer, cpu_seconds=10.0):
+    dev = "cuda:0"
+    wl = _moe_workload(hi, workload)
+    T, H, I, E = wl.T, wl.H, wl.I, wl.E
+    s_in, experts = layer["s_in"], layer["experts"]
+    X_h = hi.moe_hidden_states(wl)
+    logits_h = hi.moe_logits(wl, X_h)
+    X, logits = torch.from_numpy(X_h).to(dev), torch.from_numpy(logits_h).to(dev)
+    ws = torch.empty(haq.haq_moe_workspace_bytes(T, H, I, E), dtype=torch.uint8, device=dev)
+    out = torch.empty((T, H), dtype=torch.float16, device=dev)
+    _, dbg = haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I, debug=("counts",))
+    counts = dbg.counts.cpu().numpy()
+    prefill = workload == "moe_prefill"
+    if workload == "moe_offload":
+        res = bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out)
+    else:
+        res = _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, counts, ws)
+    if not args.no_cpu_baseline:
+        if layer["oracle"] is None:
+            layer["oracle"] = oracle_mixtral(hi, layer["host_mats"])
+            layer["host_mats"] = None
+        res["cpu_baseline"] = _moe_cpu_baseline(layer["oracle"], wl, X_h, logits_h, prefill, workload == "moe_offload", cpu_seconds)
+    return res
+
+
+def _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, counts, ws):
+    dev = "cuda:0"
+    T, H, I, E = wl.T, wl.H, wl.I, wl.E
+    s_in, experts = layer["s_in"], layer["experts"]
+    prefill = workload == "moe_prefill"
+    # Inputs of one step.  Decode is bound by reading each activated expert's weights once, and in a
+    # model no weight is touched twice per token; here one layer is replayed, and the 256 MB last-level
+    # cache would keep part of a working set that comes round again too soon.  So a replay walks over
+    # four copies of the layer's weights at distinct addresses (5.6 GB between two reads of the same
+    # bytes), and the single-token step in addition over four tokens (drawn from the 64-token batch of
+    # the same workload family) whose expert pairs are disjoint.
+    pool = [(X, logits)]
+    if T == 1:
+        wl64 = {w.T: w for w in hi.MIXTRAL_DECODE}[64]
+        X64_h = hi.moe_hidden_states(wl64)
+        L64_h = hi.moe_logits(wl64, X64_h)
+        X64, L64 = torch.from_numpy(X64_h).to(dev), torch.from_numpy(L64_h).to(dev)
+        _, d64 = haq.haq_moe_w8a8_ffn(X64, L64, s_in, experts, I, debug=("topk_idx",))
+        pairs = d64.topk_idx.cpu().numpy()
+        chosen, used = [], set()
+        for t in range(64):
+            if not (set(pairs[t].tolist()) & used):
+                chosen.append(t)
+                used |= set(pairs[t].tolist())
+        pool = [(X64[t:t + 1].contiguous(), L64[t:t + 1].contiguous()) for t in chosen]
+    n_sets = 1 if prefill else 4
+    if n_sets > 1 and layer["sets"] is None:
+        layer["sets"] = [[haq.ExpertWeights(ex.w13.clone(), ex.w2.clone(), ex.sw1, ex.sw3, ex.sw2, ex.s_mid) for ex in experts]
+                         for _ in range(n_sets - 1)]
+    sets = [experts] + (layer["sets"] if n_sets > 1 else [])
+    calls = [(x_i, l_i, ws_i) for ws_i in sets for (x_i, l_i) in pool]
+    outs = [torch.empty((T, H), dtype=torch.float16, device=dev) for _ in calls]
+    torch.cuda.synchronize()
+    # the launch sequence of one step is captured once and replayed: the decode layer is a handful
+    # of short kernels and would otherwise be bound by host launch overhead
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for (x_i, l_i, ex_i), o_i in zip(calls, outs):
+            haq.haq_moe_w8a8_ffn(x_i, l_i, s_in, ex_i, I, out=o_i, workspace=ws)
+
+    def step():
+        graph.replay()
+
+    sec = _time_steps(torch, step, args.steps, args.warmup) / len(calls)
+    eager = haq.haq_moe_w8a8_ffn(pool[0][0], pool[0][1], s_in, experts, I)
+    torch.cuda.synchronize()
+    if not torch.equal(eager, outs[0]):
+        raise SystemExit("bench.py: graph replay and eager call disagree")
+    # stage durations from the library's own events (eager launches over the same inputs)
+    k = [0]
+
+    def eager_step():
+        x_i, l_i, ex_i = calls[k[0] % len(calls)]
+        k[0] += 1
+        haq.haq_moe_w8a8_ffn(x_i, l_i, s_in, ex_i, I, out=outs[0], workspace=ws)
+
+    stages = _stage_times(torch, haq, eager_step, max(args.steps, len(calls)))
+    pairs = int(counts.sum())
+    ops = pairs * 2.0 * 3 * H * I
+    n_active = int((counts > 0).sum())
+    w_bytes = n_active * (3.0 * H * I + 4.0 * (2 * I + H + I))
+    res = {
+        "ms_per_step": sec * 1e3, "dtype": "int8",
+        "config": {"workload": wl.name, "tokens": T, "hidden": H, "intermediate": I, "experts": E, "top_k": 2,
+                   "pairs_per_expert": counts.tolist(), "activated_experts": n_active,
+                   "launch": "hipGraph replay", "calls_per_replay": len(calls), "weight_copies": n_sets},
+        "tokens_per_s": T / sec, "layer_tops": ops / sec / 1e12, "weight_stream_GBs": w_bytes / sec / 1e9,
+        "stage_ms_eager": stages, "cpu_baseline": None,
+    }
+    if prefill:
+        res.update(metric="W8A8 expert-FFN int8 TOPS (prefill)", value=ops / sec / 1e12, unit="TOPS")
+        gu_ms = stages.get("grouped gate/up GEMM + SwiGLU")
+        dn_ms = stages.get("grouped down GEMM")
+        gu_ops, dn_ops = pairs * 2.0 * H * 2 * I, pairs * 2.0 * I * H
+        res["roofline"] = {"bound": "mfma", "kernel": "gemm_i8_kernel, grouped gate/up launch (int8 MFMA GEMM + SwiGLU epilogue)",
+                           "achieved": gu_ops / (gu_ms * 1e-3) / 1e12, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                           "frac": gu_ops / (gu_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, "avg_launch_ms": gu_ms, "ops_per_launch": gu_ops,
+                           "down_launch": {"achieved": dn_ops / (dn_ms * 1e-3) / 1e12, "frac": dn_ops / (dn_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                                           "avg_launch_ms": dn_ms, "ops_per_launch": dn_ops},
+                           "whole_layer": {"achieved": ops / sec / 1e12, "frac": ops / sec / 1e12 / PEAK_INT8_TOPS},
+                           "traffic": None}
+        res["other_kernels"] = [
+            _quant_record("requantisation of the fp16 intermediate (per-expert smoothing vectors)", pairs, I,
+                          stages.get("requantise intermediate"))]
+    else:
+        res.update(metric="MoE layer tokens/s (decode)", value=T / sec, unit="tokens/s")
+        res["roofline"] = {"bound": "hbm", "kernel": "whole layer (expert weight streaming dominates)",
+                           "achieved": w_bytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": w_bytes / sec / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": w_bytes,
+                           "traffic": DECODE_TRAFFIC_BYTES.get(workload), "traffic_unit": "bytes per layer call"}
+    return res
+
+
+def _moe_cpu_baseline(ol, wl, X_h, logits_h, prefill, offload, seconds):
+    """The CPU oracle on a bounded sample of the MoE workload: whole tokens through routing, both expert FFNs
+    and the combination (`ol`: the oracle's own copy of the layer)."""
+    import oracle
+    H, I = wl.H, wl.I
     idx, gw = oracle.route_top2(logits_h)
-    n_tok = min(wl.T, 64)
+    n_tok = min(wl.T, 32)
     tokens = np.arange(n_tok)
     reps, dt = 0, 0.0
-    while dt < 10.0 and reps < 200:  # about 10 s of CPU work
+    while dt < seconds and reps < 1000:
         t0 = time.perf_counter()
-        oracle.moe_ffn(X_h, idx, gw, s_in, experts, tokens=tokens)
+        oracle.moe_ffn(X_h, idx, gw, ol["s_in"], ol["experts"], tokens=tokens)
         dt += time.perf_counter() - t0
         reps += 1
-    value = reps * n_tok * 2 * 2.0 * 3 * H * I / dt / 1e12 if prefill else reps * n_tok / dt
+    if prefill:
+        value, unit = reps * n_tok * 2 * 2.0 * 3 * H * I / dt / 1e12, "TOPS"
+    elif offload:
+        value, unit = dt / reps * wl.T / n_tok * 1e3, "ms"   # the whole 256-token layer at the sampled rate
+    else:
+        value, unit = reps * n_tok / dt, "tokens/s"
     return {"value": value, "unit": unit, "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {n_tok} of {wl.T} tokens through the whole layer, {reps} repetitions, {dt:.2f} s"}
+            "sample": f"first {n_tok} of {wl.T} tokens through the whole layer (weights in host memory), {reps} repetitions, {dt:.2f} s"
+                      + (f"; scaled to {wl.T} tokens" if offload else "")}
 
 
 def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out):
@@ -367,13 +547,28 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
         else:
             mixed.append(ex)
     torch.cuda.synchronize()
+    steps = max(3, min(args.steps, 20))
     ctx = haq.haq_ctx_create(H, I, 2)
     ref = haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I)
     t_all_resident = _time_steps(torch, lambda: haq.haq_moe_w8a8_ffn(X, logits, s_in, experts, I, out=out, workspace=ws),
-                                 args.steps, args.warmup)
-    sec = _time_steps(torch, lambda: haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx, out=out, workspace=ws),
-                      args.steps, args.warmup)
+                                 steps, args.warmup, 0.2)
+    # one timeline per timed call from the events the call records on its two streams
+    lines = []
+
+    def streamed_call():
+        haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx, out=out, workspace=ws)
+
+    for _ in range(3):
+        streamed_call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        streamed_call()
+        lines.append(haq.haq_ctx_last_call_timing(ctx))
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
     same = bool(torch.equal(out, ref))
+    total_ms, copies_ms, tail_ms = (float(np.mean([l[i] for l in lines])) for i in range(3))
     # pinned-copy peak of this machine: the same bytes, copies only
     stage = [torch.empty_like(experts[e].w13) for e in cold[:1]] + [torch.empty_like(experts[cold[0]].w2)]
 
@@ -383,31 +578,36 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
                 stage[0].copy_(mixed[e].w13, non_blocking=True)
                 stage[1].copy_(mixed[e].w2, non_blocking=True)
 
-    t_copy = _time_steps(torch, copies, max(3, args.steps // 4), 1)
+    t_copy = _time_steps(torch, copies, max(3, steps // 4), 1, 0.1)
     torch.cuda.synchronize()
     _, misses2, _, _ = haq.haq_ctx_cache_stats(ctx)
     haq.haq_ctx_destroy(ctx)
     # the same layer with as many cache slots as cold experts: after the first call every lookup hits
     ctx4 = haq.haq_ctx_create(H, I, len(cold))
     t_cached = _time_steps(torch, lambda: haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx4, out=out, workspace=ws),
-                           args.steps, args.warmup)
+                           steps, args.warmup, 0.2)
     same_cached = bool(torch.equal(out, ref))
     hits4, misses4, _, _ = haq.haq_ctx_cache_stats(ctx4)
     haq.haq_ctx_destroy(ctx4)
     streamed = sum(float(mixed[e].w13.numel() + mixed[e].w2.numel()) for e in cold if counts[e] > 0)
+    resident_ms = t_all_resident * 1e3
     return {
         "metric": "MoE layer latency with 4 of 8 experts streamed from host (ms)", "value": sec * 1e3, "unit": "ms",
         "ms_per_step": sec * 1e3, "dtype": "int8", "higher_is_better": False,
         "config": {"workload": wl.name, "tokens": T, "hidden": H, "intermediate": I, "experts": E, "top_k": 2,
                    "resident": list(wl.resident), "staging_slots": 2, "pairs_per_expert": counts.tolist()},
         "h2d_GBs": streamed / sec / 1e9, "h2d_copy_only_GBs": streamed / t_copy / 1e9, "streamed_MB": streamed / 1e6,
-        "all_resident_ms": t_all_resident * 1e3,
-        "overlap_efficiency": min(1.0, max(0.0, (t_copy + t_all_resident - sec) / t_all_resident)),
+        "all_resident_ms": resident_ms,
+        # timeline of a call, from events on the launch stream and on the copy stream: everything the layer computes
+        # except what runs after the last copy has landed is hidden under the copies
+        "timeline_ms": {"call": total_ms, "first_copy_issued_to_last_copy_landed": copies_ms, "after_last_copy": tail_ms},
+        "overlap_efficiency": min(1.0, max(0.0, (resident_ms - tail_ms) / resident_ms)),
         "matches_all_resident_bitwise": same and same_cached,
         "lru_cache": {"slots_2": {"misses": misses2, "ms": sec * 1e3},
                       f"slots_{len(cold)}": {"hits": hits4, "misses": misses4, "ms": t_cached * 1e3}},
         "roofline": {"bound": "host link", "kernel": "hipMemcpyAsync pinned host to HBM", "achieved": streamed / sec / 1e9,
-                     "peak": streamed / t_copy / 1e9, "unit": "GB/s", "frac": min(1.0, t_copy / sec), "traffic": None,
+                     "peak": streamed / t_copy / 1e9, "unit": "GB/s", "frac": min(1.0, t_copy / sec), "traffic": streamed,
+                     "traffic_unit": "bytes per layer call over the host link (algorithmic = counted: whole experts are copied)",
                      "note": "peak = the same bytes as back-to-back pinned copies on this box, measured in this run"},
         "cpu_baseline": None,
     }
@@ -508,15 +708,29 @@ def bench_hessian(args, torch, haq, hi):
     }
 
 
+def _record(res, args):
+    line = {"metric": res.pop("metric"), "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"),
+            "higher_is_better": res.pop("higher_is_better", True), "scaling": "weak", "vs_baseline": None,
+            "dtype": res.pop("dtype"),
+            "data": "synthetic"}
+    line.update(res)
+    return line
+
+
+MOE_WORKLOADS = ["moe_prefill", "moe_decode_b1", "moe_decode_b8", "moe_decode_b64", "moe_offload"]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="ffn",
-                    choices=["ffn", "linear", "moe_prefill", "moe_decode_b1", "moe_decode_b8", "moe_decode_b64",
-                             "moe_offload", "smooth_search", "hessian_quant"])
+    ap.add_argument("--workload", default="all",
+                    choices=["all", "ffn", "linear", *MOE_WORKLOADS, "smooth_search", "hessian_quant"],
+                    help="all (default): the OPT-6.7B FFN block as the headline plus one record per other configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-clock peak and the pure-MFMA ceiling (2.5 s)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MB (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=2048, help="token rows of the workload the CPU oracle is timed on")
@@ -539,20 +753,27 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if args.workload in ("ffn", "linear"):
+    everything = args.workload == "all"
+    if args.workload in ("all", "ffn", "linear"):
         res = bench_ffn(args, torch, haq, hi)
     elif args.workload == "smooth_search":
         res = bench_search(args, torch, haq, hi)
     elif args.workload == "hessian_quant":
         res = bench_hessian(args, torch, haq, hi)
     else:
-        res = bench_moe(args, torch, haq, hi)
-    line = {"metric": res.pop("metric"), "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"),
-            "higher_is_better": res.pop("higher_is_better", True), "scaling": "weak", "vs_baseline": None,
-            "dtype": res.pop("dtype"),
-            "data": "synthetic"}
-    line.update(res)
+        res = bench_moe(args, torch, haq, hi, args.workload, build_mixtral(torch, haq, hi, keep_host=not args.no_cpu_baseline))
+    line = _record(res, args)
+    if everything:
+        # the other configurations of the metric, each with a short CPU-oracle baseline of its own
+        t0 = time.perf_counter()
+        args.workload = "linear"
+        configs = [_record(bench_ffn(args, torch, haq, hi, cpu_seconds=2.0), args)]
+        torch.cuda.empty_cache()
+        layer = build_mixtral(torch, haq, hi, keep_host=not args.no_cpu_baseline)
+        for w in MOE_WORKLOADS:
+            configs.append(_record(bench_moe(args, torch, haq, hi, w, layer, cpu_seconds=2.5), args))
+            print(f"bench.py: {w} done at {time.perf_counter() - t0:.0f} s", file=sys.stderr, flush=True)
+        line["configs"] = configs
     print(json.dumps(line))
 
 

@@ -316,6 +316,12 @@ int32_t haq_ctx_destroy(haq_ctx* ctx);
 int32_t haq_ctx_cache_stats(const haq_ctx* ctx, int64_t* hits, int64_t* misses, int64_t* bytes_copied,
                             const void** slot_keys);
 int32_t haq_ctx_cache_invalidate(haq_ctx* ctx);
+/* Timeline of the context's last call that had host-resident experts, from events the call
+ * records on its two streams (waits for that call): *total_ms from its first launch to the end
+ * of the combination; *copies_ms from the first expert copy being issued to the last one having
+ * landed (0 when every activated expert was cached); *after_last_copy_ms from there to the end
+ * of the call, i.e. the part of the call that no copy overlaps (= *total_ms without copies).   */
+int32_t haq_ctx_last_call_timing(haq_ctx* ctx, float* total_ms, float* copies_ms, float* after_last_copy_ms);
 
 /* ------------------------------------------------------------------------
  * Host-side planning of the offload runtime (no device work).
@@ -372,6 +378,36 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
                          const float* s_in, const haq_expert_desc* experts_host, int32_t T, int32_t H, int32_t I,
                          int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug* dbg_host,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Measurement aids (no part of the method; used by the benchmark).
+ *
+ * haq_profile_enable(1) creates events (allocates; call it outside timed regions
+ * and graph capture); from then on haq_w8a8_ffn and haq_moe_w8a8_ffn (all experts
+ * resident) record one at every stage boundary of each call.  haq_profile_read
+ * waits for the last profiled call and returns the stage names (host strings owned
+ * by the library) and durations in milliseconds, at most max_stages of them.  The
+ * state is process wide and not thread safe; haq_profile_enable(0) frees it.
+ *
+ * haq_probe_mfma_i8: a launch of `work_groups` work-groups of four waves that
+ * issue nothing but v_mfma_i32_32x32x32_i8 on operands held in registers: every
+ * wave reads 4 operand sets of 6 fragments (2 token, 4 weight fragments, the
+ * register tile of the GEMM kernel; lane l of fragment f of set s = the 16 bytes
+ * at data[((s * 6 + f) * 64 + l) * 16], 24 KiB in all) and accumulates
+ * acc[i][j] += W(s, j) . X(s, i) over the sets, `iters` times: 2 * 32^3 * 32 *
+ * iters operations per wave.  What a GPU sustains on this loop for operands with
+ * the statistics of a workload is the ceiling a GEMM on such operands can reach.
+ * out: int32 [256 * 128] device, the accumulators of work-group 0 (thread t,
+ * tile (i, j), register r at ((t * 8 + i * 4 + j) * 16 + r), int32 wrap-around).
+ *
+ * haq_probe_clock: one wave spins for ticks_100mhz periods of the constant 100 MHz
+ * counter; out[0] = shader clock cycles elapsed, out[1] = 100 MHz periods elapsed
+ * (uint64, device).  Launched on a second stream it reads the shader clock while
+ * the kernels of another stream run.                                          */
+int32_t haq_profile_enable(int32_t on);
+int32_t haq_profile_read(int32_t max_stages, int32_t* n_stages, const char** names, float* ms);
+int32_t haq_probe_mfma_i8(const int8_t* data, int32_t iters, int32_t work_groups, int32_t* out, void* stream);
+int32_t haq_probe_clock(uint64_t* out, int64_t ticks_100mhz, void* stream);
 
 /* ------------------------------------------------------------------------
  * haq_moe_w8a8_ffn for callers that cannot allocate device memory and have no

@@ -22,7 +22,7 @@ __all__ = [
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
-    "haq_moe_w8a8_ffn_static",
+    "haq_moe_w8a8_ffn_static", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -44,7 +44,7 @@ EXPORTED_SYMBOLS = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
-    "haq_moe_w8a8_ffn_static",
+    "haq_moe_w8a8_ffn_static", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -336,6 +336,38 @@ def haq_moe_w8a8_ffn_static(x, logits, s_in, experts, I: int, *, out):
     return out
 
 
+# ---- measurement aids ------------------------------------------------------------------------
+def haq_profile_enable(on: bool):
+    _check(lib().haq_profile_enable(int(bool(on))))
+
+
+def haq_profile_read():
+    """[(stage name, milliseconds), ...] of the last profiled block-level call (waits for it)."""
+    n = C.c_int32(0)
+    names = (C.c_char_p * 16)()
+    ms = (C.c_float * 16)()
+    _check(lib().haq_profile_read(16, C.byref(n), names, ms))
+    return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def haq_probe_mfma_i8(data, iters: int, work_groups: int, *, out=None):
+    """data int8 [>= 24576] device.  Returns the int32 [256, 8, 16] accumulators of work-group 0."""
+    assert data.numel() >= 24576
+    if out is None:
+        out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)
+    _check(lib().haq_probe_mfma_i8(_ptr(data), iters, work_groups, _ptr(out), _stream()))
+    return out
+
+
+def haq_probe_clock(ticks_100mhz: int, *, out=None, stream=None):
+    """Enqueues the clock probe (on `stream`, default: the current one); out[0] / out[1] * 100 = MHz once it has run."""
+    if out is None:
+        out = torch.zeros((2,), dtype=torch.int64, device="cuda")
+    st = C.c_void_p(stream.cuda_stream) if stream is not None else _stream()
+    _check(lib().haq_probe_clock(_ptr(out), C.c_int64(ticks_100mhz), st))
+    return out
+
+
 # ---- adaptive smoothing (Algorithm 1 step 1) --------------------------------------------
 def haq_smoothing_search_workspace_bytes(T: int, K: int, N: int, n_e: int) -> int:
     return int(lib().haq_smoothing_search_workspace_bytes(T, K, N, n_e))
@@ -383,6 +415,13 @@ def haq_ctx_cache_stats(ctx):
     keys = (C.c_void_p * 32)()
     _check(lib().haq_ctx_cache_stats(ctx, C.byref(h), C.byref(m), C.byref(b), keys))
     return int(h.value), int(m.value), int(b.value), list(keys)
+
+
+def haq_ctx_last_call_timing(ctx):
+    """(total ms, ms from first copy issued to last copy landed, ms after the last copy) of the last offload call."""
+    a, b, c = C.c_float(0), C.c_float(0), C.c_float(0)
+    _check(lib().haq_ctx_last_call_timing(ctx, C.byref(a), C.byref(b), C.byref(c)))
+    return float(a.value), float(b.value), float(c.value)
 
 
 def haq_ctx_cache_invalidate(ctx):

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhaq.so")
-SOURCES = ["api.hip", "quant.hip", "gemm.hip", "moe.hip", "decode.hip", "search.hip", "sched.hip", "hessian.hip"]
+SOURCES = ["api.hip", "quant.hip", "gemm.hip", "moe.hip", "decode.hip", "search.hip", "sched.hip", "hessian.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -172,6 +172,29 @@ static int static_scratch_address(void** out) {
     return HAQ_OK;
 }
 
+// Stage timing (haq_profile_*): events recorded at the stage boundaries of the block-level calls.
+namespace {
+constexpr int PROF_MAX = 16;
+struct Profile {
+    bool on = false;
+    hipEvent_t ev[PROF_MAX + 1] = {};
+    const char* name[PROF_MAX] = {};
+    int n = -1;  // stages recorded by the last profiled call; -1: none yet
+} g_prof;
+inline void prof_begin(hipStream_t st) {
+    if (!g_prof.on) return;
+    g_prof.n = hipEventRecord(g_prof.ev[0], st) == hipSuccess ? 0 : -1;
+}
+inline void prof_mark(hipStream_t st, const char* name) {  // the stage `name` ends here
+    if (!g_prof.on || g_prof.n < 0 || g_prof.n >= PROF_MAX) return;
+    if (hipEventRecord(g_prof.ev[g_prof.n + 1], st) != hipSuccess) {
+        g_prof.n = -1;
+        return;
+    }
+    g_prof.name[g_prof.n++] = name;
+}
+}  // namespace
+
 // Context of layers with host-resident experts: staging slots in HBM, the copy stream and the
 // events that order copies against the GEMMs that read (and later overwrite) a slot.
 struct haq_ctx {
@@ -181,6 +204,10 @@ struct haq_ctx {
     int8_t* slot[32] = {};
     hipEvent_t copied[32] = {}, done[32] = {};
     hipEvent_t routed = nullptr, call_done = nullptr;
+    // timeline of the last call with host-resident experts (timing events): start of the call, first copy
+    // issued, last copy landed, end of the call
+    hipEvent_t t_start = nullptr, t_copy0 = nullptr, t_copy1 = nullptr, t_end = nullptr;
+    bool timed = false, timed_copies = false;
     bool used = false;
     int32_t* counts_host = nullptr;  // pinned
     // the slots double as an expert cache with least-recently-used replacement: which host
@@ -318,11 +345,17 @@ int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int
     hipStream_t st = (hipStream_t)stream;
     const FfnWs w = carve_ffn(workspace, T, K, F);
     __half* h = h_dbg_fp16 ? (__half*)h_dbg_fp16 : w.h;
+    prof_begin(st);
     int rc = quant_packed(x_fp16, ldx, s1, T, K, w.q1, w.sx1, nullptr, st);
     if (rc != HAQ_OK) return rc;
+    prof_mark(st, "quantise X");
     if ((rc = gemm_packed(w.q1, w.sx1, w1_packed, w1_scale, T, K, F, act, h, F, nullptr, st)) != HAQ_OK) return rc;
+    prof_mark(st, "GEMM 1 + activation");
     if ((rc = quant_packed(h, F, s2, T, F, w.q2, w.sx2, nullptr, st)) != HAQ_OK) return rc;
-    return gemm_packed(w.q2, w.sx2, w2_packed, w2_scale, T, F, N, HAQ_ACT_NONE, y_fp16, ldy, nullptr, st);
+    prof_mark(st, "requantise H");
+    rc = gemm_packed(w.q2, w.sx2, w2_packed, w2_scale, T, F, N, HAQ_ACT_NONE, y_fp16, ldy, nullptr, st);
+    prof_mark(st, "GEMM 2");
+    return rc;
 }
 
 int64_t haq_packed_act_rows(int32_t T) { return T < 0 ? 0 : padded_rows(T); }
@@ -372,6 +405,8 @@ int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out) {
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->routed, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->call_done, hipEventDisableTiming);
+    for (hipEvent_t* t : {&c->t_start, &c->t_copy0, &c->t_copy1, &c->t_end})
+        if (e == hipSuccess) e = hipEventCreate(t);
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->counts_host, 32 * sizeof(int32_t), hipHostMallocDefault);
     if (e != hipSuccess) {
         set_error("haq_ctx_create: %s", hipGetErrorString(e));
@@ -392,6 +427,8 @@ int32_t haq_ctx_destroy(haq_ctx* c) {
     }
     if (c->routed) (void)hipEventDestroy(c->routed);
     if (c->call_done) (void)hipEventDestroy(c->call_done);
+    for (hipEvent_t t : {c->t_start, c->t_copy0, c->t_copy1, c->t_end})
+        if (t) (void)hipEventDestroy(t);
     if (c->counts_host) (void)hipHostFree(c->counts_host);
     if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     delete c;
@@ -477,6 +514,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     float* sh = d.sh ? d.sh : w.sh;
 
     int rc;
+    prof_begin(st);
     const bool decode_path = n_host == 0 && decode_supported(T, H, I);
     // one or two tokens, and none of the intermediate outputs the fused kernels keep on chip is asked for
     const bool tiny_path = decode_path && decode_tiny_supported(T, H, I) && !d.q && !d.sx && !d.hq && !d.sh;
@@ -507,6 +545,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     qa.scale_dest = w.sx_sorted;
     if ((rc = launch_quant(qa, st)) != HAQ_OK) return rc;
     }
+    if (!tiny_path) prof_mark(st, "route + permute + quantise tokens");
 
     if (decode_path) {
         // few rows per expert: stream every activated expert's weights once
@@ -533,7 +572,10 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         else
             rc = launch_decode(da, T, st);
         if (rc != HAQ_OK) return rc;
-        return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+        prof_mark(st, tiny_path ? "route + quantise + gate/up + requantise + down (2 launches)" : "gate/up + requantise + down (3 launches)");
+        rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+        prof_mark(st, "combine");
+        return rc;
     }
 
     // gate/up GEMM + SwiGLU, requantisation and down GEMM for a set of experts (rows of the others untouched)
@@ -555,6 +597,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         g1.ldy = I;
         int r = launch_gemm(g1, EPI_SWIGLU, st);
         if (r != HAQ_OK) return r;
+        if (n_host == 0) prof_mark(st, "grouped gate/up GEMM + SwiGLU");
 
         QuantArgs qb{};
         qb.x = mid;
@@ -573,6 +616,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         for (int i = 0; i < n_sel; ++i) qb.sel[i] = sel[i];
         qb.max_rows = max_rows;
         if ((r = launch_quant(qb, st)) != HAQ_OK) return r;
+        if (n_host == 0) prof_mark(st, "requantise intermediate");
 
         GemmArgs g2{};
         g2.A = w.hq_cm;
@@ -597,7 +641,10 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         int all[32];
         for (int e = 0; e < E; ++e) all[e] = e;
         if ((rc = run_experts(all, E, P)) != HAQ_OK) return rc;
-        return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+        prof_mark(st, "grouped down GEMM");
+        rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+        prof_mark(st, "combine");
+        return rc;
     }
 
     // ---- some experts live in pinned host memory (Section III.C: experts are moved in their
@@ -605,6 +652,8 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     // activated host experts are copied into the staging slots on the copy stream, and the
     // device-resident experts compute meanwhile; each streamed expert computes as soon as its
     // copy has landed and frees its slot for the expert n_slots further down the list.
+    ctx->timed = false;
+    HAQ_CHECK_HIP(hipEventRecord(ctx->t_start, st));
     HAQ_CHECK_HIP(hipMemcpyAsync(ctx->counts_host, counts, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     HAQ_CHECK_HIP(hipEventRecord(ctx->routed, st));
     HAQ_CHECK_HIP(hipEventSynchronize(ctx->routed));
@@ -661,6 +710,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
             HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->call_done, 0));
         }
         if ((r = launch_set_tab(tab, E, w.tab, st)) != HAQ_OK) return r;
+        HAQ_CHECK_HIP(hipEventRecord(ctx->t_copy0, ctx->copy_stream));
         // misses whose slot is not in use by an earlier expert of this call are copied right away
         for (int k = 0; k < n_order; ++k)
             if (!hit[k] && prev_user[k] < 0 && (r = issue_copy(k)) != HAQ_OK) return r;
@@ -694,7 +744,9 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
                 break;
             }
         }
+        HAQ_CHECK_HIP(hipEventRecord(ctx->t_copy1, ctx->copy_stream));
         if ((r = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st)) != HAQ_OK) return r;
+        HAQ_CHECK_HIP(hipEventRecord(ctx->t_end, st));
         HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
         return HAQ_OK;
     };
@@ -719,6 +771,23 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     ctx->misses += n_order - n_hit;
     ctx->bytes_copied += (int64_t)(n_order - n_hit) * (int64_t)(ctx->w13_bytes + ctx->w2_bytes);
     ctx->used = true;
+    ctx->timed = true;
+    ctx->timed_copies = n_order - n_hit > 0;
+    return HAQ_OK;
+}
+
+int32_t haq_ctx_last_call_timing(haq_ctx* c, float* total_ms, float* copies_ms, float* after_last_copy_ms) {
+    if (!c || !total_ms || !copies_ms || !after_last_copy_ms) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_last_call_timing: null argument");
+    if (!c->timed) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_last_call_timing: no completed call with host-resident experts on this context");
+    HAQ_CHECK_HIP(hipEventSynchronize(c->t_end));
+    HAQ_CHECK_HIP(hipEventSynchronize(c->t_copy1));
+    HAQ_CHECK_HIP(hipEventElapsedTime(total_ms, c->t_start, c->t_end));
+    *copies_ms = 0.0f;
+    *after_last_copy_ms = *total_ms;
+    if (c->timed_copies) {
+        HAQ_CHECK_HIP(hipEventElapsedTime(copies_ms, c->t_copy0, c->t_copy1));
+        HAQ_CHECK_HIP(hipEventElapsedTime(after_last_copy_ms, c->t_copy1, c->t_end));
+    }
     return HAQ_OK;
 }
 
@@ -742,6 +811,34 @@ int32_t haq_moe_w8a8_ffn_static(const void* x_fp16, int64_t ldx, const void* log
     // every buffer carved from the scratch is written before it is read within the call: nothing has to be cleared
     return haq_moe_w8a8_ffn(nullptr, x_fp16, ldx, logits_fp16, ldl, s_in, experts, T, H, I, E, top_k, out_fp16, ldo, nullptr, ws,
                             HAQ_STATIC_SCRATCH_BYTES, stream);
+}
+
+int32_t haq_profile_enable(int32_t on) {
+    if (on && !g_prof.on) {
+        for (int i = 0; i <= PROF_MAX; ++i) HAQ_CHECK_HIP(hipEventCreate(&g_prof.ev[i]));
+        g_prof.on = true;
+        g_prof.n = -1;
+    } else if (!on && g_prof.on) {
+        g_prof.on = false;
+        for (int i = 0; i <= PROF_MAX; ++i) {
+            if (g_prof.ev[i]) (void)hipEventDestroy(g_prof.ev[i]);
+            g_prof.ev[i] = nullptr;
+        }
+    }
+    return HAQ_OK;
+}
+
+int32_t haq_profile_read(int32_t max_stages, int32_t* n_stages, const char** names, float* ms) {
+    if (!n_stages || max_stages < 0 || (max_stages > 0 && (!names || !ms))) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_profile_read: null buffer");
+    if (!g_prof.on || g_prof.n < 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_profile_read: no profiled call (haq_profile_enable(1), then a block-level call)");
+    const int n = g_prof.n < max_stages ? g_prof.n : max_stages;
+    HAQ_CHECK_HIP(hipEventSynchronize(g_prof.ev[g_prof.n]));
+    for (int i = 0; i < n; ++i) {
+        names[i] = g_prof.name[i];
+        HAQ_CHECK_HIP(hipEventElapsedTime(&ms[i], g_prof.ev[i], g_prof.ev[i + 1]));
+    }
+    *n_stages = n;
+    return HAQ_OK;
 }
 
 int32_t haq_lru_plan(int32_t n_slots, uint64_t* slot_keys, uint64_t* slot_ticks, uint64_t* tick, const uint64_t* keys,

@@ -628,3 +628,43 @@ def test_quantize_layer_matches_oracle_composition(name):
     # and the layer it produces runs on the hot path as the oracle's does
     y = haq.haq_w8a8_linear(dev(X), s, haq.haq_pack_weight(wq), sw, W.shape[1])
     assert bits_equal(host(y), oracle.w8a8_linear(X, s_ref, Wq_ref, sw_ref))
+
+
+# ------------------------------------------------------------------ measurement aids
+def test_mfma_probe_computes_the_stated_dot_products():
+    """The pure-MFMA loop behind the benchmark's sustained ceiling is a correct computation: its accumulators
+    equal the int8 dot products of the operand fragments it was given, times the iteration count."""
+    rng = np.random.default_rng(5)
+    data = rng.integers(-127, 128, 24576).astype(np.int8)
+    iters = 3
+    out = host(haq.haq_probe_mfma_i8(dev(data), iters, 3))          # [256 threads, 8 tiles, 16 registers]
+    frag = data.reshape(4, 6, 64, 16).astype(np.int64)
+    rows = np.concatenate([frag[:, :, :32, :], frag[:, :, 32:, :]], axis=3)   # [set, fragment, row 32, k 32]
+    X, W = rows[:, :2], rows[:, 2:]
+    prod = np.einsum("sjwk,sixk->ijwx", W, X) * iters                # [i, j, weight row, token row]
+    ref = np.empty((256, 8, 16), np.int64)
+    for t in range(256):
+        l = t % 64
+        for r in range(16):
+            wrow = 8 * (r // 4) + 4 * (l // 32) + r % 4
+            ref[t, :, r] = prod[:, :, wrow, l % 32].reshape(8)
+    assert np.array_equal(out.astype(np.int64), ref)
+
+
+def test_stage_profile_and_clock_probe_report():
+    m = offline.small_moe(seed=33, T=300, H=128, I=320, E=8)
+    experts = upload_experts(m["experts"])
+    haq.haq_profile_enable(True)
+    try:
+        haq.haq_moe_w8a8_ffn(dev(m["X"]), dev(m["logits"]), dev(m["s_in"]), experts, 320)
+        stages = haq.haq_profile_read()
+    finally:
+        haq.haq_profile_enable(False)
+    names = [n for n, _ in stages]
+    assert names == ["route + permute + quantise tokens", "grouped gate/up GEMM + SwiGLU", "requantise intermediate",
+                     "grouped down GEMM", "combine"]
+    assert all(0.0 < ms < 50.0 for _, ms in stages)
+    clk = haq.haq_probe_clock(20000)
+    torch.cuda.synchronize()
+    cycles, ticks = (int(v) for v in clk.tolist())
+    assert ticks >= 20000 and 100.0 < cycles / ticks * 100.0 < 3000.0     # MHz
