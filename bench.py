@@ -127,13 +127,17 @@ def _mfma_ceiling(torch, haq, data, work_groups, seconds):
     n = max(3, int(seconds / max(time.perf_counter() - t0, 1e-4)))
     for _ in range(max(1, n // 3)):  # settle
         launch()
+    side = torch.cuda.Stream()
+    clk = torch.zeros((2,), dtype=torch.int64, device=data.device)
     ev[0].record()
     for _ in range(n):
         launch()
     ev[1].record()
+    haq.haq_probe_clock(1000000, out=clk, stream=side)  # 10 ms of the loop's steady state, from a second stream
     torch.cuda.synchronize()
     sec = ev[0].elapsed_time(ev[1]) * 1e-3
-    return n * work_groups * 4.0 * iters * 32 * 65536 / sec / 1e12, sec
+    c, w = (int(v) for v in clk.tolist())
+    return n * work_groups * 4.0 * iters * 32 * 65536 / sec / 1e12, sec, c / max(w, 1) * 100.0
 
 
 def _fragment_sets(torch, q_packed, R, w_packed, Npad):
@@ -263,8 +267,8 @@ def bench_ffn(args, torch, haq, hi, cpu_seconds=10.0):
         ceil = {}
         for label, data in (("workload_codes", data_wl), ("uniform_random_codes", data_rnd)):
             for wgs, tag in ((256, "1_wave_per_simd"), (512, "2_waves_per_simd")):
-                v, dur = _mfma_ceiling(torch, haq, data, wgs, 0.5)
-                ceil[f"{label}/{tag}"] = {"TOPs": v, "seconds": dur}
+                v, dur, clk = _mfma_ceiling(torch, haq, data, wgs, 0.5)
+                ceil[f"{label}/{tag}"] = {"TOPs": v, "seconds": dur, "clock_mhz": clk}
         best = max(v["TOPs"] for k, v in ceil.items() if k.startswith("workload_codes"))
         roof["sustained_mfma_ceiling"] = ceil
         roof["peak_sustained"] = best

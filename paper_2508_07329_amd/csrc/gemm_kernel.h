@@ -219,13 +219,34 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
             for (int i = 0; i < MI; ++i)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xb[j], xa[i], acc[i][j], 0, 0, 0);
     };
-    auto interleave = [&]() {  // one LDS read behind each of the first MFMAs of the group
+#ifndef HAQ_ILV
+#define HAQ_ILV 0
+#endif
+    auto interleave = [&]() {
+#if HAQ_ILV == 0
+        // one LDS read behind each of the first MFMAs of the group
 #pragma unroll
         for (int i = 0; i < MI + NI; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
+#elif HAQ_ILV == 1
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - 1, 0);
+#elif HAQ_ILV == 2
+        __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI, 0);
+#elif HAQ_ILV == 3
+        // two reads behind each of the first MFMAs
+#pragma unroll
+        for (int i = 0; i < (MI + NI) / 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI) / 2, 0);
+#endif
     };
 
     // prologue: request every ring buffer (K-steps 0..STAGES-1); K-step 0 landed -> its fragments
