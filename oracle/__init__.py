@@ -404,3 +404,101 @@ def w8a8_linear_asym(X, s, Wq, sw, act="none", full=False):
     acc = asym_gemm(q, zp, Wq)
     Y = epilogue(acc, sx, sw, act)
     return (Y, acc, q, sx, zp) if full else Y
+
+
+def moe_ffn_asym(X, idx, gw, s_in, experts: list[Expert], tokens=None, dumps=False):
+    """The routed expert FFN with asymmetric activation codes for the tokens and for the requantised
+    intermediate.  With dumps: (out, mid fp16, hq uint8, sh, zh int32, y fp16), pair rows ordered by
+    (token position in `tokens`, slot)."""
+    X = _c(X, np.float16)
+    T, H = X.shape
+    I = experts[0].w1.shape[1]
+    idx = _c(idx, np.int32)
+    gw = _c(gw, np.float32)
+    tok = None if tokens is None else _c(tokens, np.int32)
+    n_tok = T if tok is None else tok.size
+    out = np.empty((n_tok, H), np.float16)
+    mid = hq = sh = zh = y = None
+    if dumps:
+        mid = np.empty((2 * n_tok, I), np.float16)
+        hq = np.empty((2 * n_tok, I), np.uint8)
+        sh = np.empty(2 * n_tok, np.float32)
+        zh = np.empty(2 * n_tok, np.int32)
+        y = np.empty((2 * n_tok, H), np.float16)
+    arr = _expert_array(experts)
+    lib().oracle_moe_ffn_asym(_p(X), C.c_int64(H), _p(idx), _p(gw), _p(_c(s_in, np.float32)), arr, T, H, I,
+                              _p(tok), n_tok, _p(out), _p(mid), _p(hq), _p(sh), _p(zh), _p(y))
+    return (out, mid, hq, sh, zh, y) if dumps else out
+
+
+# ---- the CPU side of the heterogeneous deployment (Section III.B.3, III.C.1a) ------------------
+def dequant_weight(Wq: np.ndarray, sw: np.ndarray) -> np.ndarray:
+    """The floating-point copy the CPU caches at load time: float(code) * scale, binary32."""
+    Wq = _c(Wq, np.int8)
+    K, N = Wq.shape
+    Wf = np.empty((K, N), np.float32)
+    lib().oracle_dequant_weight(_p(Wq), _p(_c(sw, np.float32)), K, N, _p(Wf))
+    return Wf
+
+
+def fp_linear(X: np.ndarray, s: np.ndarray | None, Wf: np.ndarray) -> np.ndarray:
+    """(X / s) Wf in binary32: one accumulator per output, k ascending, fused multiply-adds."""
+    X = _c(X, np.float32)
+    Wf = _c(Wf, np.float32)
+    T, K = X.shape
+    N = Wf.shape[1]
+    Y = np.empty((T, N), np.float32)
+    s_ = None if s is None else _c(s, np.float32)
+    lib().oracle_fp_linear(_p(X), C.c_int64(K), _p(s_), _p(Wf), T, K, N, _p(Y))
+    return Y
+
+
+@dataclass
+class CpuExpert:
+    """An expert's floating-point copy on the CPU: W1f, W3f [H,I], W2f [I,H] binary32, and s_mid."""
+    w1f: np.ndarray
+    w3f: np.ndarray
+    w2f: np.ndarray
+    s_mid: np.ndarray
+
+
+def cpu_expert(ex: Expert) -> CpuExpert:
+    return CpuExpert(dequant_weight(ex.w1, ex.sw1), dequant_weight(ex.w3, ex.sw3), dequant_weight(ex.w2, ex.sw2), ex.s_mid)
+
+
+def cpu_expert_ffn(X: np.ndarray, s_in, ce: CpuExpert, dumps=False):
+    """One SwiGLU expert in floating point on its CPU copy: rows of X (fp16) -> y fp16 [rows, H]."""
+    X = _c(X, np.float16)
+    n, H = X.shape
+    I = ce.w1f.shape[1]
+    Y = np.empty((n, H), np.float16)
+    mid = np.empty((n, I), np.float16) if dumps else None
+    lib().oracle_cpu_expert_ffn(_p(X), C.c_int64(H), _p(_c(s_in, np.float32)), _p(_c(ce.w1f, np.float32)),
+                                _p(_c(ce.w3f, np.float32)), _p(_c(ce.w2f, np.float32)), _p(_c(ce.s_mid, np.float32)),
+                                n, H, I, _p(Y), C.c_int64(H), _p(mid))
+    return (Y, mid) if dumps else Y
+
+
+def combine(y: np.ndarray, gw: np.ndarray) -> np.ndarray:
+    """out[t] = fp16(g0 y[2t] + g1 y[2t+1]) (y in pair order)."""
+    y = _c(y, np.float16)
+    P, H = y.shape
+    out = np.empty((P // 2, H), np.float16)
+    lib().oracle_combine(_p(y), _p(_c(gw, np.float32)), P // 2, H, _p(out))
+    return out
+
+
+def moe_ffn_hybrid(X, idx, gw, s_in, experts: list[Expert], on_cpu):
+    """The routed expert FFN when the experts in `on_cpu` are computed on the CPU (option A of the
+    cost-benefit analysis: floating point on the dequantised copy) and the others by the W8A8 path;
+    the per-pair outputs are combined as always.  Returns (out, y per pair)."""
+    T = X.shape[0]
+    idx = _c(idx, np.int32)
+    _, _, _, _, y = moe_ffn(X, idx, gw, s_in, experts, dumps=True)
+    y = y.copy()
+    flat = idx.ravel()
+    for e in sorted(set(int(v) for v in on_cpu)):
+        rows = np.nonzero(flat == e)[0]
+        if rows.size:
+            y[rows] = cpu_expert_ffn(X[rows // 2], s_in, cpu_expert(experts[e]))
+    return combine(y, gw), y

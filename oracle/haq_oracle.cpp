@@ -591,4 +591,167 @@ void oracle_asym_gemm(const uint8_t* q, int64_t ldq, const int32_t* zp, const in
     }
 }
 
+
+// ---- asymmetric activation codes inside the routed expert FFN ---------------------------------
+// One row of the asymmetric quantiser above (same arithmetic), on binary32 inputs.
+static void asym_quant_row(const float* xrow, const float* s, int K, uint8_t* q, float* scale_out, int32_t* zp_out,
+                           std::vector<float>& y) {
+    float mn = 0.0f, mx = 0.0f;
+    for (int k = 0; k < K; ++k) {
+        y[k] = s ? xrow[k] / s[k] : xrow[k];
+        mn = std::fmin(mn, y[k]);
+        mx = std::fmax(mx, y[k]);
+    }
+    const float range = mx - mn;
+    if (range == 0.0f) {
+        *scale_out = 0.0f;
+        *zp_out = 0;
+        for (int k = 0; k < K; ++k) q[k] = 0;
+        return;
+    }
+    const float sc = range / 255.0f;
+    float z = std::rint(-mn / sc);
+    z = std::fmin(std::fmax(z, 0.0f), 255.0f);
+    *scale_out = sc;
+    *zp_out = (int32_t)z;
+    for (int k = 0; k < K; ++k) {
+        float c = std::rint(y[k] / sc) + z;
+        c = std::fmin(std::fmax(c, 0.0f), 255.0f);
+        q[k] = (uint8_t)c;
+    }
+}
+
+// acc[n] = sum_k (q[k] - zp) * Wq[k][n] for one row.
+static void asym_row_gemm(const uint8_t* q, int32_t zp, const int8_t* Wq, int K, int N, int32_t* acc) {
+    for (int n = 0; n < N; ++n) acc[n] = 0;
+    for (int k = 0; k < K; ++k) {
+        const int32_t a = (int32_t)q[k] - zp;
+        const int8_t* w = Wq + (size_t)k * N;
+        for (int n = 0; n < N; ++n) acc[n] += a * (int32_t)w[n];
+    }
+}
+
+// The routed expert FFN of oracle_moe_ffn with asymmetric activation codes (Section IV.A names
+// asymmetric quantisation as the default of the experiments): the token is quantised once with
+// s_in to (q, scale, zero point); per selected expert the gate/up accumulators are sums of
+// (q - zp) * w, h = fp16(silu(g) * u) as before, h is requantised asymmetrically with the
+// expert's s_mid, the down accumulator is the sum of (hq - zh) * w2, and everything after the
+// accumulators (dequantisation with the outer-dimension scales, fp16 rounding, combination) is
+// unchanged.  Weights stay symmetric per output channel.  Dumps as in oracle_moe_ffn, plus the
+// zero points of the requantised intermediate.
+void oracle_moe_ffn_asym(const uint16_t* X, int64_t ldx, const int32_t* idx, const float* gw, const float* s_in,
+                         const OracleExpert* experts, int T, int H, int I, const int32_t* tokens, int n_tok,
+                         uint16_t* out, uint16_t* mid_dump, uint8_t* hq_dump, float* sh_dump, int32_t* zh_dump,
+                         uint16_t* y_dump) {
+    (void)T;
+#pragma omp parallel
+    {
+        std::vector<float> xr(H), ybuf(std::max(H, I)), hrow(I);
+        std::vector<uint8_t> q(H), hq(I);
+        std::vector<int32_t> a1(I), a3(I), a2(H);
+        std::vector<uint16_t> yh(2 * (size_t)H);
+#pragma omp for schedule(dynamic, 1)
+        for (int i = 0; i < n_tok; ++i) {
+            const int t = tokens ? tokens[i] : i;
+            for (int k = 0; k < H; ++k) xr[k] = half_to_float(X[(size_t)t * ldx + k]);
+            float sx;
+            int32_t zx;
+            asym_quant_row(xr.data(), s_in, H, q.data(), &sx, &zx, ybuf);
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const OracleExpert& ex = experts[idx[2 * t + k2]];
+                asym_row_gemm(q.data(), zx, ex.w1, H, I, a1.data());
+                asym_row_gemm(q.data(), zx, ex.w3, H, I, a3.data());
+                for (int j = 0; j < I; ++j) {
+                    const float g = dequant(a1[j], sx, ex.sw1[j]);
+                    const float u = dequant(a3[j], sx, ex.sw3[j]);
+                    const uint16_t hh = float_to_half(silu(g) * u);
+                    if (mid_dump) mid_dump[((size_t)2 * i + k2) * I + j] = hh;
+                    hrow[j] = half_to_float(hh);
+                }
+                float sh;
+                int32_t zh;
+                asym_quant_row(hrow.data(), ex.s_mid, I, hq.data(), &sh, &zh, ybuf);
+                if (hq_dump) std::memcpy(hq_dump + ((size_t)2 * i + k2) * I, hq.data(), I);
+                if (sh_dump) sh_dump[2 * i + k2] = sh;
+                if (zh_dump) zh_dump[2 * i + k2] = zh;
+                asym_row_gemm(hq.data(), zh, ex.w2, I, H, a2.data());
+                for (int n = 0; n < H; ++n) {
+                    yh[(size_t)k2 * H + n] = float_to_half(dequant(a2[n], sh, ex.sw2[n]));
+                    if (y_dump) y_dump[((size_t)2 * i + k2) * H + n] = yh[(size_t)k2 * H + n];
+                }
+            }
+            const float g0 = gw[2 * t], g1 = gw[2 * t + 1];
+            for (int n = 0; n < H; ++n) {
+                const float v = g0 * half_to_float(yh[n]) + g1 * half_to_float(yh[(size_t)H + n]);
+                out[(size_t)i * H + n] = float_to_half(v);
+            }
+        }
+    }
+}
+
+// ---- the CPU side of the heterogeneous deployment (Section III.B.3; Algorithm 1 step 3, CPU
+// branch; Section III.C.1a, option A) ---------------------------------------------------------
+// On the CPU an expert's int8 weights are dequantised once, when the model is loaded, to a
+// floating-point copy that stays cached in host memory; an expert that the offload policy
+// decides to compute on the CPU then runs in floating point on that copy, and only its output
+// rows travel to the GPU.  Reading taken here: the cached copy is binary32,
+// Wf[k][n] = float(code[k][n]) * scale[n] (one multiplication); the activations are not
+// quantised on this side but carry the same smoothing, xs = x / s (binary32 division); every
+// inner product is one binary32 accumulator started at 0 that takes the terms in ascending k
+// with one fused multiply-add each; SiLU and the binary16 roundings of the intermediate and of
+// the output are those of the int8 path.
+void oracle_dequant_weight(const int8_t* Wq, const float* col_scale, int K, int N, float* Wf) {
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n) Wf[(size_t)k * N + n] = (float)Wq[(size_t)k * N + n] * col_scale[n];
+}
+
+// Y[t][n] = sum_k (X[t][k] / s[k]) * Wf[k][n], binary32, k ascending, fused multiply-adds.
+// X is binary32 here (the caller converts binary16 exactly); s may be null.
+void oracle_fp_linear(const float* X, int64_t ldx, const float* s, const float* Wf, int T, int K, int N, float* Y) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        float* y = Y + (size_t)t * N;
+        for (int n = 0; n < N; ++n) y[n] = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            const float x = X[(size_t)t * ldx + k];
+            const float xs = s ? x / s[k] : x;
+            const float* w = Wf + (size_t)k * N;
+            for (int n = 0; n < N; ++n) y[n] = std::fmaf(xs, w[n], y[n]);
+        }
+    }
+}
+
+// One SwiGLU expert on the CPU's floating-point copy for n_rows token rows (fp16 in, fp16 out):
+// g = (x / s_in) W1f, u = (x / s_in) W3f, h = fp16(silu(g) * u), y = fp16((h / s_mid) W2f).
+// Optional dump of h (null to skip).
+void oracle_cpu_expert_ffn(const uint16_t* X, int64_t ldx, const float* s_in, const float* W1f, const float* W3f,
+                           const float* W2f, const float* s_mid, int n_rows, int H, int I, uint16_t* Y, int64_t ldy,
+                           uint16_t* mid_dump) {
+    std::vector<float> xf((size_t)n_rows * H), g((size_t)n_rows * I), u((size_t)n_rows * I), hf((size_t)n_rows * I),
+        y((size_t)n_rows * H);
+    for (int t = 0; t < n_rows; ++t)
+        for (int k = 0; k < H; ++k) xf[(size_t)t * H + k] = half_to_float(X[(size_t)t * ldx + k]);
+    oracle_fp_linear(xf.data(), H, s_in, W1f, n_rows, H, I, g.data());
+    oracle_fp_linear(xf.data(), H, s_in, W3f, n_rows, H, I, u.data());
+    for (size_t i = 0; i < (size_t)n_rows * I; ++i) {
+        const uint16_t hh = float_to_half(silu(g[i]) * u[i]);
+        if (mid_dump) mid_dump[i] = hh;
+        hf[i] = half_to_float(hh);
+    }
+    oracle_fp_linear(hf.data(), I, s_mid, W2f, n_rows, I, H, y.data());
+    for (int t = 0; t < n_rows; ++t)
+        for (int n = 0; n < H; ++n) Y[(size_t)t * ldy + n] = float_to_half(y[(size_t)t * H + n]);
+}
+
+// out[t] = fp16(g0 * y[2t] + g1 * y[2t+1]): the weighted combination at the end of the expert
+// FFN as a step of its own (y holds the two expert outputs of every token, pair order).
+void oracle_combine(const uint16_t* y, const float* gw, int T, int H, uint16_t* out) {
+    for (int t = 0; t < T; ++t)
+        for (int n = 0; n < H; ++n) {
+            const float v = gw[2 * t] * half_to_float(y[((size_t)2 * t) * H + n]) +
+                            gw[2 * t + 1] * half_to_float(y[((size_t)2 * t + 1) * H + n]);
+            out[(size_t)t * H + n] = float_to_half(v);
+        }
+}
+
 }  // extern "C"

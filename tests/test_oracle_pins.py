@@ -706,3 +706,152 @@ def test_outlier_channels_are_fixed_and_large():
     assert a[idx].min() > 3 * rest.max()
     X2, idx2, _ = hi.hidden_states(1, 64, 4096)
     assert np.array_equal(idx, idx2)
+
+
+# ----------------------------------------------------------------- asymmetric codes inside the routed expert FFN
+def _asym_chain_from_pinned_pieces(X, idx, gw, s_in, experts):
+    """The asymmetric layer assembled in Python from the separately pinned pieces."""
+    T, H = X.shape
+    q, sx, zp = oracle.asym_quant_act(X, s_in)
+    out = np.zeros((T, H), np.float16)
+    mids, ys = [], []
+    for t in range(T):
+        y2 = []
+        for k in range(2):
+            ex = experts[idx[t, k]]
+            a1 = oracle.asym_gemm(q[t:t + 1], zp[t:t + 1], ex.w1)[0]
+            a3 = oracle.asym_gemm(q[t:t + 1], zp[t:t + 1], ex.w3)[0]
+            g = (a1.astype(F32) * sx[t]) * ex.sw1
+            u = (a3.astype(F32) * sx[t]) * ex.sw3
+            h = oracle.float_to_half((g / (F32(1) + oracle.exp_spec(-g))) * u)
+            y = oracle.w8a8_linear_asym(h[None, :], ex.s_mid, ex.w2, ex.sw2)[0]
+            mids.append(h)
+            ys.append(y)
+            y2.append(y.astype(F32))
+        out[t] = oracle.float_to_half(gw[t, 0] * y2[0] + gw[t, 1] * y2[1])
+    return out, np.stack(mids), np.stack(ys)
+
+
+def test_moe_asym_equals_chain_of_pinned_pieces_and_token_subset():
+    m = offline.small_moe(seed=115, T=19, H=128, I=192, E=8)
+    X, idx, gw, s_in, ex = m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]
+    out, mid, hq, sh, zh, y = oracle.moe_ffn_asym(X, idx, gw, s_in, ex, dumps=True)
+    out_c, mid_c, y_c = _asym_chain_from_pinned_pieces(X, idx, gw, s_in, ex)
+    assert np.array_equal(out.view(np.uint16), out_c.view(np.uint16))
+    assert np.array_equal(mid.view(np.uint16), mid_c.view(np.uint16)) and np.array_equal(y.view(np.uint16), y_c.view(np.uint16))
+    r = 7
+    q_r, s_r, z_r = oracle.asym_quant_act(mid[r:r + 1], ex[idx.ravel()[r]].s_mid)
+    assert np.array_equal(q_r[0], hq[r]) and s_r[0] == sh[r] and z_r[0] == zh[r]
+    tok = np.array([17, 3, 3, 0], np.int32)
+    sub, mid_s, hq_s, sh_s, zh_s, y_s = oracle.moe_ffn_asym(X, idx, gw, s_in, ex, tokens=tok, dumps=True)
+    rows = (2 * tok[:, None] + np.arange(2)[None, :]).ravel()
+    assert np.array_equal(sub.view(np.uint16), out[tok].view(np.uint16))
+    assert np.array_equal(hq_s, hq[rows]) and np.array_equal(zh_s, zh[rows]) and np.array_equal(sh_s, sh[rows])
+    assert np.array_equal(y_s.view(np.uint16), y[rows].view(np.uint16)) and np.array_equal(mid_s.view(np.uint16), mid[rows].view(np.uint16))
+
+
+def test_moe_asym_exact_integer_case():
+    """Integer tokens in [-100, 155] (scale 1, zero point 100, like the dense pin) and power-of-two weight scales:
+    the gate/up values are exact integers / 2^k, so the intermediate must be silu(g) u to fp16 accuracy; the down
+    accumulator is then pinned through the dumped codes: y = fp16((sum (hq - zh) w2) sh sw2) with exact integers."""
+    rng = np.random.default_rng(116)
+    T, H, I, E = 6, 64, 96, 4
+    X = rng.integers(-100, 156, (T, H)).astype(np.float16)
+    X[:, 0], X[:, 1] = -100, 155
+    experts = []
+    for e in range(E):
+        experts.append(oracle.Expert(rng.integers(-127, 128, (H, I)).astype(np.int8), rng.integers(-127, 128, (H, I)).astype(np.int8),
+                                     rng.integers(-127, 128, (I, H)).astype(np.int8), np.full(I, 2.0 ** -17, F32),
+                                     np.full(I, 2.0 ** -16, F32), np.full(H, 2.0 ** -9, F32), np.ones(I, F32)))
+    logits = rng.standard_normal((T, E)).astype(np.float16)
+    idx, gw = oracle.route_top2(logits)
+    out, mid, hq, sh, zh, y = oracle.moe_ffn_asym(X, idx, gw, np.ones(H, F32), experts, dumps=True)
+    Xi = X.astype(np.int64)
+    for r in range(2 * T):
+        ex = experts[idx.ravel()[r]]
+        g = (Xi[r // 2] @ ex.w1.astype(np.int64)) * 2.0 ** -17
+        u = (Xi[r // 2] @ ex.w3.astype(np.int64)) * 2.0 ** -16
+        ref = g / (1 + np.exp(-g)) * u
+        assert np.all(np.abs(mid[r].astype(np.float64) - ref) <= np.spacing(np.abs(ref).astype(np.float16)).astype(np.float64))
+        acc2 = (hq[r].astype(np.int64) - zh[r]) @ ex.w2.astype(np.int64)
+        assert np.array_equal(y[r], ((acc2.astype(F32) * sh[r]) * ex.sw2).astype(np.float16))
+        rec = (hq[r].astype(np.float64) - zh[r]) * sh[r]
+        assert np.all(np.abs(rec - mid[r].astype(np.float64)) <= sh[r] * (1 + 1e-6))
+    assert np.array_equal(out.view(np.uint16), oracle.combine(y, gw).view(np.uint16))
+
+
+def test_moe_asym_identical_experts_reduce_to_dense_ffn_and_track_the_float_reference():
+    m = offline.small_moe(seed=117, T=12, H=128, I=192, E=4)
+    same = [m["experts"][0]] * 4
+    out, _, _, _, _, y = oracle.moe_ffn_asym(m["X"], m["idx"], m["gw"], m["s_in"], same, dumps=True)
+    assert np.array_equal(y[0::2].view(np.uint16), y[1::2].view(np.uint16))
+    assert np.max(np.abs(out.astype(np.float64) - y[0::2].astype(np.float64))) <= np.max(np.spacing(np.abs(y[0::2]))) * 1.01
+    out = oracle.moe_ffn_asym(m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]).astype(np.float64)
+    ref = _float_moe_reference(m["X"], m["weights"], m["idx"], m["gw"].astype(np.float64))
+    assert np.sqrt(np.mean((out - ref) ** 2) / np.mean(ref ** 2)) < 0.03
+
+
+# ----------------------------------------------------------------- the CPU side: floating point on dequantised weights
+def test_dequantised_copy_and_fp_linear():
+    rng = np.random.default_rng(120)
+    Wq = rng.integers(-127, 128, (70, 33)).astype(np.int8)
+    sw = np.exp(rng.normal(-5, 1, 33)).astype(F32)
+    Wf = oracle.dequant_weight(Wq, sw)
+    assert Wf.dtype == F32 and np.array_equal(Wf.astype(np.float64), (Wq.astype(np.float64) * sw.astype(np.float64)).astype(F32).astype(np.float64))
+    # exact integer case: small integers, power-of-two smoothing entries -> the exact product
+    Xi = rng.integers(-64, 65, (5, 70)).astype(F32)
+    s2 = (2.0 ** rng.integers(-2, 3, 70)).astype(F32)
+    Wi = rng.integers(-127, 128, (70, 33)).astype(F32)
+    Y = oracle.fp_linear(Xi * s2, s2, Wi)
+    assert np.array_equal(Y.astype(np.int64), Xi.astype(np.int64) @ Wi.astype(np.int64))
+    # general case: within the forward error bound of a length-K binary32 sum, and s divides per input channel
+    X = rng.standard_normal((5, 70)).astype(F32)
+    s = np.exp(rng.normal(0, 1, 70)).astype(F32)
+    Y = oracle.fp_linear(X, s, Wf).astype(np.float64)
+    xs = (X / s).astype(np.float64)
+    ref = xs @ Wf.astype(np.float64)
+    bound = 70 * 2.0 ** -24 * (np.abs(xs) @ np.abs(Wf.astype(np.float64))) * 1.01
+    assert np.all(np.abs(Y - ref) <= bound)
+    assert not np.allclose(Y, X.astype(np.float64) @ Wf.astype(np.float64), rtol=1e-3)   # s really is applied
+
+
+def test_cpu_expert_follows_its_definition_and_has_no_activation_quantisation_error():
+    m = offline.small_moe(seed=121, T=16, H=128, I=320, E=4)
+    ex = m["experts"][1]
+    ce = oracle.cpu_expert(ex)
+    X, s_in = m["X"], m["s_in"]
+    Y, mid = oracle.cpu_expert_ffn(X, s_in, ce, dumps=True)
+    xs = (X.astype(F32) / s_in).astype(np.float64)
+    g, u = xs @ ce.w1f.astype(np.float64), xs @ ce.w3f.astype(np.float64)
+    h = g / (1 + np.exp(-g)) * u
+    assert np.allclose(mid.astype(np.float64), h, rtol=2e-3, atol=1e-4 * np.abs(h).max())
+    ref = (mid.astype(F32) / ex.s_mid).astype(np.float64) @ ce.w2f.astype(np.float64)
+    assert np.allclose(Y.astype(np.float64), ref, rtol=2e-3, atol=1e-4 * np.abs(ref).max())
+    # the same expert through the W8A8 path deviates from that floating-point result by the activation
+    # quantisation error; the CPU path by binary16 / binary32 roundings only
+    idx = np.full((16, 2), 1, np.int32)
+    _, _, _, _, y8 = oracle.moe_ffn(X, idx, np.full((16, 2), 0.5, F32), s_in, m["experts"], dumps=True)
+    full = ((h.astype(np.float16).astype(F32) / ex.s_mid).astype(np.float64)) @ ce.w2f.astype(np.float64)
+    e_cpu = np.mean((Y.astype(np.float64) - full) ** 2)
+    e_w8a8 = np.mean((y8[0::2].astype(np.float64) - full) ** 2)
+    assert e_cpu < 0.05 * e_w8a8
+
+
+def test_hybrid_layer_swaps_exactly_the_cpu_experts_rows():
+    m = offline.small_moe(seed=122, T=23, H=128, I=192, E=8)
+    X, idx, gw, s_in, ex = m["X"], m["idx"], m["gw"], m["s_in"], m["experts"]
+    out8, _, _, _, y8 = oracle.moe_ffn(X, idx, gw, s_in, ex, dumps=True)
+    assert np.array_equal(oracle.combine(y8, gw).view(np.uint16), out8.view(np.uint16))      # the combination step alone
+    out0, y0 = oracle.moe_ffn_hybrid(X, idx, gw, s_in, ex, on_cpu=())
+    assert np.array_equal(out0.view(np.uint16), out8.view(np.uint16))
+    on_cpu = (2, 5)
+    out, y = oracle.moe_ffn_hybrid(X, idx, gw, s_in, ex, on_cpu)
+    flat = idx.ravel()
+    cpu_rows = np.isin(flat, on_cpu)
+    assert cpu_rows.any() and np.array_equal(y[~cpu_rows].view(np.uint16), y8[~cpu_rows].view(np.uint16))
+    for e in on_cpu:
+        rows = np.nonzero(flat == e)[0]
+        assert np.array_equal(y[rows].view(np.uint16), oracle.cpu_expert_ffn(X[rows // 2], s_in, oracle.cpu_expert(ex[e])).view(np.uint16))
+    untouched = ~np.isin(idx, on_cpu).any(axis=1)
+    assert np.array_equal(out[untouched].view(np.uint16), out8[untouched].view(np.uint16))
+    assert np.max(np.abs(out.astype(np.float64) - out8.astype(np.float64))) < 0.05 * np.abs(out8.astype(np.float64)).max()
