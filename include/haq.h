@@ -380,6 +380,40 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * The routed expert FFN with ASYMMETRIC activation codes (Section IV.A: asymmetric
+ * quantisation is the default of the paper's experiments), for the tokens and for
+ * the requantised intermediate; expert weights stay symmetric per output channel.
+ * Routing, grouping by expert and the combination are those of haq_moe_w8a8_ffn
+ * (top-2 softmax gating; pairs sorted by (expert, pair id)).  Per token, with
+ * y = x / s_in: scale, zero point zx and codes q in [0, 255] exactly as in
+ * haq_w8a8_linear_asym.  Per (token, expert) pair:
+ *   g = deq(sum_k (q - zx) w1), u = deq(sum_k (q - zx) w3), h = fp16(silu(g) * u);
+ *   hq, sh, zh = asymmetric codes of h / s_mid;  y = fp16(deq(sum_j (hq - zh) w2));
+ * out[t] = fp16(g0 * y0 + g1 * y1).  The packed operands hold code - 128 and the
+ * GEMM epilogues add (128 - zero point) * column sum of the expert's weight codes:
+ * colsums_host [E] (HOST array) points at int32 device vectors cs1 [I], cs3 [I]
+ * (of the w1 and w3 codes) and cs2 [H] (of the w2 codes) from haq_weight_colsum.
+ * Every expert must be device resident; every batch size takes the grouped tiled
+ * GEMMs.  2 <= E <= 32, top_k = 2, H % 64 == 0, I % 64 == 0, both <= 16384.
+ * dbg: the fields of haq_moe_debug (q and hq receive the uint8 codes) plus the zero
+ * points zx [T] and zh [2T] (sorted order); every field optional.               */
+typedef struct haq_expert_colsum {
+    const int32_t* cs1; /* [I] device */
+    const int32_t* cs3; /* [I] device */
+    const int32_t* cs2; /* [H] device */
+} haq_expert_colsum;
+typedef struct haq_moe_debug_asym {
+    haq_moe_debug base;
+    int32_t* zx; /* [T] */
+    int32_t* zh; /* [2T] sorted order */
+} haq_moe_debug_asym;
+size_t haq_moe_asym_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
+int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl, const float* s_in,
+                              const haq_expert_desc* experts_host, const haq_expert_colsum* colsums_host, int32_t T,
+                              int32_t H, int32_t I, int32_t E, int32_t top_k, void* out_fp16, int64_t ldo,
+                              const haq_moe_debug_asym* dbg_host, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Measurement aids (no part of the method; used by the benchmark).
  *
  * haq_profile_enable(1) creates events (allocates; call it outside timed regions

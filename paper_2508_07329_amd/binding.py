@@ -22,7 +22,7 @@ __all__ = [
     "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
-    "haq_moe_w8a8_ffn_static", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
+    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -44,7 +44,7 @@ EXPORTED_SYMBOLS = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
-    "haq_moe_w8a8_ffn_static", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
+    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -83,7 +83,7 @@ def lib() -> C.CDLL:
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
                   "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes", "haq_hessian_quant_workspace_bytes",
                   "haq_inverse_cholesky_workspace_bytes", "haq_linear_asym_workspace_bytes",
-                  "haq_quantize_layer_workspace_bytes"):
+                  "haq_quantize_layer_workspace_bytes", "haq_moe_asym_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -334,6 +334,52 @@ def haq_moe_w8a8_ffn_static(x, logits, s_in, experts, I: int, *, out):
     _check(lib().haq_moe_w8a8_ffn_static(_ptr(x), C.c_int64(x.stride(0)), _ptr(logits), C.c_int64(logits.stride(0)), _ptr(s_in),
                                          descs, T, H, I, E, 2, _ptr(out), C.c_int64(out.stride(0)), _stream()))
     return out
+
+
+class _ExpertColsum(C.Structure):
+    _fields_ = [("cs1", C.c_void_p), ("cs3", C.c_void_p), ("cs2", C.c_void_p)]
+
+
+class _MoeDebugAsym(C.Structure):
+    _fields_ = [("base", _MoeDebug), ("zx", C.c_void_p), ("zh", C.c_void_p)]
+
+
+def haq_moe_asym_workspace_bytes(T: int, H: int, I: int, E: int) -> int:
+    return int(lib().haq_moe_asym_workspace_bytes(T, H, I, E))
+
+
+def haq_moe_w8a8_ffn_asym(x, logits, s_in, experts, colsums, I: int, *, out=None, workspace=None, debug=False):
+    """The routed expert FFN with asymmetric activation codes.  colsums: per expert (cs1 [I], cs3 [I], cs2 [H]) int32
+    tensors from haq_weight_colsum.  With debug=True returns (y, MoeDebug with uint8 q / hq, zx [T], zh [2T])."""
+    T, H = x.shape
+    E = len(experts)
+    dev = x.device
+    y = out if out is not None else torch.empty((T, H), dtype=torch.float16, device=dev)
+    if workspace is None:
+        workspace = _ws(haq_moe_asym_workspace_bytes(T, H, I, E), dev)
+    descs = (_ExpertDesc * E)()
+    cs = (_ExpertColsum * E)()
+    for i, (e, c) in enumerate(zip(experts, colsums)):
+        descs[i].w13, descs[i].w2 = e.w13.data_ptr(), e.w2.data_ptr()
+        descs[i].sw1, descs[i].sw3, descs[i].sw2 = e.sw1.data_ptr(), e.sw3.data_ptr(), e.sw2.data_ptr()
+        descs[i].s_mid, descs[i].location = e.s_mid.data_ptr(), e.location
+        cs[i].cs1, cs[i].cs3, cs[i].cs2 = c[0].data_ptr(), c[1].data_ptr(), c[2].data_ptr()
+    dbg = zx = zh = None
+    dbg_c = None
+    if debug:
+        P = 2 * T
+        i32, f32, f16, u8 = torch.int32, torch.float32, torch.float16, torch.uint8
+        mk = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        spec = (((T, 2), i32), ((T, 2), f32), ((E,), i32), ((E + 1,), i32), ((P,), i32), ((P,), i32),
+                ((T, H), u8), ((T,), f32), ((P, I), f16), ((P, I), u8), ((P,), f32), ((P, H), f16))
+        dbg = MoeDebug(*[mk(*sp) for sp in spec])
+        zx, zh = mk((T,), i32), mk((P,), i32)
+        dbg_c = _MoeDebugAsym(_MoeDebug(*[getattr(dbg, n).data_ptr() for n in _DBG_FIELDS]), zx.data_ptr(), zh.data_ptr())
+    _check(lib().haq_moe_w8a8_ffn_asym(_ptr(x), C.c_int64(x.stride(0)), _ptr(logits), C.c_int64(logits.stride(0)), _ptr(s_in),
+                                       descs, cs, T, H, I, E, 2, _ptr(y), C.c_int64(y.stride(0)),
+                                       C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),
+                                       C.c_size_t(workspace.numel()), _stream()))
+    return (y, dbg, zx, zh) if debug else y
 
 
 # ---- measurement aids ------------------------------------------------------------------------

@@ -813,6 +813,148 @@ int32_t haq_moe_w8a8_ffn_static(const void* x_fp16, int64_t ldx, const void* log
                             HAQ_STATIC_SCRATCH_BYTES, stream);
 }
 
+size_t haq_moe_asym_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E) {
+    if (T < 0 || H <= 0 || I <= 0 || E <= 0) return 0;
+    const size_t P = 2 * (size_t)T;
+    return carve_moe(nullptr, T, H, I, E).bytes + 2 * (size_t)round_up((int64_t)(P > 0 ? P : 1) * 4, 256) +
+           (size_t)round_up((int64_t)E * (int64_t)sizeof(ColsumTab), 256);
+}
+
+int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logits_fp16, int64_t ldl, const float* s_in,
+                              const haq_expert_desc* experts, const haq_expert_colsum* colsums, int32_t T, int32_t H, int32_t I,
+                              int32_t E, int32_t top_k, void* out_fp16, int64_t ldo, const haq_moe_debug_asym* dbg,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || H <= 0 || I <= 0 || E <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: T=%d H=%d I=%d E=%d", T, H, I, E);
+    if (top_k != 2) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_asym: top_k=%d (only 2)", top_k);
+    if (E < 2 || E > 32) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_asym: E=%d outside [2, 32]", E);
+    if (H % 64 != 0 || I % 64 != 0 || H > 16384 || I > 16384)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_asym: H=%d and I=%d must be multiples of 64 (both <= 16384)", H, I);
+    if (T == 0) return HAQ_OK;
+    if (!x_fp16 || !logits_fp16 || !experts || !colsums || !out_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: null buffer");
+    if (ldx < H || ldx % 8 != 0 || ldl < E || ldo < H || ldo % 8 != 0)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: ldx=%lld ldl=%lld ldo=%lld", (long long)ldx, (long long)ldl, (long long)ldo);
+    if (!aligned16(x_fp16) || !aligned16(out_fp16) || (s_in && !aligned16(s_in)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: pointers must be 16-byte aligned");
+    haq_moe_debug_asym d{};
+    if (dbg) d = *dbg;
+    if ((d.base.q && !aligned16(d.base.q)) || (d.base.hq && !aligned16(d.base.hq)) || (d.base.mid_fp16 && !aligned16(d.base.mid_fp16)) ||
+        (d.base.y_fp16 && !aligned16(d.base.y_fp16)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: debug buffers q, hq, mid_fp16 and y_fp16 must be 16-byte aligned");
+    ExpertTab tab[32];
+    ColsumTab cst[32];
+    for (int e = 0; e < E; ++e) {
+        const haq_expert_desc& x = experts[e];
+        const haq_expert_colsum& c = colsums[e];
+        if (!x.w13 || !x.w2 || !x.sw1 || !x.sw3 || !x.sw2 || !x.s_mid || !c.cs1 || !c.cs3 || !c.cs2)
+            HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: expert %d has a null pointer", e);
+        if (!aligned16(x.w13) || !aligned16(x.w2) || !aligned16(x.s_mid) || !aligned16(x.sw1) || !aligned16(x.sw3) || !aligned16(x.sw2))
+            HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_moe_w8a8_ffn_asym: expert %d pointers must be 16-byte aligned", e);
+        if (x.location != HAQ_LOC_DEVICE) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_moe_w8a8_ffn_asym: expert %d is not device resident", e);
+        tab[e] = ExpertTab{x.w13, x.w2, x.sw1, x.sw3, x.sw2, x.s_mid};
+        cst[e] = ColsumTab{c.cs1, c.cs3, c.cs2};
+    }
+    const size_t need = haq_moe_asym_workspace_bytes(T, H, I, E);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_moe_w8a8_ffn_asym: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    MoeWs w = carve_moe(workspace, T, H, I, E);
+    const int P = 2 * T;
+    Carver extra((uint8_t*)workspace + w.bytes);
+    int32_t* zx_sorted = extra.take<int32_t>((size_t)P);
+    int32_t* zh_ws = extra.take<int32_t>((size_t)P);
+    ColsumTab* cstab = extra.take<ColsumTab>((size_t)E);
+    const haq_moe_debug& b = d.base;
+    int32_t* idx = b.topk_idx ? b.topk_idx : w.idx;
+    float* gw = b.topk_w ? b.topk_w : w.gw;
+    int32_t* counts = b.counts ? b.counts : w.counts;
+    int32_t* offsets = b.offsets ? b.offsets : w.offsets;
+    int32_t* perm = b.perm ? b.perm : w.perm;
+    int32_t* inv = b.inv ? b.inv : w.inv;
+    __half* mid = b.mid_fp16 ? (__half*)b.mid_fp16 : w.mid;
+    __half* y = b.y_fp16 ? (__half*)b.y_fp16 : w.y;
+    float* sh = b.sh ? b.sh : w.sh;
+    int32_t* zh = d.zh ? d.zh : zh_ws;
+
+    int rc;
+    if ((rc = launch_route_permute((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv, w.blk_counts,
+                                   st)) != HAQ_OK)
+        return rc;
+    if ((rc = launch_set_cstab(cst, E, cstab, st)) != HAQ_OK) return rc;
+    // tokens: one row of codes per (token, expert) pair in sorted order, zero point and scale with it
+    AsymRowArgs qa{};
+    qa.x = (const __half*)x_fp16;
+    qa.ldx = ldx;
+    qa.s = s_in;
+    qa.gather = perm;
+    qa.rows = P;
+    qa.K = H;
+    qa.q_cm = w.q_cm;
+    qa.R = w.R;
+    qa.q_rm = (uint8_t*)b.q;
+    qa.ldq = H;
+    qa.scale_out = w.sx_sorted;
+    qa.zp_out = zx_sorted;
+    qa.scale_in = b.sx;
+    qa.zp_in = d.zx;
+    if ((rc = launch_asym_quant_rows(qa, st)) != HAQ_OK) return rc;
+
+    GemmArgs g1{};
+    g1.A = w.q_cm;
+    g1.R = w.R;
+    g1.sx = w.sx_sorted;
+    g1.K = H;
+    g1.N = 2 * I;
+    g1.Npad = round_up(2 * (int64_t)I, NPAD);
+    g1.offsets = offsets;
+    g1.tab = w.tab;
+    g1.which = 0;
+    g1.n_sel = E;
+    for (int e = 0; e < E; ++e) g1.sel[e] = e;
+    g1.max_rows = P;
+    g1.Y = mid;
+    g1.ldy = I;
+    g1.zp = zx_sorted;
+    g1.cstab = cstab;
+    if ((rc = launch_gemm(g1, EPI_SWIGLU_ASYM, st)) != HAQ_OK) return rc;
+
+    AsymRowArgs qb{};
+    qb.x = mid;
+    qb.ldx = I;
+    qb.tab = w.tab;
+    qb.offsets = offsets;
+    qb.E = E;
+    qb.rows = P;
+    qb.K = I;
+    qb.q_cm = w.hq_cm;
+    qb.R = w.R;
+    qb.q_rm = (uint8_t*)b.hq;
+    qb.ldq = I;
+    qb.scale_out = sh;
+    qb.zp_out = zh;
+    if ((rc = launch_asym_quant_rows(qb, st)) != HAQ_OK) return rc;
+
+    GemmArgs g2{};
+    g2.A = w.hq_cm;
+    g2.R = w.R;
+    g2.sx = sh;
+    g2.K = I;
+    g2.N = H;
+    g2.Npad = round_up(H, NPAD);
+    g2.offsets = offsets;
+    g2.tab = w.tab;
+    g2.which = 1;
+    g2.n_sel = E;
+    for (int e = 0; e < E; ++e) g2.sel[e] = e;
+    g2.max_rows = P;
+    g2.act = HAQ_ACT_NONE;
+    g2.Y = y;
+    g2.ldy = H;
+    g2.zp = zh;
+    g2.cstab = cstab;
+    if ((rc = launch_gemm(g2, EPI_LINEAR_ASYM, st)) != HAQ_OK) return rc;
+    return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
+}
+
 int32_t haq_profile_enable(int32_t on) {
     if (on && !g_prof.on) {
         for (int i = 0; i <= PROF_MAX; ++i) HAQ_CHECK_HIP(hipEventCreate(&g_prof.ev[i]));

@@ -58,6 +58,7 @@ int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
     }
     const dim3 grid((unsigned)round_up((int64_t)mt * ntn, 8));
     if (epi == EPI_SWIGLU) return launch_one<EPI_SWIGLU, false>(a, grid, st);
+    if (epi == EPI_SWIGLU_ASYM) return launch_one<EPI_SWIGLU_ASYM, false>(a, grid, st);
     if (epi == EPI_LINEAR_ASYM) return a.acc_dbg ? launch_one<EPI_LINEAR_ASYM, true>(a, grid, st) : launch_one<EPI_LINEAR_ASYM, false>(a, grid, st);
     if (a.acc_dbg) return launch_one<EPI_LINEAR, true>(a, grid, st);
     return launch_one<EPI_LINEAR, false>(a, grid, st);

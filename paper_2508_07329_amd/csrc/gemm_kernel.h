@@ -114,8 +114,10 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     constexpr int GA = 4 * BM / 64, GB = 4 * BN / 64;  // 1 KB (64 rows x 16 B) load groups per K-step
     constexpr int LPW = (GA + GB) / NW;                // direct-to-LDS loads per wave per K-step
     static_assert((GA + GB) % NW == 0, "load groups must divide among the waves");
-    static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate/up blocks come in pairs");
-    constexpr int OUT_WN = (EPI == EPI_SWIGLU) ? WN / 2 : WN;  // output channels per wave tile
+    constexpr bool SWIGLU = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_ASYM;
+    constexpr bool ASYM = EPI == EPI_LINEAR_ASYM || EPI == EPI_SWIGLU_ASYM;
+    static_assert(!SWIGLU || NI % 2 == 0, "gate/up blocks come in pairs");
+    constexpr int OUT_WN = SWIGLU ? WN / 2 : WN;  // output channels per wave tile
     constexpr int PITCH = OUT_WN * 2 + 16;                     // staged fp16 row pitch in bytes
     static_assert(32 * PITCH * NW <= STAGES * STAGE_BYTES, "epilogue staging must fit in the ring");
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
@@ -128,6 +130,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     const int8_t* Bmat = a.B;
     const float* sw_a = a.sw;
     const float* sw_b = nullptr;
+    const int32_t* cs_a = a.colsum;  // column sums of the weight codes (asymmetric activation codes only)
+    const int32_t* cs_b = nullptr;
     if (a.offsets) {
         const ExpertTab& t = a.tab[tc.e];
         if (a.which == 0) {
@@ -137,6 +141,11 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
         } else {
             Bmat = t.w2;
             sw_a = t.sw2;
+        }
+        if (ASYM) {
+            const ColsumTab& c = a.cstab[tc.e];
+            cs_a = a.which == 0 ? c.cs1 : c.cs2;
+            cs_b = c.cs3;
         }
     }
 
@@ -153,7 +162,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
         const int pc = tc.n0 + i;
         float v = 0.0f;
         if (pc < a.N) {
-            if (EPI == EPI_SWIGLU) {
+            if (SWIGLU) {
                 const int col = (pc / 64) * 32 + (pc % 32);
                 v = ((pc / 32) & 1) ? sw_b[col] : sw_a[col];
             } else {
@@ -312,15 +321,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     const int m_l = lane & 31, n_l = (lane >> 5) * 4;
     constexpr int LANES_PER_ROW = OUT_WN * 2 / 16;
     constexpr int ROWS_PER_IT = 64 / LANES_PER_ROW;
-    const int out_n = (EPI == EPI_SWIGLU) ? a.N / 2 : a.N;
-    const int out_n0 = (EPI == EPI_SWIGLU) ? (tc.n0 + wn * WN) / 2 : tc.n0 + wn * WN;
+    const int out_n = SWIGLU ? a.N / 2 : a.N;
+    const int out_n0 = SWIGLU ? (tc.n0 + wn * WN) / 2 : tc.n0 + wn * WN;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
         const int rloc = wm * WM + i * 32 + m_l;
         const float sx = sx_s[rloc];
-        if (EPI != EPI_SWIGLU) {
-            int zshift = 0;  // 128 - zero point of this lane's token row (asymmetric codes only)
-            if (EPI == EPI_LINEAR_ASYM) zshift = (tc.m0 + rloc < tc.m_end) ? 128 - a.zp[tc.m0 + rloc] : 0;
+        int zshift = 0;  // 128 - zero point of this lane's token row (asymmetric codes only)
+        if (ASYM) zshift = (tc.m0 + rloc < tc.m_end) ? 128 - a.zp[tc.m0 + rloc] : 0;
+        if (!SWIGLU) {
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -332,9 +341,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         int v = acc[i][j][4 * q + e];
-                        if (EPI == EPI_LINEAR_ASYM) {
+                        if (ASYM) {
                             const int col = tc.n0 + wn * WN + nloc + e;
-                            if (col < a.N) v += zshift * a.colsum[col];
+                            if (col < a.N) v += zshift * cs_a[col];
                         }
                         if (DBG) {
                             const int row = tc.m0 + rloc, col = tc.n0 + wn * WN + nloc + e;
@@ -356,13 +365,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
                     const float4 s3 = *reinterpret_cast<const float4*>(sw_s + wn * WN + nloc + 32);
                     const float s1v[4] = {s1.x, s1.y, s1.z, s1.w}, s3v[4] = {s3.x, s3.y, s3.z, s3.w};
                     __half hv[4];
+                    const int oloc = (j / 2) * 32 + 8 * q + n_l;  // output channel inside the wave tile
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float g = dequant(acc[i][j][4 * q + e], sx, s1v[e]);
-                        const float u = dequant(acc[i][j + 1][4 * q + e], sx, s3v[e]);
+                        int ag = acc[i][j][4 * q + e], au = acc[i][j + 1][4 * q + e];
+                        if (ASYM) {
+                            const int col = out_n0 + oloc + e;
+                            if (col < out_n) {
+                                ag += zshift * cs_a[col];
+                                au += zshift * cs_b[col];
+                            }
+                        }
+                        const float g = dequant(ag, sx, s1v[e]);
+                        const float u = dequant(au, sx, s3v[e]);
                         hv[e] = f2h(silu(g) * u);
                     }
-                    const int oloc = (j / 2) * 32 + 8 * q + n_l;  // output channel inside the wave tile
                     *reinterpret_cast<uint2*>(stage + m_l * PITCH + oloc * 2) = *reinterpret_cast<const uint2*>(hv);
                 }
         }

@@ -109,7 +109,13 @@ struct QuantArgs {
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 
-enum { EPI_LINEAR = 0, EPI_SWIGLU = 1, EPI_LINEAR_ASYM = 2 };
+enum { EPI_LINEAR = 0, EPI_SWIGLU = 1, EPI_LINEAR_ASYM = 2, EPI_SWIGLU_ASYM = 3 };
+
+struct ColsumTab {  // device-side table entry: column sums of an expert's weight codes (asymmetric activation codes)
+    const int32_t* cs1;  // [I] gate
+    const int32_t* cs3;  // [I] up
+    const int32_t* cs2;  // [H] down
+};
 
 struct GemmArgs {
     const int8_t* A;   // chunk-major [K/16][R][16]
@@ -136,11 +142,35 @@ struct GemmArgs {
     // asymmetric activation codes (EPI_LINEAR_ASYM): A holds code - 128; the accumulator is corrected by
     // (128 - zp[row]) * colsum[channel] before it is dequantised
     const int32_t* zp;      // [rows]
-    const int32_t* colsum;  // [N] column sums of the weight codes
+    const int32_t* colsum;  // [N] column sums of the weight codes (single matrix)
+    const ColsumTab* cstab; // grouped: per-expert column sums, on the device
 };
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st);
 int launch_asym_quant(const __half* x, int64_t ldx, const float* s, int T, int K, int8_t* q_cm, int64_t R, uint8_t* q_rm,
                       int64_t ldq, float* scale, int32_t* zp, hipStream_t st);
+
+// Asymmetric codes row by row (one work-group per output row, K <= 16384), for the routed expert FFN:
+// output row r reads input row gather[r] >> 1 (or r), with the shared vector s or, when tab is set, the
+// s_mid of the expert whose group (offsets) holds row r.
+struct AsymRowArgs {
+    const __half* x;
+    int64_t ldx;
+    const float* s;
+    const ExpertTab* tab;
+    const int32_t* offsets;
+    int E;
+    const int32_t* gather;
+    int rows, K;
+    int8_t* q_cm;      // chunk-major [K/16][R][16], code - 128, by output row
+    int64_t R;
+    uint8_t* q_rm;     // optional dense codes [.. x K]: by input row when gather is set, else by output row
+    int64_t ldq;
+    float* scale_out;  // [rows] by output row
+    int32_t* zp_out;   // [rows] by output row
+    float* scale_in;   // optional, by input row
+    int32_t* zp_in;    // optional, by input row
+};
+int launch_asym_quant_rows(const AsymRowArgs& a, hipStream_t st);
 
 // Decode path (at most 64 rows per expert): weight-streaming kernels.
 struct DecodeArgs {

@@ -301,6 +301,23 @@ int launch_set_tab(const ExpertTab* tab_host, int E, ExpertTab* tab_dev, hipStre
     return HAQ_OK;
 }
 
+namespace {
+struct ColsumAll {
+    ColsumTab e[32];
+};
+__global__ void set_cstab_kernel(ColsumAll tab, int E, ColsumTab* tab_dev) {
+    if ((int)threadIdx.x < E) tab_dev[threadIdx.x] = tab.e[threadIdx.x];
+}
+}  // namespace
+
+int launch_set_cstab(const ColsumTab* tab_host, int E, ColsumTab* tab_dev, hipStream_t st) {
+    ColsumAll tab{};
+    for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
+    hipLaunchKernelGGL(set_cstab_kernel, dim3(1), dim3(64), 0, st, tab, E, tab_dev);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
 int launch_combine(const __half* y, int64_t ldy, const int32_t* inv, const float* gw, int T, int H, __half* out,
                    int64_t ldo, hipStream_t st) {
     hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, st, y, ldy, inv, gw, T, H, out, ldo);

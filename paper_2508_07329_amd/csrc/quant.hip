@@ -645,6 +645,89 @@ __global__ __launch_bounds__(QMAX_THREADS) void asym_quant_kernel(AsymQuantArgs 
     }
 }
 
+// The same codes one row per work-group (thread c owns chunk c of the row; K <= 16 * QMAX_THREADS), for the
+// routed expert FFN: rows gathered through the permutation, or rows of the sorted intermediate with the
+// smoothing vector of the expert whose group holds the row.
+__global__ __launch_bounds__(QMAX_THREADS) void asym_quant_row_kernel(AsymRowArgs a) {
+    __shared__ float red_mn[QMAX_THREADS / 64], red_mx[QMAX_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = blockDim.x >> 6;
+    const int row = blockIdx.x;
+    const int src = a.gather ? (a.gather[row] >> 1) : row;
+    const float* s = a.s;
+    if (a.tab) {
+        int e = 0;
+        while (e + 1 < a.E && row >= a.offsets[e + 1]) ++e;
+        s = a.tab[e].s_mid;
+    }
+    const int nchunk = a.K / 16;
+    const bool active = tid < nchunk;
+    float y[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) y[i] = 0.0f;
+    if (active) {
+        load_x16(a.x + (size_t)src * a.ldx, tid, y);
+        if (s) {
+            float sv[16], rv[16];
+            const bool fast = load_s16(s, tid, sv, rv);
+            if (fast) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) y[i] = div_by(y[i], sv[i], rv[i], true);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) y[i] = y[i] / sv[i];
+            }
+        }
+    }
+    float mn = 0.0f, mx = 0.0f;  // the range always contains 0
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        mn = fminf(mn, y[i]);
+        mx = fmaxf(mx, y[i]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o));
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    if (lane == 0) {
+        red_mn[wave] = mn;
+        red_mx[wave] = mx;
+    }
+    __syncthreads();
+    float lo = 0.0f, hi = 0.0f;
+    for (int w = 0; w < nwave; ++w) {
+        lo = fminf(lo, red_mn[w]);
+        hi = fmaxf(hi, red_mx[w]);
+    }
+    const float range = hi - lo;
+    float scale = 0.0f, z = 0.0f;
+    uint32_t w4[4] = {0x80808080u, 0x80808080u, 0x80808080u, 0x80808080u};  // code 0 -> -128
+    uint32_t u4[4] = {0, 0, 0, 0};
+    if (range != 0.0f) {
+        scale = range / 255.0f;
+        z = fminf(fmaxf(rintf(-lo / scale), 0.0f), 255.0f);
+        const float rscale = 1.0f / scale;
+        const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float qv = sfast ? div_by(y[i], scale, rscale, true) : y[i] / scale;
+            const float cf = fminf(fmaxf(rintf(qv) + z, 0.0f), 255.0f);
+            u4[i / 4] |= (uint32_t)(int)cf << (8 * (i % 4));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w4[i] = u4[i] ^ 0x80808080u;
+    }
+    if (tid == 0) {
+        a.scale_out[row] = scale;
+        a.zp_out[row] = (int32_t)z;
+        if (a.scale_in) a.scale_in[src] = scale;
+        if (a.zp_in) a.zp_in[src] = (int32_t)z;
+    }
+    if (!active) return;
+    if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)(a.gather ? src : row) * a.ldq + tid * 16) = make_uint4(u4[0], u4[1], u4[2], u4[3]);
+    *reinterpret_cast<uint4*>(a.q_cm + ((size_t)tid * a.R + row) * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+}
+
 __global__ void weight_colsum_kernel(const int8_t* wq, int K, int N, int32_t* colsum) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
@@ -811,6 +894,16 @@ int launch_asym_quant(const __half* x, int64_t ldx, const float* s, int T, int K
         case 2: hipLaunchKernelGGL(asym_quant_kernel<2>, dim3(nb), dim3(threads), 0, st, a, CL); break;
         default: hipLaunchKernelGGL(asym_quant_kernel<1>, dim3(nb), dim3(threads), 0, st, a, CL); break;
     }
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int launch_asym_quant_rows(const AsymRowArgs& a, hipStream_t st) {
+    if (a.rows <= 0) return HAQ_OK;
+    const int nchunk = a.K / 16;
+    const int threads = (int)round_up(nchunk, 64);
+    if (threads > QMAX_THREADS) return HAQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(asym_quant_row_kernel, dim3(a.rows), dim3(threads), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

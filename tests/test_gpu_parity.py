@@ -668,3 +668,81 @@ def test_stage_profile_and_clock_probe_report():
     torch.cuda.synchronize()
     cycles, ticks = (int(v) for v in clk.tolist())
     assert ticks >= 20000 and 100.0 < cycles / ticks * 100.0 < 3000.0     # MHz
+
+
+# ------------------------------------------------------------------ asymmetric codes inside the routed expert FFN
+def _colsums(dev_experts_src):
+    """Per expert (cs1, cs3, cs2) from the library's own column-sum kernel on the canonical int8 matrices."""
+    return [(haq.haq_weight_colsum(dev(ex.w1)), haq.haq_weight_colsum(dev(ex.w3)), haq.haq_weight_colsum(dev(ex.w2)))
+            for ex in dev_experts_src]
+
+
+def _check_moe_asym(m, dev_experts=None, colsums=None, tokens=None):
+    X, logits, s_in, experts = m["X"], m["logits"], m["s_in"], m["experts"]
+    T, H = X.shape
+    I = experts[0].w1.shape[1]
+    E = len(experts)
+    if dev_experts is None:
+        dev_experts = upload_experts(experts)
+    if colsums is None:
+        colsums = _colsums(experts)
+    out, d, zx, zh = haq.haq_moe_w8a8_ffn_asym(dev(X), dev(logits), dev(s_in), dev_experts, colsums, I, debug=True)
+    torch.cuda.synchronize()
+    idx_ref, gw_ref = oracle.route_top2(logits)
+    counts, offsets, perm, inv = oracle.permute(idx_ref, E)
+    assert bits_equal(host(d.topk_idx), idx_ref) and bits_equal(host(d.topk_w), gw_ref)
+    assert bits_equal(host(d.counts), counts) and bits_equal(host(d.offsets), offsets)
+    assert bits_equal(host(d.perm), perm) and bits_equal(host(d.inv), inv)
+    q_ref, sx_ref, zx_ref = oracle.asym_quant_act(X, s_in)
+    assert bits_equal(host(d.sx), sx_ref) and bits_equal(host(zx), zx_ref)
+    assert bits_equal(host(d.q), q_ref), diff_report(host(d.q), q_ref)
+    tok = np.arange(T, dtype=np.int32) if tokens is None else np.asarray(tokens, np.int32)
+    out_ref, mid_ref, hq_ref, sh_ref, zh_ref, y_ref = oracle.moe_ffn_asym(X, idx_ref, gw_ref, s_in, experts, tokens=tok, dumps=True)
+    pos = inv[(2 * tok[:, None] + np.arange(2)[None, :]).ravel()]
+    assert fp16_close(host(out)[tok], out_ref)
+    for name, g, c in (("mid", host(d.mid_fp16)[pos], mid_ref), ("hq", host(d.hq)[pos], hq_ref), ("sh", host(d.sh)[pos], sh_ref),
+                       ("zh", host(zh)[pos], zh_ref), ("y", host(d.y_fp16)[pos], y_ref), ("out", host(out)[tok], out_ref)):
+        assert bits_equal(g, c), f"{name}: {diff_report(g, c)}"
+    out2 = haq.haq_moe_w8a8_ffn_asym(dev(X), dev(logits), dev(s_in), dev_experts, colsums, I)
+    assert bits_equal(host(out2), host(out))
+    return counts
+
+
+@pytest.mark.parametrize("T,H,I,E", [(37, 128, 320, 8), (1, 128, 192, 8), (300, 256, 576, 8), (9, 128, 192, 2), (530, 192, 448, 4),
+                                      (700, 128, 192, 32), (64, 256, 1024, 4), (2100, 128, 256, 8)])
+def test_moe_asym_small_everything_bit_exact(T, H, I, E):
+    _check_moe_asym(offline.small_moe(seed=220 + T, T=T, H=H, I=I, E=E))
+
+
+def test_moe_asym_skewed_routing_empty_expert_and_one_sided_tokens():
+    m = offline.small_moe(seed=231, T=64, H=128, I=192, E=8, routing="popularity")
+    m["logits"][:, 5] = -100                     # nobody picks expert 5
+    m["X"][:20] = np.abs(m["X"][:20])            # one-sided rows: zero point 0
+    m["X"][7] = 0                                # a zero row: scale 0, zero point 0, codes 0
+    counts = _check_moe_asym(m)
+    assert counts[5] == 0
+
+
+def test_moe_asym_identical_experts_equal_the_dense_asymmetric_linear_chain():
+    """All experts the same: every pair's y is the dense chain (asymmetric gate/up linears, SwiGLU, asymmetric down
+    linear) that haq_w8a8_linear_asym computes for the down stage."""
+    m = offline.small_moe(seed=232, T=40, H=128, I=320, E=4)
+    ex0 = m["experts"][0]
+    same = [ex0] * 4
+    m2 = dict(m, experts=same)
+    _check_moe_asym(m2)
+    out, d, zx, zh = haq.haq_moe_w8a8_ffn_asym(dev(m["X"]), dev(m["logits"]), dev(m["s_in"]), upload_experts(same), _colsums(same),
+                                               320, debug=True)
+    w2_d = dev(ex0.w2)
+    y_lin = haq.haq_w8a8_linear_asym(d.mid_fp16, dev(ex0.s_mid), haq.haq_pack_weight(w2_d), dev(ex0.sw2), haq.haq_weight_colsum(w2_d), 128)
+    assert bits_equal(host(y_lin), host(d.y_fp16))
+
+
+@pytest.mark.parametrize("name", ["decode_b8", "prefill"])
+def test_moe_asym_mixtral(layer, name):
+    """The Mixtral-shaped layer with asymmetric codes: 8 tokens, and the 4096-token Zipf prefill batch
+    (every token against the oracle)."""
+    wl = hi.MIXTRAL_PREFILL if name == "prefill" else {w.T: w for w in hi.MIXTRAL_DECODE}[8]
+    if "colsums" not in layer:
+        layer["colsums"] = _colsums(layer["experts"])
+    _check_moe_asym(_mixtral_case(wl, layer), layer["dev_experts"], layer["colsums"], np.arange(wl.T))
