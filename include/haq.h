@@ -330,9 +330,9 @@ int32_t haq_ctx_last_call_timing(haq_ctx* ctx, float* total_ms, float* copies_ms
  * costs T_CPU = n * latency_cpu; transferring it costs T_sum = t_e + n *
  * latency_gpu.  *n_critical = the largest batch n for which the CPU is not
  * slower; the expert is worth transferring when n_inputs > *n_critical.
- * *n_critical = -1 when latency_cpu <= latency_gpu (never transfer).  This
- * library has no CPU compute path: haq_moe_w8a8_ffn always transfers; the
- * figure is for a host runtime that owns one.
+ * *n_critical = -1 when latency_cpu <= latency_gpu (never transfer).
+ * haq_moe_w8a8_ffn applies the rule once a context has been given the three
+ * figures (haq_ctx_set_offload_policy below); without them it always transfers.
  *
  * haq_select_experts (Algorithm 2): which experts of every layer to keep
  * resident.  Layer l owns the paths path_offsets[l] .. path_offsets[l+1]-1;
@@ -360,6 +360,57 @@ int32_t haq_select_experts(int32_t num_layers, int32_t experts_per_layer, int32_
                            const int32_t* path_offsets, const int32_t* path_experts, int32_t path_len,
                            const double* path_freq, const double* expert_freq, int32_t* selected,
                            int32_t* n_selected);
+
+/* ------------------------------------------------------------------------
+ * The CPU side of the heterogeneous deployment (Section III.B.3; Algorithm 1
+ * step 3, CPU branch; Section III.C.1a, option A).  All pointers HOST.
+ *
+ * haq_cpu_expert_create dequantises an expert once, at load time, into a
+ * floating-point copy that stays cached in host memory: Wf = float(code) *
+ * scale of the output channel, binary32.  Inputs are the canonical row-major
+ * int8 matrices of haq_quant_weight (w1q, w3q [H x I], w2q [I x H]), their
+ * scales and the expert's s_mid [I]; the copy takes 12 H I bytes.
+ * haq_cpu_expert_ffn computes the expert for n_rows token rows in floating
+ * point on that copy (the activations are not quantised on this side):
+ *   xs = x / s_in;  g = xs W1f, u = xs W3f;  h = fp16(silu(g) * u);
+ *   y = fp16((h / s_mid) W2f)
+ * with one binary32 accumulator per inner product, input channels in ascending
+ * order, one fused multiply-add per term (silu and e^t as in haq_moe_w8a8_ffn),
+ * so the result does not depend on n_threads (0 = all hardware threads, at most
+ * 64; threads split the output channels).  x fp16 [n_rows x H] (row stride ldx),
+ * s_in [H] or NULL, y fp16 [n_rows x H] (row stride ldy).
+ *
+ * haq_ctx_set_offload_policy gives a context the cost model of Eq. 7-8 (t_e,
+ * latency_cpu, latency_gpu in one unit of time, calibrated by the caller) and a
+ * host copy of s_in (NULL if the layer has none); haq_ctx_register_cpu_expert
+ * tells it which host-resident expert (key = the w13 pointer its descriptor
+ * carries) has a CPU copy (expert = NULL removes the entry).  From then on
+ * haq_moe_w8a8_ffn decides per activated host-resident expert (Section
+ * III.C.1b): held by the GPU cache -> computed there; else n_inputs >
+ * n_critical -> transferred (through the cache, as before); else -> computed by
+ * haq_cpu_expert_ffn on the host while the GPU works on the other experts, and
+ * only its output rows are copied to the GPU.  Experts without a CPU copy, or
+ * with more rows than the staging area (min(n_critical, 1024) rows), are
+ * transferred.  t_e < 0 switches the rule off again (always transfer, the
+ * default).  The calls allocate (pinned staging, a stream): set-up, not serving.
+ * haq_ctx_last_decisions: for the last call, per activated host-resident expert
+ * in expert order: its index, its batch n_inputs and the decision; *n_critical
+ * (optional) receives the break-even batch in force (-1: the CPU is never
+ * slower; -2: no cost model set).                                            */
+#define HAQ_DECISION_GPU_CACHED 0
+#define HAQ_DECISION_TRANSFER 1
+#define HAQ_DECISION_CPU 2
+typedef struct haq_cpu_expert haq_cpu_expert;
+int32_t haq_cpu_expert_create(const int8_t* w1q, const int8_t* w3q, const int8_t* w2q, const float* sw1, const float* sw3,
+                              const float* sw2, const float* s_mid, int32_t H, int32_t I, haq_cpu_expert** out);
+int32_t haq_cpu_expert_destroy(haq_cpu_expert* expert);
+int32_t haq_cpu_expert_ffn(const haq_cpu_expert* expert, const void* x_fp16, int64_t ldx, const float* s_in, int32_t n_rows,
+                           void* y_fp16, int64_t ldy, int32_t n_threads);
+int32_t haq_ctx_set_offload_policy(haq_ctx* ctx, double t_e, double latency_cpu, double latency_gpu, const float* s_in_host,
+                                   int32_t cpu_threads);
+int32_t haq_ctx_register_cpu_expert(haq_ctx* ctx, const void* key, const haq_cpu_expert* expert);
+int32_t haq_ctx_last_decisions(const haq_ctx* ctx, int32_t max_n, int32_t* n, int32_t* expert, int32_t* n_inputs,
+                               int32_t* decision, int64_t* n_critical);
 
 size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
 

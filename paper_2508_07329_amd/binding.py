@@ -19,9 +19,10 @@ __all__ = [
     "haq_quant_act_packed", "haq_gemm_w8a8_packed", "haq_ffn_workspace_bytes", "haq_w8a8_ffn",
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_ctx_create", "haq_ctx_destroy", "ExpertWeights", "MoeDebug", "HAQ_ACT_NONE", "HAQ_ACT_RELU",
-    "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS",
+    "HAQ_LOC_DEVICE", "HAQ_LOC_HOST_PINNED", "EXPORTED_SYMBOLS", "HAQ_DECISION_GPU_CACHED", "HAQ_DECISION_TRANSFER", "HAQ_DECISION_CPU",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
+    "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
     "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
@@ -31,6 +32,7 @@ __all__ = [
 
 HAQ_ACT_NONE, HAQ_ACT_RELU = 0, 1
 HAQ_LOC_DEVICE, HAQ_LOC_HOST_PINNED = 0, 1
+HAQ_DECISION_GPU_CACHED, HAQ_DECISION_TRANSFER, HAQ_DECISION_CPU = 0, 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libhaq.so")
@@ -44,6 +46,7 @@ EXPORTED_SYMBOLS = [
     "haq_moe_workspace_bytes", "haq_moe_w8a8_ffn",
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
+    "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
     "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
@@ -380,6 +383,49 @@ def haq_moe_w8a8_ffn_asym(x, logits, s_in, experts, colsums, I: int, *, out=None
                                        C.byref(dbg_c) if dbg_c is not None else None, _ptr(workspace),
                                        C.c_size_t(workspace.numel()), _stream()))
     return (y, dbg, zx, zh) if debug else y
+
+
+# ---- the CPU side of the offload runtime (Section III.B.3, III.C.1a-b) ----------------------------
+def haq_cpu_expert_create(w1q, w3q, w2q, sw1, sw3, sw2, s_mid):
+    """CPU tensors: canonical int8 matrices w1q, w3q [H,I], w2q [I,H], their scales and s_mid.  Returns an opaque handle
+    to the expert's dequantised floating-point copy (free it with haq_cpu_expert_destroy)."""
+    H, I = w1q.shape
+    for t in (w1q, w3q, w2q, sw1, sw3, sw2, s_mid):
+        assert t.device.type == "cpu" and t.is_contiguous()
+    h = C.c_void_p()
+    _check(lib().haq_cpu_expert_create(_ptr(w1q), _ptr(w3q), _ptr(w2q), _ptr(sw1), _ptr(sw3), _ptr(sw2), _ptr(s_mid), H, I, C.byref(h)))
+    return h
+
+
+def haq_cpu_expert_destroy(handle):
+    _check(lib().haq_cpu_expert_destroy(handle))
+
+
+def haq_cpu_expert_ffn(handle, x, s_in, H: int, n_threads: int = 0):
+    """x fp16 [n, H] CPU tensor, s_in fp32 [H] CPU tensor or None -> y fp16 [n, H] (CPU)."""
+    n = x.shape[0]
+    y = torch.empty((n, H), dtype=torch.float16)
+    _check(lib().haq_cpu_expert_ffn(handle, _ptr(x), C.c_int64(x.stride(0)), _ptr(s_in), n, _ptr(y), C.c_int64(H), n_threads))
+    return y
+
+
+def haq_ctx_set_offload_policy(ctx, t_e: float, latency_cpu: float, latency_gpu: float, s_in_host=None, cpu_threads: int = 0):
+    _check(lib().haq_ctx_set_offload_policy(ctx, C.c_double(t_e), C.c_double(latency_cpu), C.c_double(latency_gpu),
+                                            _ptr(s_in_host), cpu_threads))
+
+
+def haq_ctx_register_cpu_expert(ctx, expert_weights, handle):
+    """expert_weights: the ExpertWeights (host resident) whose w13 address keys the entry; handle None removes it."""
+    _check(lib().haq_ctx_register_cpu_expert(ctx, C.c_void_p(expert_weights.w13.data_ptr()), handle))
+
+
+def haq_ctx_last_decisions(ctx):
+    """([(expert, n_inputs, decision), ...], n_critical) of the context's last call."""
+    n = C.c_int32(0)
+    ex, ni, de = (C.c_int32 * 32)(), (C.c_int32 * 32)(), (C.c_int32 * 32)()
+    nc = C.c_int64(0)
+    _check(lib().haq_ctx_last_decisions(ctx, 32, C.byref(n), ex, ni, de, C.byref(nc)))
+    return [(int(ex[i]), int(ni[i]), int(de[i])) for i in range(n.value)], int(nc.value)
 
 
 # ---- measurement aids ------------------------------------------------------------------------

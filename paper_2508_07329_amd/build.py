@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhaq.so")
-SOURCES = ["api.hip", "quant.hip", "gemm.hip", "moe.hip", "decode.hip", "search.hip", "sched.hip", "hessian.hip", "probe.hip"]
+SOURCES = ["api.hip", "quant.hip", "gemm.hip", "moe.hip", "decode.hip", "search.hip", "sched.hip", "hessian.hip", "probe.hip", "cpu_expert.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -16,6 +16,7 @@ HIPCC_FLAGS = [
     "-fhip-fp32-correctly-rounded-divide-sqrt",
     "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Xarch_host", "-mavx2", "-Xarch_host", "-mfma",  # host code of the CPU expert path: hardware fused multiply-adds
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "haq_common.h"
 #include "moe.h"
@@ -209,6 +210,25 @@ struct haq_ctx {
     hipEvent_t t_start = nullptr, t_copy0 = nullptr, t_copy1 = nullptr, t_end = nullptr;
     bool timed = false, timed_copies = false;
     bool used = false;
+    // Offload policy (Section III.C.1a-b): the cost model of Eq. 7-8 and the CPU copies of host-resident
+    // experts it may choose; a third stream carries the small copies of the CPU experts' rows
+    bool policy_on = false;
+    double t_e = 0.0, latency_cpu = 0.0, latency_gpu = 0.0;
+    int64_t n_critical = 0;
+    int cpu_threads = 0, stage_rows = 0;
+    bool has_s_in = false;
+    std::vector<float> s_in_host;
+    struct CpuReg {
+        const void* key;
+        const haq_cpu_expert* ex;
+    };
+    std::vector<CpuReg> cpu_experts;
+    hipStream_t aux_stream = nullptr;
+    hipEvent_t aux_done = nullptr;
+    uint16_t *x_stage = nullptr, *y_stage = nullptr;  // pinned [stage_rows x H]
+    int32_t* perm_stage = nullptr;                    // pinned [stage_rows]
+    int n_dec = 0;
+    int32_t dec_expert[32] = {}, dec_n[32] = {}, dec_what[32] = {};
     int32_t* counts_host = nullptr;  // pinned
     // the slots double as an expert cache with least-recently-used replacement: which host
     // expert (keyed by the address of its gate/up matrix) a slot holds, and when it was last used
@@ -430,6 +450,12 @@ int32_t haq_ctx_destroy(haq_ctx* c) {
     for (hipEvent_t t : {c->t_start, c->t_copy0, c->t_copy1, c->t_end})
         if (t) (void)hipEventDestroy(t);
     if (c->counts_host) (void)hipHostFree(c->counts_host);
+    if (c->aux_stream) (void)hipStreamSynchronize(c->aux_stream);
+    if (c->x_stage) (void)hipHostFree(c->x_stage);
+    if (c->y_stage) (void)hipHostFree(c->y_stage);
+    if (c->perm_stage) (void)hipHostFree(c->perm_stage);
+    if (c->aux_done) (void)hipEventDestroy(c->aux_done);
+    if (c->aux_stream) (void)hipStreamDestroy(c->aux_stream);
     if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     delete c;
     return HAQ_OK;
@@ -672,9 +698,33 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     // cache state; the context only takes it over once every copy and launch of the call is
     // enqueued, so a call that fails half way never leaves a slot labelled with weights that did
     // not arrive.
-    int order[32], n_order = 0;
-    for (int i = 0; i < n_host; ++i)
-        if (ctx->counts_host[host_expert[i]] > 0) order[n_order++] = host_expert[i];
+    // Decision per activated host expert (Section III.C.1b): one that the cache holds computes on the GPU;
+    // otherwise, with a cost model set and a CPU copy registered, it is transferred only if its batch
+    // exceeds the break-even size of Eq. 7-8 and computed on the CPU if not.
+    int order[32], n_order = 0, cpu_list[32], n_cpu = 0;
+    const haq_cpu_expert* cpu_of[32] = {};
+    ctx->n_dec = 0;
+    for (int i = 0; i < n_host; ++i) {
+        const int e = host_expert[i], n = ctx->counts_host[e];
+        if (n <= 0) continue;
+        const void* key = experts[e].w13;
+        bool cached = false;
+        for (int c = 0; c < ctx->n_slots; ++c) cached = cached || ctx->slot_key[c] == key;
+        int what = cached ? HAQ_DECISION_GPU_CACHED : HAQ_DECISION_TRANSFER;
+        if (!cached && ctx->policy_on && (ctx->n_critical < 0 || n <= ctx->n_critical) && n <= ctx->stage_rows &&
+            (!s_in || ctx->has_s_in)) {
+            for (const auto& r : ctx->cpu_experts)
+                if (r.key == key) cpu_of[e] = r.ex;
+            if (cpu_of[e]) what = HAQ_DECISION_CPU;
+        }
+        ctx->dec_expert[ctx->n_dec] = e;
+        ctx->dec_n[ctx->n_dec] = n;
+        ctx->dec_what[ctx->n_dec++] = what;
+        if (what == HAQ_DECISION_CPU)
+            cpu_list[n_cpu++] = e;
+        else
+            order[n_order++] = e;
+    }
     uint64_t keys_l[32], ticks_l[32], tick_l = ctx->tick, req[32];
     for (int c = 0; c < 32; ++c) {
         keys_l[c] = (uint64_t)(uintptr_t)ctx->slot_key[c];
@@ -745,6 +795,30 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
             }
         }
         HAQ_CHECK_HIP(hipEventRecord(ctx->t_copy1, ctx->copy_stream));
+        // Option A: the experts left to the CPU are computed here, on the host, while the GPU works through
+        // what was enqueued above; their token rows come over on a third stream and their output rows go
+        // back into the sorted per-pair outputs before the combination.
+        if (n_cpu > 0) {
+            int off_host[33] = {0};
+            for (int e = 0; e < E; ++e) off_host[e + 1] = off_host[e] + ctx->counts_host[e];
+            HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->aux_stream, ctx->routed, 0));
+            for (int i = 0; i < n_cpu; ++i) {
+                const int e = cpu_list[i], n = ctx->counts_host[e], lo = off_host[e];
+                HAQ_CHECK_HIP(hipMemcpyAsync(ctx->perm_stage, perm + lo, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, ctx->aux_stream));
+                HAQ_CHECK_HIP(hipStreamSynchronize(ctx->aux_stream));
+                for (int q = 0; q < n; ++q)
+                    HAQ_CHECK_HIP(hipMemcpyAsync(ctx->x_stage + (size_t)q * H, (const __half*)x_fp16 + (size_t)(ctx->perm_stage[q] >> 1) * ldx,
+                                                 (size_t)H * 2, hipMemcpyDeviceToHost, ctx->aux_stream));
+                HAQ_CHECK_HIP(hipStreamSynchronize(ctx->aux_stream));
+                if ((r = haq_cpu_expert_ffn(cpu_of[e], ctx->x_stage, H, s_in ? ctx->s_in_host.data() : nullptr, n, ctx->y_stage, H,
+                                            ctx->cpu_threads)) != HAQ_OK)
+                    return r;
+                HAQ_CHECK_HIP(hipMemcpyAsync(y + (size_t)lo * H, ctx->y_stage, (size_t)n * H * 2, hipMemcpyHostToDevice, ctx->aux_stream));
+                HAQ_CHECK_HIP(hipStreamSynchronize(ctx->aux_stream));  // the staging rows are free again
+            }
+            HAQ_CHECK_HIP(hipEventRecord(ctx->aux_done, ctx->aux_stream));
+            HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->aux_done, 0));
+        }
         if ((r = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st)) != HAQ_OK) return r;
         HAQ_CHECK_HIP(hipEventRecord(ctx->t_end, st));
         HAQ_CHECK_HIP(hipEventRecord(ctx->call_done, st));
@@ -773,6 +847,79 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     ctx->used = true;
     ctx->timed = true;
     ctx->timed_copies = n_order - n_hit > 0;
+    return HAQ_OK;
+}
+
+int32_t haq_ctx_set_offload_policy(haq_ctx* c, double t_e, double latency_cpu, double latency_gpu, const float* s_in_host,
+                                   int32_t cpu_threads) {
+    if (!c) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_set_offload_policy: null context");
+    if (t_e < 0.0) {  // back to "always transfer"
+        c->policy_on = false;
+        return HAQ_OK;
+    }
+    int64_t nc = 0;
+    const int rc = haq_offload_n_critical(t_e, latency_cpu, latency_gpu, &nc);
+    if (rc != HAQ_OK) return rc;
+    if (cpu_threads < 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_set_offload_policy: cpu_threads=%d", cpu_threads);
+    // staging for the rows of one CPU expert: as many rows as the rule can ever send to the CPU, at most 1024
+    const int rows = (int)(nc < 0 ? 1024 : (nc < 1 ? 1 : (nc > 1024 ? 1024 : nc)));
+    if (rows > c->stage_rows) {
+        if (c->aux_stream) HAQ_CHECK_HIP(hipStreamSynchronize(c->aux_stream));
+        if (c->x_stage) (void)hipHostFree(c->x_stage);
+        if (c->y_stage) (void)hipHostFree(c->y_stage);
+        if (c->perm_stage) (void)hipHostFree(c->perm_stage);
+        c->x_stage = c->y_stage = nullptr;
+        c->perm_stage = nullptr;
+        c->stage_rows = 0;
+        HAQ_CHECK_HIP(hipHostMalloc((void**)&c->x_stage, (size_t)rows * c->H * 2, hipHostMallocDefault));
+        HAQ_CHECK_HIP(hipHostMalloc((void**)&c->y_stage, (size_t)rows * c->H * 2, hipHostMallocDefault));
+        HAQ_CHECK_HIP(hipHostMalloc((void**)&c->perm_stage, (size_t)rows * sizeof(int32_t), hipHostMallocDefault));
+        c->stage_rows = rows;
+    }
+    if (!c->aux_stream) HAQ_CHECK_HIP(hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking));  // default priority
+    if (!c->aux_done) HAQ_CHECK_HIP(hipEventCreateWithFlags(&c->aux_done, hipEventDisableTiming));
+    try {
+        c->has_s_in = s_in_host != nullptr;
+        if (s_in_host) c->s_in_host.assign(s_in_host, s_in_host + c->H);
+    } catch (const std::bad_alloc&) {
+        HAQ_FAIL(HAQ_ERR_HIP, "haq_ctx_set_offload_policy: out of host memory");
+    }
+    c->t_e = t_e;
+    c->latency_cpu = latency_cpu;
+    c->latency_gpu = latency_gpu;
+    c->n_critical = nc;
+    c->cpu_threads = cpu_threads;
+    c->policy_on = true;
+    return HAQ_OK;
+}
+
+int32_t haq_ctx_register_cpu_expert(haq_ctx* c, const void* key, const haq_cpu_expert* expert) {
+    if (!c || !key) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_register_cpu_expert: null context or key");
+    try {
+        for (size_t i = 0; i < c->cpu_experts.size(); ++i)
+            if (c->cpu_experts[i].key == key) {
+                c->cpu_experts.erase(c->cpu_experts.begin() + (long)i);
+                break;
+            }
+        if (expert) c->cpu_experts.push_back({key, expert});
+    } catch (const std::bad_alloc&) {
+        HAQ_FAIL(HAQ_ERR_HIP, "haq_ctx_register_cpu_expert: out of host memory");
+    }
+    return HAQ_OK;
+}
+
+int32_t haq_ctx_last_decisions(const haq_ctx* c, int32_t max_n, int32_t* n, int32_t* expert, int32_t* n_inputs, int32_t* decision,
+                               int64_t* n_critical) {
+    if (!c || !n || max_n < 0 || (max_n > 0 && (!expert || !n_inputs || !decision)))
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_ctx_last_decisions: null argument");
+    const int k = c->n_dec < max_n ? c->n_dec : max_n;
+    for (int i = 0; i < k; ++i) {
+        expert[i] = c->dec_expert[i];
+        n_inputs[i] = c->dec_n[i];
+        decision[i] = c->dec_what[i];
+    }
+    *n = k;
+    if (n_critical) *n_critical = c->policy_on ? c->n_critical : -2;
     return HAQ_OK;
 }
 

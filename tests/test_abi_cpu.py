@@ -182,3 +182,25 @@ def test_moe_rejects_misaligned_debug_buffers():
         rc = L.haq_moe_w8a8_ffn(None, one, C.c_int64(64), one, C.c_int64(8), None, descs, 4, 64, 64, 2, 2, one,
                                 C.c_int64(64), C.byref(dbg), one, C.c_size_t(0), None)
         assert rc == -1 and "debug buffers" in L.haq_last_error().decode(), field
+
+
+def test_cpu_expert_matches_the_oracle_bit_for_bit_for_any_thread_count():
+    """The host code of the offload runtime's option A (floating point on the dequantised copy) against the oracle's
+    plain statement of it; it runs without a GPU."""
+    import torch
+
+    from tests import offline
+    for seed, T, H, I in ((131, 7, 128, 320), (132, 1, 64, 192), (133, 21, 192, 448)):
+        m = offline.small_moe(seed=seed, T=T, H=H, I=I, E=2)
+        ex = m["experts"][1]
+        ref, mid_ref = oracle.cpu_expert_ffn(m["X"], m["s_in"], oracle.cpu_expert(ex), dumps=True)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+        h = haq.haq_cpu_expert_create(t(ex.w1), t(ex.w3), t(ex.w2), t(ex.sw1), t(ex.sw3), t(ex.sw2), t(ex.s_mid))
+        try:
+            for nt in (1, 3, 0):
+                y = haq.haq_cpu_expert_ffn(h, t(m["X"]), t(m["s_in"]), H, nt).numpy()
+                assert np.array_equal(y.view(np.uint16), ref.view(np.uint16)), (seed, nt)
+            y0 = haq.haq_cpu_expert_ffn(h, t(m["X"]), None, H, 2).numpy()
+            assert np.array_equal(y0.view(np.uint16), oracle.cpu_expert_ffn(m["X"], np.ones(H, np.float32), oracle.cpu_expert(ex)).view(np.uint16))
+        finally:
+            haq.haq_cpu_expert_destroy(h)

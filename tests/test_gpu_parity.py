@@ -746,3 +746,65 @@ def test_moe_asym_mixtral(layer, name):
     if "colsums" not in layer:
         layer["colsums"] = _colsums(layer["experts"])
     _check_moe_asym(_mixtral_case(wl, layer), layer["dev_experts"], layer["colsums"], np.arange(wl.T))
+
+
+# ------------------------------------------------------------------ offload policy: Eq. 7-8 decision and CPU experts
+def _cpu_handles(experts, ids):
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
+    return {e: haq.haq_cpu_expert_create(t(experts[e].w1), t(experts[e].w3), t(experts[e].w2), t(experts[e].sw1), t(experts[e].sw3),
+                                         t(experts[e].sw2), t(experts[e].s_mid)) for e in ids}
+
+
+@pytest.mark.parametrize("t_e,lat_cpu,lat_gpu", [(10.0, 1.0, 0.5), (3.0, 1.0, 0.9), (0.4, 1.0, 0.1), (5.0, 0.2, 0.5)])
+def test_offload_policy_decides_by_the_break_even_batch_and_cpu_experts_match_the_oracle(t_e, lat_cpu, lat_gpu):
+    """Host-resident experts with CPU copies: per activated expert the call must take the decision of Eq. 7-8
+    (n_inputs > n_critical -> transfer, else CPU; a cached expert stays on the GPU), and the layer output must be
+    the oracle's hybrid layer for exactly those experts, bit for bit."""
+    E, H, I = 8, 128, 320
+    m = offline.small_moe(seed=140, T=48, H=H, I=I, E=E, routing="popularity")
+    host_ids = (2, 3, 4, 5, 6, 7)
+    dev_experts = upload_experts(m["experts"])
+    mixed = _offload(dev_experts, host_ids)
+    handles = _cpu_handles(m["experts"], host_ids[:-1])       # expert 7 has no CPU copy: always transferred
+    ctx = haq.haq_ctx_create(H, I, 2)
+    try:
+        haq.haq_ctx_set_offload_policy(ctx, t_e, lat_cpu, lat_gpu, torch.from_numpy(m["s_in"]), 3)
+        for e, h in handles.items():
+            haq.haq_ctx_register_cpu_expert(ctx, mixed[e], h)
+        n_crit = oracle.n_critical(t_e, lat_cpu, lat_gpu)
+        X, logits, s_in = dev(m["X"]), dev(m["logits"]), dev(m["s_in"])
+        idx, gw = oracle.route_top2(m["logits"])
+        counts = np.bincount(idx.ravel(), minlength=E)
+        cached = set()
+        for call in range(2):
+            out = haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx)
+            torch.cuda.synchronize()
+            dec, nc = haq.haq_ctx_last_decisions(ctx)
+            assert nc == (-1 if n_crit is None else n_crit)
+            want, on_cpu = [], []
+            for e in host_ids:
+                if counts[e] == 0:
+                    continue
+                if e in cached:
+                    what = haq.HAQ_DECISION_GPU_CACHED
+                elif e in handles and (n_crit is None or counts[e] <= n_crit):
+                    what = haq.HAQ_DECISION_CPU
+                    on_cpu.append(e)
+                else:
+                    what = haq.HAQ_DECISION_TRANSFER
+                want.append((e, int(counts[e]), what))
+            assert dec == want, (call, dec, want)
+            ref, _ = oracle.moe_ffn_hybrid(m["X"], idx, gw, m["s_in"], m["experts"], on_cpu)
+            assert bits_equal(host(out), ref), f"call {call}: {diff_report(host(out), ref)}"
+            _, _, _, keys = haq.haq_ctx_cache_stats(ctx)
+            cached = {e for e in host_ids if mixed[e].w13.data_ptr() in keys[:2]}
+        # the rule switched off: everything is transferred again and the result is the all-GPU one
+        haq.haq_ctx_set_offload_policy(ctx, -1.0, 0.0, 0.0)
+        out = haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx)
+        assert bits_equal(host(out), host(haq.haq_moe_w8a8_ffn(X, logits, s_in, dev_experts, I)))
+        assert all(d[2] != haq.HAQ_DECISION_CPU for d in haq.haq_ctx_last_decisions(ctx)[0])
+    finally:
+        torch.cuda.synchronize()
+        haq.haq_ctx_destroy(ctx)
+        for h in handles.values():
+            haq.haq_cpu_expert_destroy(h)
