@@ -339,7 +339,8 @@ def build_mixtral(torch, haq, hi, keep_host=False):
     cal_logits = torch.from_numpy(hi.moe_logits(cal, hi.moe_hidden_states(cal))).to(dev)
     _, dbg = haq.haq_moe_w8a8_ffn(Xc, cal_logits, s_in, stage1, I, debug=True)
     offs = dbg.offsets.cpu().numpy()
-    experts = []
+    experts, canon = [], {}
+    cold = [e for e in range(E) if e not in hi.MIXTRAL_OFFLOAD.resident]
     for e in range(E):
         rows = dbg.mid_fp16[offs[e]:offs[e + 1]]
         ax_mid = haq.haq_channel_absmax_f16(rows) if rows.shape[0] else torch.zeros(I, dtype=torch.float32, device=dev)
@@ -347,9 +348,13 @@ def build_mixtral(torch, haq, hi, keep_host=False):
         w2q, sw2 = haq.haq_quant_weight(mats[(e, "w2")], s_mid)
         st = stage1[e]
         experts.append(haq.ExpertWeights(st.w13, haq.haq_pack_weight(w2q), st.sw1, st.sw3, sw2, s_mid))
+        if e in cold:  # canonical codes of the experts the offload workload keeps in host memory (for their CPU copies)
+            w1q, _ = haq.haq_quant_weight(mats[(e, "w1")], s_in)
+            w3q, _ = haq.haq_quant_weight(mats[(e, "w3")], s_in)
+            canon[e] = tuple(t.cpu().contiguous() for t in (w1q, w3q, w2q, st.sw1, st.sw3, sw2, s_mid))
     del mats, stage1, dbg
     torch.cuda.synchronize()
-    return {"s_in": s_in, "experts": experts, "host_mats": host_mats, "sets": None, "oracle": None}
+    return {"s_in": s_in, "experts": experts, "host_mats": host_mats, "sets": None, "oracle": None, "canon": canon}
 
 
 def oracle_mixtral(hi, host_mats=None):
@@ -409,7 +414,7 @@ def bench_moe(args, torch, haq, hi, workload, layer, cpu_seconds=10.0):
     counts = dbg.counts.cpu().numpy()
     prefill = workload == "moe_prefill"
     if workload == "moe_offload":
-        res = bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out)
+        res = bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out, layer.get("canon"))
     else:
         res = _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, counts, ws)
     if not args.no_cpu_baseline:
@@ -538,7 +543,66 @@ def _moe_cpu_baseline(ol, wl, X_h, logits_h, prefill, offload, seconds):
                       + (f"; scaled to {wl.T} tokens" if offload else "")}
 
 
-def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out):
+def _offload_policy(torch, haq, wl, X, logits, s_in, experts, mixed, cold, counts, canon, t_copy_per_expert, t_gpu_per_pair):
+    """Section III.C.1a-b on this machine: the cost model of Eq. 7-8 calibrated here (CPU latency per token of an expert on its
+    dequantised copy, GPU latency per pair, transfer time of one expert), the break-even batch, and the layer with the
+    rule in force: for this workload's batches, and for a single token (the decode case the paper argues from)."""
+    T, H, I = wl.T, wl.H, wl.I
+    handles = {e: haq.haq_cpu_expert_create(*canon[e]) for e in cold}
+    s_host = s_in.cpu()
+    e0 = cold[0]
+    x_host = X[:8].cpu()
+    lat = {}
+    for n in (1, 8):
+        haq.haq_cpu_expert_ffn(handles[e0], x_host[:n], s_host, H)
+        t0 = time.perf_counter()
+        for _ in range(3):
+            haq.haq_cpu_expert_ffn(handles[e0], x_host[:n], s_host, H)
+        lat[n] = (time.perf_counter() - t0) / 3
+    latency_cpu = lat[8] / 8
+    ctx = haq.haq_ctx_create(H, I, 2)
+    res = {"t_e_ms": t_copy_per_expert * 1e3, "latency_cpu_ms_per_token": latency_cpu * 1e3, "cpu_expert_ms": {"1_token": lat[1] * 1e3, "8_tokens": lat[8] * 1e3},
+           "latency_gpu_ms_per_token": t_gpu_per_pair * 1e3, "cpu_copy": "binary32, 12 H I bytes per expert"}
+    try:
+        haq.haq_ctx_set_offload_policy(ctx, t_copy_per_expert, latency_cpu, t_gpu_per_pair, s_host)
+        for e in cold:
+            haq.haq_ctx_register_cpu_expert(ctx, mixed[e], handles[e])
+        out = torch.empty((T, H), dtype=torch.float16, device=X.device)
+        ws = torch.empty(haq.haq_moe_workspace_bytes(T, H, I, wl.E), dtype=torch.uint8, device=X.device)
+
+        def timed(x, l, o, reps):
+            haq.haq_ctx_cache_invalidate(ctx)
+            haq.haq_moe_w8a8_ffn(x, l, s_in, mixed, I, ctx=ctx, out=o, workspace=ws)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                haq.haq_ctx_cache_invalidate(ctx)   # cold cache every call, as in the streamed measurement
+                haq.haq_moe_w8a8_ffn(x, l, s_in, mixed, I, ctx=ctx, out=o, workspace=ws)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        names = {0: "gpu_cached", 1: "transfer", 2: "cpu"}
+        ms = timed(X, logits, out, 5) * 1e3
+        dec, nc = haq.haq_ctx_last_decisions(ctx)
+        res.update(n_critical=nc, layer_ms=ms, decisions=[{"expert": e, "n_inputs": n, "decision": names[d]} for e, n, d in dec])
+        # one token routed to two host-resident experts (logits forced), with the rule and with plain transfers
+        l1 = torch.full((1, wl.E), -30.0, dtype=torch.float16, device=X.device)
+        l1[0, cold[0]], l1[0, cold[1]] = 5.0, 4.0
+        o1 = torch.empty((1, H), dtype=torch.float16, device=X.device)
+        ms1 = timed(X[:1], l1, o1, 5) * 1e3
+        dec1, _ = haq.haq_ctx_last_decisions(ctx)
+        haq.haq_ctx_set_offload_policy(ctx, -1.0, 0.0, 0.0)
+        ms1_t = timed(X[:1], l1, o1, 5) * 1e3
+        res["single_token_two_host_experts"] = {"with_rule_ms": ms1, "decisions": [names[d] for _, _, d in dec1], "always_transfer_ms": ms1_t}
+    finally:
+        torch.cuda.synchronize()
+        haq.haq_ctx_destroy(ctx)
+        for h in handles.values():
+            haq.haq_cpu_expert_destroy(h)
+    return res
+
+
+def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, out, canon=None):
     """4 of 8 experts resident; the others are streamed from pinned host memory on every call."""
     T, H, I, E = wl.T, wl.H, wl.I, wl.E
     cold = [e for e in range(E) if e not in wl.resident]
@@ -595,6 +659,11 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
     haq.haq_ctx_destroy(ctx4)
     streamed = sum(float(mixed[e].w13.numel() + mixed[e].w2.numel()) for e in cold if counts[e] > 0)
     resident_ms = t_all_resident * 1e3
+    policy = None
+    if canon:
+        n_streamed = max(1, sum(1 for e in cold if counts[e] > 0))
+        policy = _offload_policy(torch, haq, wl, X, logits, s_in, experts, mixed, cold, counts, canon, t_copy / n_streamed,
+                                 t_all_resident / float(counts.sum()))
     return {
         "metric": "MoE layer latency with 4 of 8 experts streamed from host (ms)", "value": sec * 1e3, "unit": "ms",
         "ms_per_step": sec * 1e3, "dtype": "int8", "higher_is_better": False,
@@ -607,6 +676,7 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
         "timeline_ms": {"call": total_ms, "first_copy_issued_to_last_copy_landed": copies_ms, "after_last_copy": tail_ms},
         "overlap_efficiency": min(1.0, max(0.0, (resident_ms - tail_ms) / resident_ms)),
         "matches_all_resident_bitwise": same and same_cached,
+        "offload_policy": policy,
         "lru_cache": {"slots_2": {"misses": misses2, "ms": sec * 1e3},
                       f"slots_{len(cold)}": {"hits": hits4, "misses": misses4, "ms": t_cached * 1e3}},
         "roofline": {"bound": "host link", "kernel": "hipMemcpyAsync pinned host to HBM", "achieved": streamed / sec / 1e9,
