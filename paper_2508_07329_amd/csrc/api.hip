@@ -592,13 +592,16 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         da.hq_rm = d.hq;
         da.sh = sh;
         da.y = y;
+        bool combined = false;
         if (tiny_path)
             rc = launch_decode_tiny(da, (const __half*)logits_fp16, ldl, (const __half*)x_fp16, ldx, s_in, T, tab, idx, gw, counts,
-                                    offsets, perm, inv, w.tab, st);
+                                    offsets, perm, inv, w.tab, (__half*)out_fp16, &combined, st);
         else
             rc = launch_decode(da, T, st);
         if (rc != HAQ_OK) return rc;
-        prof_mark(st, tiny_path ? "route + quantise + gate/up + requantise + down (2 launches)" : "gate/up + requantise + down (3 launches)");
+        prof_mark(st, combined ? "route + quantise + gate/up + requantise + down + combine (2 launches)"
+                  : tiny_path ? "route + quantise + gate/up + requantise + down (2 launches)" : "gate/up + requantise + down (3 launches)");
+        if (combined) return HAQ_OK;
         rc = launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
         prof_mark(st, "combine");
         return rc;

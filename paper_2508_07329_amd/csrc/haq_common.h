@@ -192,10 +192,11 @@ bool decode_supported(int T, int H, int I);
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st);
 // One or two tokens: two launches do routing, token quantisation, both projections and the
 // requantisation between them (q_cm, sx, hq_cm, hq_rm and sh of `a` are not used); the routing
-// results are written for the combination that follows.
+// results are written for the combination that follows.  With one token the second launch also
+// forms the combination into `out` (*combined = true: the caller launches no combine kernel).
 bool decode_tiny_supported(int T, int H, int I);
 int launch_decode_tiny(const DecodeArgs& a, const __half* logits, int64_t ldl, const __half* x, int64_t ldx, const float* s, int T,
                        const ExpertTab* tab_host, int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm,
-                       int32_t* inv, ExpertTab* tab_dev, hipStream_t st);
+                       int32_t* inv, ExpertTab* tab_dev, __half* out, bool* combined, hipStream_t st);
 
 }  // namespace haq
