@@ -129,6 +129,9 @@ def _mfma_ceiling(torch, haq, data, work_groups, seconds):
         launch()
     side = torch.cuda.Stream()
     clk = torch.zeros((2,), dtype=torch.int64, device=data.device)
+    torch.cuda.synchronize()  # the fill above is on this stream; the probe writes from another one
+    for _ in range(max(1, n // 6)):
+        launch()
     ev[0].record()
     for _ in range(n):
         launch()

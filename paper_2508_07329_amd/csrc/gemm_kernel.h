@@ -118,7 +118,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     constexpr bool ASYM = EPI == EPI_LINEAR_ASYM || EPI == EPI_SWIGLU_ASYM;
     static_assert(!SWIGLU || NI % 2 == 0, "gate/up blocks come in pairs");
     constexpr int OUT_WN = SWIGLU ? WN / 2 : WN;  // output channels per wave tile
-    constexpr int PITCH = OUT_WN * 2 + 16;                     // staged fp16 row pitch in bytes
+    // staged fp16 row pitch in bytes: 2 (mod 64) dwords, so the 8-byte pieces that the 32 rows of a half-wave
+    // write land in 32 different bank pairs (a pitch of 4 (mod 64) dwords costs 6 conflict cycles per write)
+    constexpr int PITCH = OUT_WN * 2 + 8;
     static_assert(32 * PITCH * NW <= STAGES * STAGE_BYTES, "epilogue staging must fit in the ring");
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     float* sx_s = reinterpret_cast<float*>(lds + STAGES * STAGE_BYTES);  // [BM] row scales of the tile
@@ -390,7 +392,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
             const int r2 = it * ROWS_PER_IT + lane / LANES_PER_ROW;
             const int c8 = (lane % LANES_PER_ROW) * 8;
             const int orow = tc.m0 + wm * WM + i * 32 + r2, ocol = out_n0 + c8;
-            const uint4 v = *reinterpret_cast<const uint4*>(stage + r2 * PITCH + c8 * 2);
+            const uint2 v0 = *reinterpret_cast<const uint2*>(stage + r2 * PITCH + c8 * 2);  // rows are 8-byte aligned
+            const uint2 v1 = *reinterpret_cast<const uint2*>(stage + r2 * PITCH + c8 * 2 + 8);
+            const uint4 v = make_uint4(v0.x, v0.y, v1.x, v1.y);
             if (orow < tc.m_end && ocol < out_n) *reinterpret_cast<uint4*>(a.Y + (size_t)orow * a.ldy + ocol) = v;
         }
         HAQ_CFENCE();
