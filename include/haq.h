@@ -19,7 +19,10 @@
  *  - Arguments are validated on the host before any HIP call.  Return value:
  *    HAQ_OK or a negative HAQ_ERR_*; haq_last_error() gives a thread-local text.
  *  - Device pointers must be 16-byte aligned; leading dimensions are in
- *    elements; K (the contracted dimension) must be a multiple of 64.
+ *    elements; the contracted dimension K must be a multiple of 16 for the dense
+ *    calls (the packed layouts round it up to whole 64-byte k-steps and keep the
+ *    pad of the weights at zero) and of 64 for the expert FFN and the offline
+ *    search / Hessian tools.
  *  - Arithmetic is IEEE binary32 with one rounding per operation, int32
  *    accumulation, round-half-to-even; results do not depend on launch shape.
  */
@@ -54,7 +57,7 @@ const char* haq_last_error(void); /* host string, valid until the thread's next 
  *   q = clamp(rne(y / scale_t), -127, 127).   A zero row gives scale 0, codes 0.
  * x_fp16 [T x K] row-major (row stride ldx), s [K] (> 0, finite) or NULL for all
  * ones.  Outputs q int8 [T x K] (row stride ldq) and row_scale [T].
- * T >= 0 (T == 0 is a no-op), K % 64 == 0, K <= 65536.
+ * T >= 0 (T == 0 is a no-op), K % 16 == 0, K <= 65536.
  */
 int32_t haq_smooth_quant_act(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K,
                              int8_t* q, int64_t ldq, float* row_scale, void* stream);
@@ -82,9 +85,10 @@ int32_t haq_quant_weight(const float* w, const float* s, int32_t K, int32_t N, i
  * Weight layout for the MFMA kernels (offline, Algorithm 1 step 3 keeps int8
  * weights on the GPU in the form its kernels consume).
  *
- * Packed layout of a [K x N] int8 matrix: [K/16][Npad][16] - for each group of
+ * Packed layout of a [K x N] int8 matrix: [Kpad/16][Npad][16] - for each group of
  * 16 consecutive input channels, all output channels side by side, each with its
- * 16 bytes.  Npad = N rounded up to a multiple of 256; padding is zero.
+ * 16 bytes.  Npad = N rounded up to a multiple of 256, Kpad = K rounded up to a
+ * multiple of 64; padding is zero.  K % 16 == 0 (haq_pack_gate_up: K % 64 == 0).
  * haq_packed_bytes(K, N) gives the size.  haq_pack_weight converts the canonical
  * row-major [K x N] matrix.  haq_pack_gate_up interleaves the gate (w1) and up
  * (w3) matrices of a SwiGLU expert, both [K x N], into one packed [K x 2N]
@@ -102,16 +106,17 @@ int32_t haq_pack_gate_up(const int8_t* w1q, const int8_t* w3q, int32_t K, int32_
  * x_fp16 [T x K], s [K] or NULL, w_packed from haq_pack_weight, w_scale [N].
  * Y fp16 [T x N] (row stride ldy).  Optional outputs (NULL to skip): acc_dbg
  * int32 [T x N] dense, q_dbg int8 [T x K] dense, sx_dbg [T].
- * T >= 0, K % 64 == 0, N % 16 == 0.
+ * T >= 0, K % 16 == 0, N % 16 == 0.
  */
 size_t haq_linear_workspace_bytes(int32_t T, int32_t K, int32_t N);
 
 /* The two stages of haq_w8a8_linear as calls of their own (same kernels, same
  * results), for callers that keep activations in int8 between layers or time the
  * stages separately.  The packed activation layout is that of the weights:
- * [K/16][R][16] with R = haq_packed_act_rows(T) rows (T rounded up to 16, plus
- * one 256-row tile of slack that the GEMM may read but never uses); its size is
- * haq_packed_act_bytes(T, K) = K * R.
+ * [Kpad/16][R][16] with R = haq_packed_act_rows(T) rows (T rounded up to 16, plus
+ * one 256-row tile of slack that the GEMM may read but never uses) and Kpad = K
+ * rounded up to 64 (chunks past K are never written; the weights are zero there);
+ * its size is haq_packed_act_bytes(T, K) = Kpad * R.
  * haq_quant_act_packed: Q(s^-1 X) as in haq_smooth_quant_act, codes written in
  *   the packed layout.  haq_gemm_w8a8_packed: int8 GEMM + dequantise + activation
  *   on such codes; row_scale [T], y fp16 [T x N]; acc_dbg optional.            */
@@ -127,6 +132,15 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
                         int64_t ldy, int32_t* acc_dbg, int8_t* q_dbg, float* sx_dbg, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/* The same layer on weights in the canonical layout of Eq. 1's weight operand as the offline
+ * quantiser emits it: wq_kn int8 [K x N] row-major (input channel major).  The call packs the
+ * matrix into its workspace first (one extra pass over the weights per call: the run-time
+ * path proper takes pre-packed weights), then runs haq_w8a8_linear; same results.            */
+size_t haq_linear_kn_workspace_bytes(int32_t T, int32_t K, int32_t N);
+int32_t haq_w8a8_linear_kn(const void* x_fp16, int64_t ldx, const float* s, const int8_t* wq_kn, const float* w_scale,
+                           int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * The linear layer with ASYMMETRIC activation codes (the quantisation mode the
  * paper's experimental setup, Section IV.A, names as its default); the weight
@@ -140,7 +154,7 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
  * (128 - zp_t) * colsum[n] to the accumulator, colsum[n] = sum_k Wq[k][n] from
  * haq_weight_colsum (offline, int32 [N], device).
  * Optional outputs: acc_dbg int32 [T x N] (corrected accumulators), q_dbg uint8
- * [T x K] dense codes, sx_dbg [T], zp_dbg int32 [T].  K % 64 == 0, K <= 16384,
+ * [T x K] dense codes, sx_dbg [T], zp_dbg int32 [T].  K % 16 == 0, K <= 16384,
  * N % 16 == 0.                                                                */
 int32_t haq_weight_colsum(const int8_t* wq, int32_t K, int32_t N, int32_t* colsum, void* stream);
 size_t haq_linear_asym_workspace_bytes(int32_t T, int32_t K, int32_t N);
@@ -156,7 +170,7 @@ int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, co
  * Results are identical to two haq_w8a8_linear calls; the block call keeps H and
  * both sets of int8 codes in one workspace.  X [T x K], W1 packed
  * [K x F], W2 packed [F x N]; h_dbg optional fp16 [T x F] dense copy of H.
- * K % 64 == 0, F % 64 == 0, N % 16 == 0.                                     */
+ * K % 16 == 0, F % 16 == 0, N % 16 == 0.                                     */
 size_t haq_ffn_workspace_bytes(int32_t T, int32_t K, int32_t F, int32_t N);
 int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int8_t* w1_packed, const float* w1_scale,
                      int32_t act, const float* s2, const int8_t* w2_packed, const float* w2_scale, int32_t T,

@@ -23,6 +23,7 @@ __all__ = [
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
+    "haq_linear_kn_workspace_bytes", "haq_w8a8_linear_kn",
     "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
@@ -47,6 +48,7 @@ EXPORTED_SYMBOLS = [
     "haq_smoothing_search_workspace_bytes", "haq_reference_matmul_f64", "haq_quant_loss_f64", "haq_smoothing_search",
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
+    "haq_linear_kn_workspace_bytes", "haq_w8a8_linear_kn",
     "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
@@ -86,7 +88,7 @@ def lib() -> C.CDLL:
         for n in ("haq_packed_bytes", "haq_linear_workspace_bytes", "haq_moe_workspace_bytes", "haq_packed_act_bytes",
                   "haq_ffn_workspace_bytes", "haq_smoothing_search_workspace_bytes", "haq_hessian_quant_workspace_bytes",
                   "haq_inverse_cholesky_workspace_bytes", "haq_linear_asym_workspace_bytes",
-                  "haq_quantize_layer_workspace_bytes", "haq_moe_asym_workspace_bytes"):
+                  "haq_quantize_layer_workspace_bytes", "haq_moe_asym_workspace_bytes", "haq_linear_kn_workspace_bytes"):
             getattr(L, n).restype = C.c_size_t
         L.haq_packed_act_rows.restype = C.c_int64
         _lib = L
@@ -199,6 +201,22 @@ def haq_w8a8_linear(x, s, w_packed, w_scale, N: int, act: int = HAQ_ACT_NONE, *,
                                  _ptr(y), C.c_int64(y.stride(0)), _ptr(acc), _ptr(q), _ptr(sx), _ptr(workspace),
                                  C.c_size_t(workspace.numel()), _stream()))
     return (y, acc, q, sx) if debug else y
+
+
+def haq_linear_kn_workspace_bytes(T: int, K: int, N: int) -> int:
+    return int(lib().haq_linear_kn_workspace_bytes(T, K, N))
+
+
+def haq_w8a8_linear_kn(x, s, wq_kn, w_scale, act: int = HAQ_ACT_NONE, *, out=None, workspace=None):
+    """x fp16 [T,K], canonical int8 weights wq_kn [K,N] (packed per call into the workspace) -> y fp16 [T,N]."""
+    T, K = x.shape
+    N = wq_kn.shape[1]
+    y = out if out is not None else torch.empty((T, N), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = _ws(haq_linear_kn_workspace_bytes(T, K, N), x.device)
+    _check(lib().haq_w8a8_linear_kn(_ptr(x), C.c_int64(x.stride(0)), _ptr(s), _ptr(wq_kn), _ptr(w_scale), T, K, N, act, _ptr(y),
+                                    C.c_int64(y.stride(0)), _ptr(workspace), C.c_size_t(workspace.numel()), _stream()))
+    return y
 
 
 def haq_packed_act_rows(T: int) -> int:

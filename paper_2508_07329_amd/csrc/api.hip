@@ -49,7 +49,7 @@ LinearWs carve_linear(void* ws, int T, int K) {
     Carver c(ws);
     LinearWs w;
     w.R = padded_rows(T);
-    w.q_cm = c.take<int8_t>((size_t)K * w.R);
+    w.q_cm = c.take<int8_t>((size_t)round_up(K, 64) * w.R);  // whole 64-byte k-steps (the pad is never written, its weights are zero)
     w.sx = c.take<float>((size_t)T);
     w.bytes = c.off;
     return w;
@@ -65,8 +65,8 @@ FfnWs carve_ffn(void* ws, int T, int K, int F) {
     Carver c(ws);
     FfnWs w;
     const int64_t R = padded_rows(T);
-    w.q1 = c.take<int8_t>((size_t)K * R);
-    w.q2 = c.take<int8_t>((size_t)F * R);
+    w.q1 = c.take<int8_t>((size_t)round_up(K, 64) * R);
+    w.q2 = c.take<int8_t>((size_t)round_up(F, 64) * R);
     w.sx1 = c.take<float>((size_t)T);
     w.sx2 = c.take<float>((size_t)T);
     w.h = c.take<__half>((size_t)T * F);
@@ -268,8 +268,8 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
                         int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg,
                         int8_t* q_dbg, float* sx_dbg, void* workspace, size_t workspace_bytes, void* stream) {
     if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: T=%d K=%d N=%d", T, K, N);
-    if (K % 64 != 0 || K > 65536 || N % 16 != 0)
-        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: K=%d must be a multiple of 64 (<= 65536), N=%d of 16", K, N);
+    if (K % 16 != 0 || K > 65536 || N % 16 != 0)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: K=%d must be a multiple of 16 (<= 65536), N=%d of 16", K, N);
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear: null buffer");
@@ -288,6 +288,28 @@ int32_t haq_w8a8_linear(const void* x_fp16, int64_t ldx, const float* s, const i
     return gemm_packed(w.q_cm, w.sx, w_packed, w_scale, T, K, N, act, y_fp16, ldy, acc_dbg, st);
 }
 
+size_t haq_linear_kn_workspace_bytes(int32_t T, int32_t K, int32_t N) {
+    if (T < 0 || K <= 0 || N <= 0) return 0;
+    return carve_linear(nullptr, T, K).bytes + (size_t)round_up((int64_t)haq_packed_bytes(K, N), 256);
+}
+
+int32_t haq_w8a8_linear_kn(const void* x_fp16, int64_t ldx, const float* s, const int8_t* wq_kn, const float* w_scale, int32_t T,
+                           int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_kn: T=%d K=%d N=%d", T, K, N);
+    if (K % 16 != 0 || K > 65536 || N % 16 != 0)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_kn: K=%d must be a multiple of 16 (<= 65536), N=%d of 16", K, N);
+    if (T == 0) return HAQ_OK;
+    if (!wq_kn) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_kn: null buffer");
+    const size_t lin = carve_linear(nullptr, T, K).bytes, need = haq_linear_kn_workspace_bytes(T, K, N);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u))
+        HAQ_FAIL(HAQ_ERR_WORKSPACE, "haq_w8a8_linear_kn: workspace of %zu bytes (256-byte aligned) needed, got %zu", need, workspace_bytes);
+    int8_t* packed = (int8_t*)workspace + lin;
+    const int rc = haq_pack_weight(wq_kn, K, N, packed, stream);
+    if (rc != HAQ_OK) return rc;
+    return haq_w8a8_linear(x_fp16, ldx, s, packed, w_scale, T, K, N, act, y_fp16, ldy, nullptr, nullptr, nullptr, workspace, lin, stream);
+}
+
 size_t haq_linear_asym_workspace_bytes(int32_t T, int32_t K, int32_t N) {
     (void)N;
     if (T < 0 || K <= 0) return 0;
@@ -299,8 +321,8 @@ int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, co
                              int64_t ldy, int32_t* acc_dbg, uint8_t* q_dbg, float* sx_dbg, int32_t* zp_dbg, void* workspace,
                              size_t workspace_bytes, void* stream) {
     if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: T=%d K=%d N=%d", T, K, N);
-    if (K % 64 != 0 || K > 16384 || N % 16 != 0)
-        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: K=%d must be a multiple of 64 (<= 16384), N=%d of 16", K, N);
+    if (K % 16 != 0 || K > 16384 || N % 16 != 0)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: K=%d must be a multiple of 16 (<= 16384), N=%d of 16", K, N);
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !w_packed || !w_scale || !w_colsum || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_linear_asym: null buffer");
@@ -349,8 +371,8 @@ int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int
                      int32_t F, int32_t N, void* y_fp16, int64_t ldy, void* h_dbg_fp16, void* workspace,
                      size_t workspace_bytes, void* stream) {
     if (T < 0 || K <= 0 || F <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: T=%d K=%d F=%d N=%d", T, K, F, N);
-    if (K % 64 != 0 || F % 64 != 0 || N % 16 != 0 || K > 65536 || F > 65536)
-        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_ffn: K=%d and F=%d must be multiples of 64 (<= 65536), N=%d of 16", K, F, N);
+    if (K % 16 != 0 || F % 16 != 0 || N % 16 != 0 || K > 65536 || F > 65536)
+        HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_ffn: K=%d and F=%d must be multiples of 16 (<= 65536), N=%d of 16", K, F, N);
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_ffn: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !w1_packed || !w1_scale || !w2_packed || !w2_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_w8a8_ffn: null buffer");
@@ -379,12 +401,12 @@ int32_t haq_w8a8_ffn(const void* x_fp16, int64_t ldx, const float* s1, const int
 }
 
 int64_t haq_packed_act_rows(int32_t T) { return T < 0 ? 0 : padded_rows(T); }
-size_t haq_packed_act_bytes(int32_t T, int32_t K) { return (T < 0 || K <= 0) ? 0 : (size_t)K * (size_t)padded_rows(T); }
+size_t haq_packed_act_bytes(int32_t T, int32_t K) { return (T < 0 || K <= 0) ? 0 : (size_t)round_up(K, 64) * (size_t)padded_rows(T); }
 
 int32_t haq_quant_act_packed(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K, int8_t* q_packed,
                              float* row_scale, void* stream) {
     if (T < 0 || K <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: T=%d K=%d", T, K);
-    if (K % 64 != 0 || K > 65536) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_quant_act_packed: K=%d must be a multiple of 64, <= 65536", K);
+    if (K % 16 != 0 || K > 65536) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_quant_act_packed: K=%d must be a multiple of 16, <= 65536", K);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !q_packed || !row_scale) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: null buffer");
     if (ldx < K || ldx % 8 != 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_quant_act_packed: ldx=%lld", (long long)ldx);
@@ -397,7 +419,7 @@ int32_t haq_gemm_w8a8_packed(const int8_t* q_packed, const float* row_scale, con
                              int32_t T, int32_t K, int32_t N, int32_t act, void* y_fp16, int64_t ldy, int32_t* acc_dbg,
                              void* stream) {
     if (T < 0 || K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: T=%d K=%d N=%d", T, K, N);
-    if (K % 64 != 0 || N % 16 != 0) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: K=%d must be a multiple of 64, N=%d of 16", K, N);
+    if (K % 16 != 0 || N % 16 != 0) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: K=%d must be a multiple of 16, N=%d of 16", K, N);
     if (act != HAQ_ACT_NONE && act != HAQ_ACT_RELU) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_gemm_w8a8_packed: act=%d", act);
     if (T == 0) return HAQ_OK;
     if (!q_packed || !row_scale || !w_packed || !w_scale || !y_fp16) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_gemm_w8a8_packed: null buffer");

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int nkt = a.K / 64;
+    const int nkt = (a.K + 63) / 64;  // a last partial k-step reads chunks past K: the weight operand is zero there
 
     // tile scales into LDS (consumed only by the epilogue)
     for (int i = tid; i < BM; i += S::THREADS) {

@@ -802,7 +802,7 @@ __global__ void pack_kernel(const int8_t* w1, const int8_t* w3, int K, int Nsrc,
     const int kc = blockIdx.y;
     if (n >= Npad) return;
     uint32_t wv[4] = {0, 0, 0, 0};
-    if (n < Nout) {
+    if (n < Nout && kc * 16 < K) {  // chunks past K (the pad up to a whole 64-byte k-step) stay zero
         const int8_t* src = w1;
         int col = n;
         if (w3) {
@@ -917,7 +917,7 @@ extern "C" {
 int32_t haq_smooth_quant_act(const void* x_fp16, int64_t ldx, const float* s, int32_t T, int32_t K, int8_t* q,
                              int64_t ldq, float* row_scale, void* stream) {
     if (T < 0 || K <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_smooth_quant_act: T=%d K=%d", T, K);
-    if (K % 64 != 0 || K > 65536) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_smooth_quant_act: K=%d must be a multiple of 64, <= 65536", K);
+    if (K % 16 != 0 || K > 65536) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_smooth_quant_act: K=%d must be a multiple of 16, <= 65536", K);
     if (T == 0) return HAQ_OK;
     if (!x_fp16 || !q || !row_scale) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_smooth_quant_act: null buffer");
     if (ldx < K || ldq < K || ldx % 8 != 0 || ldq % 16 != 0)
@@ -979,15 +979,15 @@ int32_t haq_weight_colsum(const int8_t* wq, int32_t K, int32_t N, int32_t* colsu
 
 size_t haq_packed_bytes(int32_t K, int32_t N) {
     if (K <= 0 || N <= 0) return 0;
-    return (size_t)K * (size_t)round_up(N, NPAD);
+    return (size_t)round_up(K, 64) * (size_t)round_up(N, NPAD);
 }
 
 int32_t haq_pack_weight(const int8_t* wq, int32_t K, int32_t N, int8_t* packed, void* stream) {
     if (K <= 0 || N <= 0) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_pack_weight: K=%d N=%d", K, N);
-    if (K % 64 != 0 || K / 16 > 65535) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_pack_weight: K=%d must be a multiple of 64", K);
+    if (K % 16 != 0 || K / 16 > 65532) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_pack_weight: K=%d must be a multiple of 16", K);
     if (!wq || !packed || !aligned16(packed)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_pack_weight: null or misaligned buffer");
     const int Npad = (int)round_up(N, NPAD);
-    hipLaunchKernelGGL(pack_kernel, dim3(Npad / 256, K / 16), dim3(256), 0, (hipStream_t)stream, wq,
+    hipLaunchKernelGGL(pack_kernel, dim3(Npad / 256, (unsigned)(round_up(K, 64) / 16)), dim3(256), 0, (hipStream_t)stream, wq,
                        (const int8_t*)nullptr, K, N, N, Npad, packed);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;

@@ -140,6 +140,37 @@ def test_linear_ragged_shapes(T, K, N, act):
     _linear_case(X, hi.gaussian_weight(T + K, 0, K, N), act)
 
 
+@pytest.mark.parametrize("T,K,N,act", [(37, 80, 48, "relu"), (300, 1040, 272, "none"), (5, 16, 16, "none"), (2051, 4112, 64, "relu")])
+def test_linear_input_widths_that_are_not_whole_k_steps(T, K, N, act):
+    """K a multiple of 16 but not of 64: the packed operands round K up, the pad of the weights is zero and whatever the
+    activation buffer holds there drops out.  The workspace is filled with a non-zero pattern first."""
+    X, _, _ = hi.hidden_states(T + K, T, K, n_outlier=2)
+    W = hi.gaussian_weight(T + K, 0, K, N)
+    s, Wq, sw = offline.quantize_linear(X, W)
+    Y_ref, acc_ref, q_ref, sx_ref = oracle.w8a8_linear(X, s, Wq, sw, act, full=True)
+    ws = torch.full((haq.haq_linear_workspace_bytes(T, K, N),), 0x5B, dtype=torch.uint8, device="cuda:0")
+    y, acc, q, sx = haq.haq_w8a8_linear(dev(X), dev(s), haq.haq_pack_weight(dev(Wq)), dev(sw), N, oracle.ACT[act], workspace=ws, debug=True)
+    assert bits_equal(host(q), q_ref) and bits_equal(host(sx), sx_ref) and bits_equal(host(acc), acc_ref)
+    assert bits_equal(host(y), Y_ref)
+    # the call that takes the canonical [K x N] layout of the weight operand
+    ws2 = torch.full((haq.haq_linear_kn_workspace_bytes(T, K, N),), 0x5B, dtype=torch.uint8, device="cuda:0")
+    assert bits_equal(host(haq.haq_w8a8_linear_kn(dev(X), dev(s), dev(Wq), dev(sw), oracle.ACT[act], workspace=ws2)), Y_ref)
+    q2, sx2 = haq.haq_smooth_quant_act(dev(X), dev(s))
+    assert bits_equal(host(q2), q_ref) and bits_equal(host(sx2), sx_ref)
+
+
+def test_ffn_widths_that_are_not_whole_k_steps():
+    T, K, F, N = 130, 208, 304, 80
+    X, _, _ = hi.hidden_states(9, T, K, n_outlier=2)
+    W1, W2 = hi.gaussian_weight(9, 0, K, F), hi.gaussian_weight(9, 1, F, N)
+    (s1, W1q, sw1), (s2, W2q, sw2) = offline.quantize_ffn(X, W1, W2)
+    h_ref = oracle.w8a8_linear(X, s1, W1q, sw1, "relu")
+    y_ref = oracle.w8a8_linear(h_ref, s2, W2q, sw2, "none")
+    y, h = haq.haq_w8a8_ffn(dev(X), dev(s1), haq.haq_pack_weight(dev(W1q)), dev(sw1), F, haq.HAQ_ACT_RELU, dev(s2),
+                            haq.haq_pack_weight(dev(W2q)), dev(sw2), N, debug=True)
+    assert bits_equal(host(h), h_ref) and bits_equal(host(y), y_ref)
+
+
 def test_linear_extreme_accumulators():
     K = 16384
     X = np.full((3, K), 127, np.float16)
