@@ -270,7 +270,14 @@ int32_t haq_quantize_layer(const void* x_fp16, int64_t ldx, int32_t T, const flo
                            size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
- * Top-2 routed SwiGLU expert FFN with W8A8 experts.
+ * Top-2 routed SwiGLU expert FFN with W8A8 experts: Eq. 1 (Section III.B.1)
+ * applied to every linear of an expert, experts kept in int8 on the GPU (Section
+ * III.B.3), "the gating network selects" which experts a token visits (Section
+ * III.C.1b), two per layer (an activation path holds 2 experts per layer: Section
+ * III.C.2, stage 1 of the proposed strategy), and host-resident experts move to
+ * the GPU in their low-bit form through an expert cache (Section III.C.1c).  The
+ * paper names neither the gate normalisation nor the expert's activation; they
+ * are those of the Mixtral-style layers its experiments run on.
  *
  * Per token t: top-2 experts by router logit (lowest index wins ties); gate
  * weights = softmax over all E logits, renormalised over the two.  The token is
@@ -433,7 +440,11 @@ size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
  * H % 64 == 0, I % 64 == 0.  Host-resident experts that the call activates and
  * the context's cache does not hold are copied into its slots with
  * hipMemcpyAsync on its side stream while resident experts compute; results
- * are identical to the all-resident call.
+ * are identical to the all-resident call.  With host-resident experts the call
+ * is NOT asynchronous: it waits on the host for the routing histogram (which
+ * experts are activated decides what is copied; one small device-to-host copy),
+ * and, when the offload policy sends experts to the CPU, for their computation;
+ * everything else of the call is enqueued as usual.
  * Launch shapes (same results on every path): more than 64 tokens or any
  * host-resident expert -> grouped tiled GEMMs; up to 64 tokens, all experts
  * resident, H % 128 == 0 and I % 256 == 0 -> weight-streaming kernels (five
