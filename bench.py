@@ -17,9 +17,9 @@ routing), in decode (1, 8, 64 tokens: HBM GB/s and tokens/s) and with 4 of 8
 experts streamed from host memory; the Mixtral layer is built once for all of them.
 
 Single workloads (--workload): ffn, linear, moe_prefill, moe_decode_b1 / _b8 /
-_b64, moe_offload, and smooth_search and hessian_quant (the offline grid search
-of the smoothing exponent and the Hessian-aware weight quantiser, on fc1 of the
-default block).
+_b64, moe_offload, smooth_search and hessian_quant (the offline grid search of
+the smoothing exponent and the Hessian-aware weight quantiser, on fc1 of the
+default block), and gemm_sweep (the GEMM stage alone over shapes, K and rows).
 """
 from __future__ import annotations
 
@@ -49,7 +49,7 @@ QUANT_VALU_PER_ELEMENT = 24.0
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
 # of the committed summary profiles/gemm_i8_kernel__opt6.7b_ffn.md and only applies to that workload.
-GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.856e+08
+GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.77e+08
 # The same for one call of the decode layer (all its kernels; reads only, the writes are a few MB), from
 # profiles/decode_kernels__mixtral_decode.md: within 0.3-2 % of the algorithmic weight bytes.
 DECODE_TRAFFIC_BYTES = {"moe_decode_b1": 3.55e+08, "moe_decode_b8": 1.063e+09, "moe_decode_b64": 1.440e+09}
@@ -690,6 +690,46 @@ def bench_offload(args, torch, haq, wl, X, logits, s_in, experts, counts, ws, ou
     }
 
 
+def bench_gemm_sweep(args, torch, haq, hi):
+    """haq_gemm_w8a8_packed over shapes of equal work, over K, and over the row count (events around 200 launches each):
+    separates the K-loop rate from the fixed cost of a round of tiles and shows what operand footprints do."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev).manual_seed(0)
+
+    def run(T, K, N, reps=200):
+        x = torch.randn((T, K), device=dev, generator=g).half()
+        x[:, :20] *= 50
+        wq = torch.clamp((torch.randn((K, N), device=dev, generator=g) * 30).round(), -127, 127).to(torch.int8)
+        wp, sw = haq.haq_pack_weight(wq), torch.full((N,), 1e-3, device=dev)
+        q, sx = haq.haq_quant_act_packed(x, None)
+        y = torch.empty((T, N), dtype=torch.float16, device=dev)
+        f = lambda: haq.haq_gemm_w8a8_packed(q, sx, wp, sw, T, K, N, haq.HAQ_ACT_NONE, out=y)
+        _settle(torch, f, 0.3)
+        ev = _events(torch, 2)
+        ev[0].record()
+        for _ in range(reps):
+            f()
+        ev[1].record()
+        torch.cuda.synchronize()
+        us = ev[0].elapsed_time(ev[1]) / reps * 1e3
+        return {"T": T, "K": K, "N": N, "us": us, "TOPs": 2.0 * T * K * N / us / 1e6}
+
+    shapes = [(1024, 4096, 16384), (4096, 4096, 4096), (2048, 4096, 8192), (8192, 4096, 2048), (16384, 4096, 1024)]
+    ksweep = [(4096, k, 4096) for k in (1024, 2048, 4096, 8192, 16384)]
+    rows = [(t, 4096, 16384) for t in (256, 512, 1024, 2048, 4096, 8192)]
+    t0 = time.perf_counter()
+    res = {"equal_work": [run(*s) for s in shapes], "k_sweep": [run(*s) for s in ksweep], "row_sweep": [run(*s) for s in rows]}
+    k = res["k_sweep"]
+    slope = (k[-1]["us"] - k[-2]["us"]) / (k[-1]["K"] - k[-2]["K"])   # us per unit of K in one round of 512 tiles
+    res["k_loop_TOPs"] = 2.0 * 4096 * 4096 / slope / 1e6
+    res["fixed_us_per_round"] = k[0]["us"] - slope * k[0]["K"]
+    best = max(r["TOPs"] for v in (res["equal_work"], res["k_sweep"], res["row_sweep"]) for r in v)
+    return {"metric": "int8 GEMM + epilogue TOPS over a shape sweep (best)", "value": best, "unit": "TOPS",
+            "ms_per_step": (time.perf_counter() - t0) * 1e3, "dtype": "int8", "config": {"workload": "gemm_sweep"},
+            "sweep": res, "roofline": {"bound": "mfma", "achieved": best, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                                       "frac": best / PEAK_INT8_TOPS, "traffic": None}, "cpu_baseline": None}
+
+
 def bench_search(args, torch, haq, hi):
     """Adaptive smoothing (Algorithm 1 step 1): 11 exponents on fc1 of the OPT-6.7B-shaped block."""
     wl = hi.OPT67B_FFN
@@ -804,7 +844,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="all",
-                    choices=["all", "ffn", "linear", *MOE_WORKLOADS, "smooth_search", "hessian_quant"],
+                    choices=["all", "ffn", "linear", *MOE_WORKLOADS, "smooth_search", "hessian_quant", "gemm_sweep"],
                     help="all (default): the OPT-6.7B FFN block as the headline plus one record per other configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-clock peak and the pure-MFMA ceiling (2.5 s)")
@@ -837,6 +877,8 @@ def main():
         res = bench_search(args, torch, haq, hi)
     elif args.workload == "hessian_quant":
         res = bench_hessian(args, torch, haq, hi)
+    elif args.workload == "gemm_sweep":
+        res = bench_gemm_sweep(args, torch, haq, hi)
     else:
         res = bench_moe(args, torch, haq, hi, args.workload, build_mixtral(torch, haq, hi, keep_host=not args.no_cpu_baseline))
     line = _record(res, args)
