@@ -333,12 +333,13 @@ def build_mixtral(torch, haq, hi, keep_host=False):
         haq.haq_weight_row_absmax(mats[(e, "w3")], aw)
     s_in = haq.haq_smoothing_vector(ax, aw, 0.5)
     ones = torch.ones(I, dtype=torch.float32, device=dev)
-    stage1 = []
+    stage1, cs13, colsums = [], [], []
     for e in range(E):
         w1q, sw1 = haq.haq_quant_weight(mats[(e, "w1")], s_in)
         w3q, sw3 = haq.haq_quant_weight(mats[(e, "w3")], s_in)
         w2q, sw2 = haq.haq_quant_weight(mats[(e, "w2")], None)
         stage1.append(haq.ExpertWeights(haq.haq_pack_gate_up(w1q, w3q), haq.haq_pack_weight(w2q), sw1, sw3, sw2, ones))
+        cs13.append((haq.haq_weight_colsum(w1q), haq.haq_weight_colsum(w3q)))
     cal_logits = torch.from_numpy(hi.moe_logits(cal, hi.moe_hidden_states(cal))).to(dev)
     _, dbg = haq.haq_moe_w8a8_ffn(Xc, cal_logits, s_in, stage1, I, debug=True)
     offs = dbg.offsets.cpu().numpy()
@@ -351,13 +352,15 @@ def build_mixtral(torch, haq, hi, keep_host=False):
         w2q, sw2 = haq.haq_quant_weight(mats[(e, "w2")], s_mid)
         st = stage1[e]
         experts.append(haq.ExpertWeights(st.w13, haq.haq_pack_weight(w2q), st.sw1, st.sw3, sw2, s_mid))
+        colsums.append((cs13[e][0], cs13[e][1], haq.haq_weight_colsum(w2q)))  # for the asymmetric-code variant
         if e in cold:  # canonical codes of the experts the offload workload keeps in host memory (for their CPU copies)
             w1q, _ = haq.haq_quant_weight(mats[(e, "w1")], s_in)
             w3q, _ = haq.haq_quant_weight(mats[(e, "w3")], s_in)
             canon[e] = tuple(t.cpu().contiguous() for t in (w1q, w3q, w2q, st.sw1, st.sw3, sw2, s_mid))
     del mats, stage1, dbg
     torch.cuda.synchronize()
-    return {"s_in": s_in, "experts": experts, "host_mats": host_mats, "sets": None, "oracle": None, "canon": canon}
+    return {"s_in": s_in, "experts": experts, "host_mats": host_mats, "sets": None, "oracle": None, "canon": canon,
+            "colsums": colsums}
 
 
 def oracle_mixtral(hi, host_mats=None):
@@ -485,6 +488,14 @@ def _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, co
         haq.haq_moe_w8a8_ffn(x_i, l_i, s_in, ex_i, I, out=outs[0], workspace=ws)
 
     stages = _stage_times(torch, haq, eager_step, max(args.steps, len(calls)))
+    # the same layer with asymmetric activation codes (uint8 with zero points; same weights, same launch recipe)
+    ws_a = torch.empty(haq.haq_moe_asym_workspace_bytes(T, H, I, E), dtype=torch.uint8, device=dev)
+    graph_a = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph_a):
+        for (x_i, l_i, ex_i), o_i in zip(calls, outs):
+            haq.haq_moe_w8a8_ffn_asym(x_i, l_i, s_in, ex_i, layer["colsums"], I, out=o_i, workspace=ws_a)
+    sec_a = _time_steps(torch, graph_a.replay, max(5, args.steps // 4), max(2, args.warmup // 4), settle=0.2) / len(calls)
+    del graph_a, ws_a
     pairs = int(counts.sum())
     ops = pairs * 2.0 * 3 * H * I
     n_active = int((counts > 0).sum())
@@ -496,6 +507,7 @@ def _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, co
                    "launch": "hipGraph replay", "calls_per_replay": len(calls), "weight_copies": n_sets},
         "tokens_per_s": T / sec, "layer_tops": ops / sec / 1e12, "weight_stream_GBs": w_bytes / sec / 1e9,
         "stage_ms_eager": stages, "cpu_baseline": None,
+        "asymmetric_codes": {"entry_point": "haq_moe_w8a8_ffn_asym", "ms_per_step": sec_a * 1e3, "vs_symmetric": sec_a / sec},
     }
     if prefill:
         res.update(metric="W8A8 expert-FFN int8 TOPS (prefill)", value=ops / sec / 1e12, unit="TOPS")

@@ -203,7 +203,7 @@ struct haq_ctx {
     size_t w13_bytes = 0, w2_bytes = 0;
     hipStream_t copy_stream = nullptr;
     int8_t* slot[32] = {};
-    hipEvent_t copied[32] = {}, done[32] = {};
+    hipEvent_t copied13[32] = {}, copied[32] = {}, done[32] = {};  // gate/up weights landed; both landed; GEMMs over
     hipEvent_t routed = nullptr, call_done = nullptr;
     // timeline of the last call with host-resident experts (timing events): start of the call, first copy
     // issued, last copy landed, end of the call
@@ -443,6 +443,7 @@ int32_t haq_ctx_create(int32_t H, int32_t I, int32_t n_slots, haq_ctx** out) {
     for (int i = 0; e == hipSuccess && i < n_slots; ++i) e = hipMalloc((void**)&c->slot[i], c->w13_bytes + c->w2_bytes);
     for (int i = 0; e == hipSuccess && i < 32; ++i) {
         e = hipEventCreateWithFlags(&c->copied[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->copied13[i], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming);
     }
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->routed, hipEventDisableTiming);
@@ -465,6 +466,7 @@ int32_t haq_ctx_destroy(haq_ctx* c) {
     for (int i = 0; i < 32; ++i) {
         if (c->slot[i]) (void)hipFree(c->slot[i]);
         if (c->copied[i]) (void)hipEventDestroy(c->copied[i]);
+        if (c->copied13[i]) (void)hipEventDestroy(c->copied13[i]);
         if (c->done[i]) (void)hipEventDestroy(c->done[i]);
     }
     if (c->routed) (void)hipEventDestroy(c->routed);
@@ -630,7 +632,8 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
     }
 
     // gate/up GEMM + SwiGLU, requantisation and down GEMM for a set of experts (rows of the others untouched)
-    auto run_experts = [&](const int* sel, int n_sel, int max_rows) -> int {
+    // (before_down: an event the launch stream waits for between the requantisation and the down GEMM)
+    auto run_experts = [&](const int* sel, int n_sel, int max_rows, hipEvent_t before_down = nullptr) -> int {
         GemmArgs g1{};
         g1.A = w.q_cm;
         g1.R = w.R;
@@ -668,6 +671,7 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         qb.max_rows = max_rows;
         if ((r = launch_quant(qb, st)) != HAQ_OK) return r;
         if (n_host == 0) prof_mark(st, "requantise intermediate");
+        if (before_down) HAQ_CHECK_HIP(hipStreamWaitEvent(st, before_down, 0));
 
         GemmArgs g2{};
         g2.A = w.hq_cm;
@@ -771,11 +775,14 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         const int e = order[k];
         int8_t* slot = ctx->slot[slot_of[k]];
         HAQ_CHECK_HIP(hipMemcpyAsync(slot, experts[e].w13, ctx->w13_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
+        HAQ_CHECK_HIP(hipEventRecord(ctx->copied13[k], ctx->copy_stream));
         HAQ_CHECK_HIP(hipMemcpyAsync(slot + ctx->w13_bytes, experts[e].w2, ctx->w2_bytes, hipMemcpyHostToDevice, ctx->copy_stream));
         HAQ_CHECK_HIP(hipEventRecord(ctx->copied[k], ctx->copy_stream));
         issued[k] = true;
         return HAQ_OK;
     };
+    int off_host[33] = {0};
+    for (int e = 0; e < E; ++e) off_host[e + 1] = off_host[e] + ctx->counts_host[e];
     auto enqueue = [&]() -> int {
         int r;
         // slots may still be read by the previous call on another stream
@@ -805,11 +812,39 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         for (int k = 0; k < n_order; ++k) {
             const int e = order[k];
             if (grouped[k]) continue;
+            // a streamed expert's gate/up projection starts when its gate/up weights have landed, under the copy of
+            // its down weights; the down projection waits for those
             if (!hit[k]) {
                 if (!issued[k]) HAQ_FAIL(HAQ_ERR_HIP, "haq_moe_w8a8_ffn: internal error, expert copy never issued");
-                HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied[k], 0));
+                HAQ_CHECK_HIP(hipStreamWaitEvent(st, ctx->copied13[k], 0));
             }
-            if ((r = run_experts(&e, 1, ctx->counts_host[e])) != HAQ_OK) return r;
+            const int n_e = ctx->counts_host[e];
+            hipEvent_t w2_landed = hit[k] ? nullptr : ctx->copied[k];
+            if (n_e <= 64 && decode_supported(n_e, H, I)) {
+                // few rows: stream the expert's weights once through the weight-streaming kernels instead of
+                // running the tiled GEMMs on a handful of work-groups (same arithmetic, same bits)
+                DecodeArgs da{};
+                da.q_cm = w.q_cm;
+                da.sx = w.sx_sorted;
+                da.R = w.R;
+                da.offsets = offsets;
+                da.tab = w.tab;
+                da.E = E;
+                da.H = H;
+                da.I = I;
+                da.Npad13 = round_up(2 * (int64_t)I, NPAD);
+                da.Npad2 = round_up(H, NPAD);
+                da.mid = mid;
+                da.pmax = w.pmax;
+                da.hq_cm = w.hq_cm;
+                da.hq_rm = d.hq;
+                da.sh = sh;
+                da.y = y;
+                r = launch_decode_one_expert(da, e, off_host[e], n_e, w2_landed, st);
+            } else {
+                r = run_experts(&e, 1, n_e, w2_landed);
+            }
+            if (r != HAQ_OK) return r;
             HAQ_CHECK_HIP(hipEventRecord(ctx->done[k], st));
             // a later expert of this call that evicts this one may overwrite the slot after these GEMMs
             for (int k2 = k + 1; k2 < n_order; ++k2) {
@@ -824,8 +859,6 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
         // what was enqueued above; their token rows come over on a third stream and their output rows go
         // back into the sorted per-pair outputs before the combination.
         if (n_cpu > 0) {
-            int off_host[33] = {0};
-            for (int e = 0; e < E; ++e) off_host[e + 1] = off_host[e] + ctx->counts_host[e];
             HAQ_CHECK_HIP(hipStreamWaitEvent(ctx->aux_stream, ctx->routed, 0));
             for (int i = 0; i < n_cpu; ++i) {
                 const int e = cpu_list[i], n = ctx->counts_host[e], lo = off_host[e];
@@ -1070,6 +1103,28 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
     qa.zp_in = d.zx;
     if ((rc = launch_asym_quant_rows(qa, st)) != HAQ_OK) return rc;
 
+    // At most 64 tokens: every activated expert's weights are streamed once by the weight-streaming kernels
+    // (their asymmetric instantiations); longer batches take the grouped tiled GEMM.
+    const bool decode_path = decode_supported(T, H, I);
+    DecodeArgs da{};
+    da.q_cm = w.q_cm;
+    da.sx = w.sx_sorted;
+    da.R = w.R;
+    da.offsets = offsets;
+    da.tab = w.tab;
+    da.E = E;
+    da.H = H;
+    da.I = I;
+    da.Npad13 = round_up(2 * (int64_t)I, NPAD);
+    da.Npad2 = round_up(H, NPAD);
+    da.mid = mid;
+    da.hq_cm = w.hq_cm;
+    da.sh = sh;
+    da.y = y;
+    da.zx = zx_sorted;
+    da.zh = zh;
+    da.cstab = cstab;
+
     GemmArgs g1{};
     g1.A = w.q_cm;
     g1.R = w.R;
@@ -1087,7 +1142,7 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
     g1.ldy = I;
     g1.zp = zx_sorted;
     g1.cstab = cstab;
-    if ((rc = launch_gemm(g1, EPI_SWIGLU_ASYM, st)) != HAQ_OK) return rc;
+    if ((rc = decode_path ? launch_decode_gate_up_asym(da, T, st) : launch_gemm(g1, EPI_SWIGLU_ASYM, st)) != HAQ_OK) return rc;
 
     AsymRowArgs qb{};
     qb.x = mid;
@@ -1123,7 +1178,7 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
     g2.ldy = H;
     g2.zp = zh;
     g2.cstab = cstab;
-    if ((rc = launch_gemm(g2, EPI_LINEAR_ASYM, st)) != HAQ_OK) return rc;
+    if ((rc = decode_path ? launch_decode_down_asym(da, T, st) : launch_gemm(g2, EPI_LINEAR_ASYM, st)) != HAQ_OK) return rc;
     return launch_combine(y, H, inv, gw, T, H, (__half*)out_fp16, ldo, st);
 }
 

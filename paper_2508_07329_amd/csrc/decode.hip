@@ -59,10 +59,15 @@ __device__ __forceinline__ int nth_active_expert(const int32_t* offsets, int E, 
 // XLDS: the token codes and their scales do not come from memory but from LDS (rows of H bytes at
 // xl, scales at sxl), where `prep` -- called once the first weight fragments are in flight --
 // leaves them; lanes past the last row read the last row (their results are dropped).
-template <int NRB, int DEPTH, bool XLDS, class Prep>
+//
+// ASYM: the token codes are unsigned with a zero point per row (the operand holds code - 128): the
+// accumulators are corrected by (128 - zero point) x column sum of the expert's weights before the
+// scales are applied, and no partial row maxima are left (the asymmetric requantisation needs the
+// row's minimum and maximum and finds them itself).
+template <int NRB, int DEPTH, bool XLDS, bool ASYM, class Prep>
 __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTab& t, int lo, int m, int unit,
                                              int (*part)[2][16][64], float (*wmax)[32], const int8_t* xl, const float* sxl,
-                                             Prep&& prep) {
+                                             Prep&& prep, const ColsumTab* cs = nullptr) {
     static_assert(!XLDS || NRB == 1, "the LDS variant carries one row block");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -146,6 +151,14 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
     const float4 s3 = *reinterpret_cast<const float4*>(t.sw3 + ch);
     const float4 sm = *reinterpret_cast<const float4*>(t.s_mid + ch);
     const float s1v[4] = {s1.x, s1.y, s1.z, s1.w}, s3v[4] = {s3.x, s3.y, s3.z, s3.w}, smv[4] = {sm.x, sm.y, sm.z, sm.w};
+    int c1v[4] = {0, 0, 0, 0}, c3v[4] = {0, 0, 0, 0};
+    if constexpr (ASYM) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            c1v[q] = cs->cs1[ch + q];
+            c3v[q] = cs->cs3[ch + q];
+        }
+    }
 #pragma unroll
     for (int b = 0; b < NRB; ++b) {
         if (b > 0) __syncthreads();  // part and wmax are reused
@@ -159,6 +172,8 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
         const int row = 32 * b + l32;
         const bool live = row < m;
         const float sx = live ? (XLDS ? sxl[row] : a.sx[lo + row]) : 0.0f;
+        int zshift = 0;
+        if constexpr (ASYM) zshift = live ? 128 - a.zx[lo + row] : 0;
         __half hv[4];
         float ymax = 0.0f;
 #pragma unroll
@@ -169,11 +184,16 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
                 g += part[w][0][4 * wave + q][lane];
                 u += part[w][1][4 * wave + q][lane];
             }
+            if constexpr (ASYM) {
+                g += zshift * c1v[q];
+                u += zshift * c3v[q];
+            }
             const float gf = dequant(g, sx, s1v[q]), uf = dequant(u, sx, s3v[q]);
             hv[q] = f2h(silu(gf) * uf);
-            ymax = fmaxf(ymax, fabsf(h2f(hv[q]) / smv[q]));
+            if constexpr (!ASYM) ymax = fmaxf(ymax, fabsf(h2f(hv[q]) / smv[q]));
         }
         if (live) *reinterpret_cast<uint2*>(a.mid + (size_t)(lo + row) * a.I + ch) = *reinterpret_cast<const uint2*>(hv);
+        if constexpr (ASYM) continue;
         ymax = fmaxf(ymax, __shfl_xor(ymax, 32));
         if (hi == 0) wmax[wave][l32] = ymax;
         __syncthreads();
@@ -187,16 +207,18 @@ __device__ __forceinline__ void gate_up_body(const DecodeArgs& a, const ExpertTa
     }
 }
 
+template <bool ASYM>
 __global__ __launch_bounds__(GU_WAVES * 64, 3) void decode_gate_up_kernel(DecodeArgs a) {
     __shared__ int part[GU_WAVES][2][16][64];
     __shared__ float wmax[GU_WAVES][32];
-    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
+    const int e = a.one_expert ? a.one_expert - 1 : nth_active_expert(a.offsets, a.E, blockIdx.y);
     if (e < 0) return;
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
+    const ColsumTab* cs = ASYM ? a.cstab + e : nullptr;
     if (m > 32)  // uniform over the work-group
-        gate_up_body<2, GU_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {});
+        gate_up_body<2, GU_DEPTH2, false, ASYM>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {}, cs);
     else
-        gate_up_body<1, GU_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {});
+        gate_up_body<1, GU_DEPTH, false, ASYM>(a, a.tab[e], lo, m, blockIdx.x, part, wmax, nullptr, nullptr, [] {}, cs);
 }
 
 // One or two tokens: routing, the stable grouping of the pairs and the quantisation of the
@@ -242,7 +264,7 @@ __global__ __launch_bounds__(GU_WAVES * 64, 4) void decode_tiny_gate_up_kernel(D
     if (e < 0) return;
     const int lo = rt.off[e], m = rt.cnt[e];  // m <= 2: one pair per token at most
     int8_t* xq = reinterpret_cast<int8_t*>(part);
-    gate_up_body<1, GU_DEPTH_TINY, true>(a, tab.e[e], lo, m, blockIdx.x, part, wmax, xq, s_sx, [&] {
+    gate_up_body<1, GU_DEPTH_TINY, true, false>(a, tab.e[e], lo, m, blockIdx.x, part, wmax, xq, s_sx, [&] {
 #pragma nounroll
         for (int row = 0; row < m; ++row) {
             const int tok = rt.src[lo + row] >> 1;
@@ -262,7 +284,7 @@ __global__ __launch_bounds__(GU_WAVES * 64, 4) void decode_tiny_gate_up_kernel(D
 constexpr int RQ_THREADS = 1024;
 __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a) {
     __shared__ float red[RQ_THREADS / 64];
-    const int pos = blockIdx.x;
+    const int pos = a.row0 + blockIdx.x;
     int e = 0;
     while (e + 1 < a.E && pos >= a.offsets[e + 1]) ++e;
     const float* s = a.tab[e].s_mid;
@@ -317,9 +339,11 @@ __global__ __launch_bounds__(RQ_THREADS) void decode_requant_kernel(DecodeArgs a
 // NW waves split K; wave w finishes 16 / NW of the 16 accumulator registers.
 // `tid` is the thread's index among the NW * 64 threads that share the unit (threadIdx.x, unless a work-group
 // holds several such groups); ylds, if given, also receives the fp16 outputs: ylds[row * 32 + channel of the unit].
-template <int NW, int NRB, int DEPTH, bool XLDS, class Prep>
+// ASYM: codes of the intermediate with a zero point per row, corrected as in the gate/up kernel (cs2: column sums of w2).
+template <int NW, int NRB, int DEPTH, bool XLDS, bool ASYM, class Prep>
 __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& t, int lo, int m, int unit, int (*part)[16][64],
-                                          const int8_t* xl, const float* shl, Prep&& prep, int tid, __half* ylds = nullptr) {
+                                          const int8_t* xl, const float* shl, Prep&& prep, int tid, __half* ylds = nullptr,
+                                          const int32_t* cs2 = nullptr) {
     static_assert(!XLDS || NRB == 1, "the LDS variant carries one row block");
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
@@ -395,6 +419,9 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
     float sw[RPW];
 #pragma unroll
     for (int q = 0; q < RPW; ++q) sw[q] = t.sw2[ch + q];
+    int cv[RPW];
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) cv[q] = ASYM ? cs2[ch + q] : 0;
 #pragma unroll
     for (int b = 0; b < NRB; ++b) {
         if (b > 0) __syncthreads();  // part is reused
@@ -404,12 +431,15 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
         const int row = 32 * b + l32;
         const bool live = row < m;
         const float sh = live ? (XLDS ? shl[row] : a.sh[lo + row]) : 0.0f;
+        int zshift = 0;
+        if constexpr (ASYM) zshift = live ? 128 - a.zh[lo + row] : 0;
         __half hv[RPW];
 #pragma unroll
         for (int q = 0; q < RPW; ++q) {
             int v = 0;
 #pragma unroll
             for (int w = 0; w < NW; ++w) v += part[w][r0 + q][lane];
+            if constexpr (ASYM) v += zshift * cv[q];
             hv[q] = f2h(dequant(v, sh, sw[q]));
         }
         if (live) {
@@ -426,15 +456,19 @@ __device__ __forceinline__ void down_body(const DecodeArgs& a, const ExpertTab& 
     }
 }
 
+template <bool ASYM>
 __global__ __launch_bounds__(DNG_WAVES * 64, DNG_WGS) void decode_down_kernel(DecodeArgs a) {
     __shared__ int part[DNG_WAVES][16][64];
-    const int e = nth_active_expert(a.offsets, a.E, blockIdx.y);
+    const int e = a.one_expert ? a.one_expert - 1 : nth_active_expert(a.offsets, a.E, blockIdx.y);
     if (e < 0) return;
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
+    const int32_t* cs2 = ASYM ? a.cstab[e].cs2 : nullptr;
     if (m > 32)  // uniform over the work-group
-        down_body<DNG_WAVES, 2, DNG_DEPTH2, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {}, threadIdx.x);
+        down_body<DNG_WAVES, 2, DNG_DEPTH2, false, ASYM>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {}, threadIdx.x,
+                                                         nullptr, cs2);
     else
-        down_body<DNG_WAVES, 1, DNG_DEPTH, false>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {}, threadIdx.x);
+        down_body<DNG_WAVES, 1, DNG_DEPTH, false, ASYM>(a, a.tab[e], lo, m, blockIdx.x, part, nullptr, nullptr, [] {}, threadIdx.x,
+                                                        nullptr, cs2);
 }
 
 // One or two tokens: every work-group requantises the expert's one or two rows of the
@@ -497,7 +531,7 @@ __global__ __launch_bounds__(DN_WAVES * 64, 1) void decode_tiny_down_kernel(Deco
     const int lo = a.offsets[e], m = a.offsets[e + 1] - lo;
     const ExpertTab& t = tab.e[e];
     int8_t* xq = reinterpret_cast<int8_t*>(part);
-    down_body<DN_WAVES, 1, DN_DEPTH, true>(
+    down_body<DN_WAVES, 1, DN_DEPTH, true, false>(
         a, t, lo, m, blockIdx.x, part, xq, s_sh,
         [&] { requant_rows_to_lds<DN_WAVES * 64>(a, t, lo, m, threadIdx.x, xq, s_red, s_sh); }, threadIdx.x);
 }
@@ -534,13 +568,45 @@ int launch_decode(const DecodeArgs& a, int T, hipStream_t st) {
     const int P = 2 * T;
     const int ne = a.E < P ? a.E : P;  // at most 2T experts can hold rows
     const dim3 g1(a.I / 32, ne), g2(a.H / 32, ne);
-    hipLaunchKernelGGL(decode_gate_up_kernel, g1, dim3(GU_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL(decode_gate_up_kernel<false>, g1, dim3(GU_WAVES * 64), 0, st, a);
     {
         const int nchunk = a.I / 16;
         const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
         hipLaunchKernelGGL(decode_requant_kernel, dim3(P), dim3(thr), 0, st, a);
     }
-    hipLaunchKernelGGL(decode_down_kernel, g2, dim3(DNG_WAVES * 64), 0, st, a);
+    hipLaunchKernelGGL(decode_down_kernel<false>, g2, dim3(DNG_WAVES * 64), 0, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int launch_decode_one_expert(DecodeArgs a, int e, int row0, int m, hipEvent_t before_down, hipStream_t st) {
+    if (e < 0 || e >= a.E || m < 1 || m > 64 || row0 < 0) return HAQ_ERR_INVALID_ARG;
+    a.one_expert = e + 1;
+    a.row0 = row0;
+    hipLaunchKernelGGL(decode_gate_up_kernel<false>, dim3(a.I / 32, 1), dim3(GU_WAVES * 64), 0, st, a);
+    const int nchunk = a.I / 16;
+    const int thr = nchunk >= RQ_THREADS ? RQ_THREADS : (int)round_up(nchunk, 64);
+    hipLaunchKernelGGL(decode_requant_kernel, dim3(m), dim3(thr), 0, st, a);
+    if (before_down) HAQ_CHECK_HIP(hipStreamWaitEvent(st, before_down, 0));
+    hipLaunchKernelGGL(decode_down_kernel<false>, dim3(a.H / 32, 1), dim3(DNG_WAVES * 64), 0, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int launch_decode_gate_up_asym(const DecodeArgs& a, int T, hipStream_t st) {
+    if (!a.zx || !a.cstab) return HAQ_ERR_INVALID_ARG;
+    const int P = 2 * T;
+    const int ne = a.E < P ? a.E : P;
+    hipLaunchKernelGGL(decode_gate_up_kernel<true>, dim3(a.I / 32, ne), dim3(GU_WAVES * 64), 0, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int launch_decode_down_asym(const DecodeArgs& a, int T, hipStream_t st) {
+    if (!a.zh || !a.cstab) return HAQ_ERR_INVALID_ARG;
+    const int P = 2 * T;
+    const int ne = a.E < P ? a.E : P;
+    hipLaunchKernelGGL(decode_down_kernel<true>, dim3(a.H / 32, ne), dim3(DNG_WAVES * 64), 0, st, a);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -187,9 +187,22 @@ struct DecodeArgs {
     int8_t* hq_rm;        // optional dense [P x I]
     float* sh;            // [P]
     __half* y;            // [P x H] sorted
+    // asymmetric codes only: zero points of the token rows and of the intermediate's rows (sorted), column sums per expert
+    const int32_t* zx;
+    const int32_t* zh;
+    const ColsumTab* cstab;
+    int one_expert;       // 1 + index of the only expert to process (its rows start at row0), 0: every expert that holds rows
+    int row0;
 };
 bool decode_supported(int T, int H, int I);
 int launch_decode(const DecodeArgs& a, int T, hipStream_t st);
+// The two projections of launch_decode for asymmetric codes (zx / zh, cstab set); the caller quantises the
+// intermediate between the two (no partial row maxima are produced).
+// One expert with 1..64 rows (rows row0 .. row0 + m - 1 of the sorted order): the three launches of launch_decode
+// for that expert alone; the launch stream waits for before_down (if given) ahead of the down projection.
+int launch_decode_one_expert(DecodeArgs a, int e, int row0, int m, hipEvent_t before_down, hipStream_t st);
+int launch_decode_gate_up_asym(const DecodeArgs& a, int T, hipStream_t st);
+int launch_decode_down_asym(const DecodeArgs& a, int T, hipStream_t st);
 // One or two tokens: two launches do routing, token quantisation, both projections and the
 // requantisation between them (q_cm, sx, hq_cm, hq_rm and sh of `a` are not used); the routing
 // results are written for the combination that follows.  With one token the second launch also

@@ -369,20 +369,21 @@ def _offload(dev_experts, host_ids):
     return out
 
 
-@pytest.mark.parametrize("n_slots,host_ids", [(2, (4, 5, 6, 7)), (1, (0, 3, 5)), (3, (1, 2, 3, 4, 5, 6, 7))])
-def test_moe_offload_small_matches_resident_and_oracle(n_slots, host_ids):
-    m = offline.small_moe(seed=50 + n_slots, T=90, H=128, I=320, E=8, routing="popularity")
+@pytest.mark.parametrize("H,I", [(128, 320), (256, 512)])   # the second shape lets streamed experts with at most 64 rows
+@pytest.mark.parametrize("n_slots,host_ids", [(2, (4, 5, 6, 7)), (1, (0, 3, 5)), (3, (1, 2, 3, 4, 5, 6, 7))])   # take the weight-streaming kernels
+def test_moe_offload_small_matches_resident_and_oracle(n_slots, host_ids, H, I):
+    m = offline.small_moe(seed=50 + n_slots, T=90, H=H, I=I, E=8, routing="popularity")
     if n_slots == 1:
         m["logits"][:, 3] = -100  # a host-resident expert nobody selects: never copied
     dev_experts = upload_experts(m["experts"])
     X, logits, s_in = dev(m["X"]), dev(m["logits"]), dev(m["s_in"])
-    ref = haq.haq_moe_w8a8_ffn(X, logits, s_in, dev_experts, 320)
-    ctx = haq.haq_ctx_create(128, 320, n_slots)
+    ref = haq.haq_moe_w8a8_ffn(X, logits, s_in, dev_experts, I)
+    ctx = haq.haq_ctx_create(H, I, n_slots)
     try:
         mixed = _offload(dev_experts, host_ids)
         _check_moe(m, mixed, ctx=ctx)
         for _ in range(2):  # slots are reused across calls
-            out = haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, 320, ctx=ctx)
+            out = haq.haq_moe_w8a8_ffn(X, logits, s_in, mixed, I, ctx=ctx)
             assert bits_equal(host(out), host(ref))
     finally:
         torch.cuda.synchronize()
@@ -740,7 +741,10 @@ def _check_moe_asym(m, dev_experts=None, colsums=None, tokens=None):
 
 
 @pytest.mark.parametrize("T,H,I,E", [(37, 128, 320, 8), (1, 128, 192, 8), (300, 256, 576, 8), (9, 128, 192, 2), (530, 192, 448, 4),
-                                      (700, 128, 192, 32), (64, 256, 1024, 4), (2100, 128, 256, 8)])
+                                      (700, 128, 192, 32), (64, 256, 1024, 4), (2100, 128, 256, 8),
+                                      # at most 64 tokens with I a multiple of 256: the weight-streaming kernels
+                                      (1, 128, 256, 8), (2, 256, 512, 8), (33, 128, 512, 2), (64, 128, 256, 2), (17, 256, 768, 8),
+                                      (64, 128, 256, 32)])
 def test_moe_asym_small_everything_bit_exact(T, H, I, E):
     _check_moe_asym(offline.small_moe(seed=220 + T, T=T, H=H, I=I, E=E))
 
@@ -769,11 +773,20 @@ def test_moe_asym_identical_experts_equal_the_dense_asymmetric_linear_chain():
     assert bits_equal(host(y_lin), host(d.y_fp16))
 
 
-@pytest.mark.parametrize("name", ["decode_b8", "prefill"])
+def test_moe_asym_streaming_kernels_skewed_routing_and_empty_expert():
+    m = offline.small_moe(seed=233, T=60, H=256, I=512, E=8, routing="popularity")
+    m["logits"][:, 2] = -100                     # nobody picks expert 2
+    m["X"][:10] = np.abs(m["X"][:10])
+    m["X"][11] = 0
+    counts = _check_moe_asym(m)
+    assert counts[2] == 0 and counts.max() > 32  # both row-block code paths in one launch
+
+
+@pytest.mark.parametrize("name", ["decode_b1", "decode_b8", "decode_b64", "prefill"])
 def test_moe_asym_mixtral(layer, name):
-    """The Mixtral-shaped layer with asymmetric codes: 8 tokens, and the 4096-token Zipf prefill batch
-    (every token against the oracle)."""
-    wl = hi.MIXTRAL_PREFILL if name == "prefill" else {w.T: w for w in hi.MIXTRAL_DECODE}[8]
+    """The Mixtral-shaped layer with asymmetric codes: 1, 8 and 64 tokens (weight-streaming kernels), and the
+    4096-token Zipf prefill batch (every token against the oracle)."""
+    wl = hi.MIXTRAL_PREFILL if name == "prefill" else {w.T: w for w in hi.MIXTRAL_DECODE}[int(name.split("_b")[1])]
     if "colsums" not in layer:
         layer["colsums"] = _colsums(layer["experts"])
     _check_moe_asym(_mixtral_case(wl, layer), layer["dev_experts"], layer["colsums"], np.arange(wl.T))
