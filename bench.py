@@ -50,6 +50,10 @@ QUANT_VALU_PER_ELEMENT = 24.0
 # 256 MiB device copy); the counters cannot be read from inside this process, so the figure is the one
 # of the committed summary profiles/gemm_i8_kernel__opt6.7b_ffn.md and only applies to that workload.
 GEMM_TRAFFIC_BYTES_OPT67B_FFN = 2.77e+08
+# The same for the single GEMM launch of the small linear (16 x 768 x 3072: 3.29 MB read, 0.10 MB written) and for the
+# grouped gate/up and down launches of the prefill layer (profiles/gemm_i8_kernel__mixtral_prefill.md).
+GEMM_TRAFFIC_BYTES_OPT125M_LINEAR = 3.39e+06
+PREFILL_TRAFFIC_BYTES = {"gate_up": 3.12e+09, "down": 1.93e+09}
 # The same for one call of the decode layer (all its kernels; reads only, the writes are a few MB), from
 # profiles/decode_kernels__mixtral_decode.md: within 0.3-2 % of the algorithmic weight bytes.
 DECODE_TRAFFIC_BYTES = {"moe_decode_b1": 3.55e+08, "moe_decode_b8": 1.063e+09, "moe_decode_b64": 1.440e+09}
@@ -252,7 +256,8 @@ def bench_ffn(args, torch, haq, hi, cpu_seconds=10.0):
     roof = {"bound": "mfma", "kernel": "gemm_i8_kernel (int8 MFMA GEMM + dequant epilogue)",
             "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
             "avg_launch_ms": gemm_avg * 1e3, "launch_ms": gemm_ms, "ops_per_launch": ops_per_gemm,
-            "traffic": GEMM_TRAFFIC_BYTES_OPT67B_FFN if wl is not None else None, "traffic_unit": "bytes per launch"}
+            "traffic": GEMM_TRAFFIC_BYTES_OPT67B_FFN if wl is not None else GEMM_TRAFFIC_BYTES_OPT125M_LINEAR,
+            "traffic_unit": "bytes per launch"}
     if two and not args.no_ceilings:
         # the peak at the clock the chip really runs this kernel at, and what the matrix cores sustain on a
         # pure-MFMA loop (no memory traffic at all) fed with operands of this very workload and with uniform
@@ -514,13 +519,17 @@ def _bench_moe_resident(args, torch, haq, hi, wl, workload, layer, X, logits, co
         gu_ms = stages.get("grouped gate/up GEMM + SwiGLU")
         dn_ms = stages.get("grouped down GEMM")
         gu_ops, dn_ops = pairs * 2.0 * H * 2 * I, pairs * 2.0 * I * H
+        n_active_e = int((counts > 0).sum())
         res["roofline"] = {"bound": "mfma", "kernel": "gemm_i8_kernel, grouped gate/up launch (int8 MFMA GEMM + SwiGLU epilogue)",
                            "achieved": gu_ops / (gu_ms * 1e-3) / 1e12, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                            "frac": gu_ops / (gu_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, "avg_launch_ms": gu_ms, "ops_per_launch": gu_ops,
                            "down_launch": {"achieved": dn_ops / (dn_ms * 1e-3) / 1e12, "frac": dn_ops / (dn_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS,
-                                           "avg_launch_ms": dn_ms, "ops_per_launch": dn_ops},
+                                           "avg_launch_ms": dn_ms, "ops_per_launch": dn_ops,
+                                           "traffic": PREFILL_TRAFFIC_BYTES["down"],
+                                           "algorithmic_bytes": pairs * I + n_active_e * I * H + pairs * H * 2.0},
                            "whole_layer": {"achieved": ops / sec / 1e12, "frac": ops / sec / 1e12 / PEAK_INT8_TOPS},
-                           "traffic": None}
+                           "traffic": PREFILL_TRAFFIC_BYTES["gate_up"], "traffic_unit": "bytes per launch",
+                           "algorithmic_bytes": pairs * H + n_active_e * 2.0 * H * I + pairs * I * 2.0}
         res["other_kernels"] = [
             _quant_record("requantisation of the fp16 intermediate (per-expert smoothing vectors)", pairs, I,
                           stages.get("requantise intermediate"))]
