@@ -10,7 +10,14 @@ namespace {
 
 // 128 x 256 tiles, 4 waves (2 x 2, 64 x 128 each), 3-deep ring: 75 KB of LDS and at most
 // 256 registers per lane, so two work-groups share a CU and fill each other's stalls.
-constexpr int BM = 128, BN = 256, WAVES_M = 2, WAVES_N = 2, STAGES = 3, MINB = 2;
+// (The shape can be overridden at compile time to measure other tilings; the small-problem instantiation below is fixed.)
+#ifndef HAQ_BM
+#define HAQ_BM 128
+#define HAQ_BN 256
+#define HAQ_MINB 2
+#define HAQ_STAGES 3
+#endif
+constexpr int BM = HAQ_BM, BN = HAQ_BN, WAVES_M = 2, WAVES_N = 2, STAGES = HAQ_STAGES, MINB = HAQ_MINB;
 using Shape = GemmShape<BM, BN, WAVES_M, WAVES_N, STAGES>;
 
 template <int EPI, bool DBG>
@@ -31,9 +38,9 @@ int launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
 // work-group slots empty: twice the tiles, 49 KB of LDS, three work-groups per CU.
 constexpr int SMALL_TILE_LIMIT = 256;  // 128 x 256 tiles that would not even give every CU one work-group
 constexpr int BN_S = 128, MINB_S = 3;
-using ShapeS = GemmShape<BM, BN_S, WAVES_M, WAVES_N, STAGES>;
+using ShapeS = GemmShape<128, BN_S, WAVES_M, WAVES_N, 3>;
 int launch_small(const GemmArgs& a, dim3 grid, hipStream_t st) {
-    auto kern = gemm_i8_kernel<BM, BN_S, WAVES_M, WAVES_N, STAGES, MINB_S, EPI_LINEAR, false>;
+    auto kern = gemm_i8_kernel<128, BN_S, WAVES_M, WAVES_N, 3, MINB_S, EPI_LINEAR, false>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -53,8 +60,8 @@ int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
     const int mt = a.offsets ? a.max_rows / BM + a.n_sel : cdiv(a.M, BM);
     if (mt <= 0 || ntn <= 0) return HAQ_OK;
     if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg && mt * ntn <= SMALL_TILE_LIMIT) {
-        const int ntn_s = cdiv(a.N, BN_S);
-        return launch_small(a, dim3((unsigned)round_up((int64_t)mt * ntn_s, 8)), st);
+        const int ntn_s = cdiv(a.N, BN_S), mt_s = cdiv(a.M, 128);
+        return launch_small(a, dim3((unsigned)round_up((int64_t)mt_s * ntn_s, 8)), st);
     }
     const dim3 grid((unsigned)round_up((int64_t)mt * ntn, 8));
     if (epi == EPI_SWIGLU) return launch_one<EPI_SWIGLU, false>(a, grid, st);
