@@ -553,8 +553,10 @@ int launch_decode_tiny(const DecodeArgs& a, const __half* logits, int64_t ldl, c
         hipLaunchKernelGGL(decode_tiny_gate_up_kernel<1>, g1, dim3(GU_WAVES * 64), 0, st, a, r, tab);
     else
         hipLaunchKernelGGL(decode_tiny_gate_up_kernel<2>, g1, dim3(GU_WAVES * 64), 0, st, a, r, tab);
-    // (Both experts of a single token in one work-group of 16 waves, with the combination formed in LDS, was
-    // measured: 128 work-groups do not draw the streaming rate that 256 do, 76 us against 70 us per layer.)
+    // Measured and left out (both bit-equal, both slower than three launches at 69.6 us per layer): both experts of a
+    // single token in one work-group of 16 waves with the combination formed in LDS (76 us: 128 work-groups do not draw
+    // the streaming rate that 256 do); 256 work-groups whose weight operand holds 16 channels of either expert, so that
+    // both outputs of a channel meet in one work-group (73.2 us: every work-group then requantises both rows).
     *combined = false;
     (void)out;
     hipLaunchKernelGGL(decode_tiny_down_kernel, g2, dim3(DN_WAVES * 64), 0, st, a, tab);
