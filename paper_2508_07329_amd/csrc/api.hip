@@ -1101,7 +1101,25 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
     qa.zp_out = zx_sorted;
     qa.scale_in = b.sx;
     qa.zp_in = d.zx;
-    if ((rc = launch_asym_quant_rows(qa, st)) != HAQ_OK) return rc;
+    // long batches take the pipelined quantiser (its asymmetric instantiation), short ones the row kernel
+    QuantArgs pa{};
+    pa.x = (const __half*)x_fp16;
+    pa.ldx = ldx;
+    pa.s = s_in;
+    pa.T = P;
+    pa.K = H;
+    pa.q_rm = b.q;
+    pa.ldq = H;
+    pa.q_cm = w.q_cm;
+    pa.R = w.R;
+    pa.gather = perm;
+    pa.scale = b.sx;
+    pa.scale_dest = w.sx_sorted;
+    pa.zp = d.zx;
+    pa.zp_dest = zx_sorted;
+    rc = launch_quant(pa, st);
+    if (rc == HAQ_ERR_UNSUPPORTED) rc = launch_asym_quant_rows(qa, st);
+    if (rc != HAQ_OK) return rc;
 
     // At most 64 tokens: every activated expert's weights are streamed once by the weight-streaming kernels
     // (their asymmetric instantiations); longer batches take the grouped tiled GEMM.
@@ -1158,7 +1176,26 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
     qb.ldq = I;
     qb.scale_out = sh;
     qb.zp_out = zh;
-    if ((rc = launch_asym_quant_rows(qb, st)) != HAQ_OK) return rc;
+    QuantArgs pb{};
+    pb.x = mid;
+    pb.ldx = I;
+    pb.tab = w.tab;
+    pb.offsets = offsets;
+    pb.E = E;
+    pb.T = P;
+    pb.K = I;
+    pb.q_rm = b.hq;
+    pb.ldq = I;
+    pb.q_cm = w.hq_cm;
+    pb.R = w.R;
+    pb.scale_dest = sh;
+    pb.zp_dest = zh;
+    pb.n_sel = E;
+    for (int e = 0; e < E; ++e) pb.sel[e] = e;
+    pb.max_rows = P;
+    rc = launch_quant(pb, st);
+    if (rc == HAQ_ERR_UNSUPPORTED) rc = launch_asym_quant_rows(qb, st);
+    if (rc != HAQ_OK) return rc;
 
     GemmArgs g2{};
     g2.A = w.hq_cm;

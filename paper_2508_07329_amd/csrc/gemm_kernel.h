@@ -100,7 +100,7 @@ struct GemmShape {
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int THREADS = NW * 64;
     static constexpr int STAGE_BYTES = (BM + BN) * 64;
-    static constexpr int SCALE_BYTES = (BM + BN) * 4;  // row scales and channel scales of the tile
+    static constexpr int SCALE_BYTES = (BM + 2 * BN) * 4;  // row scales, channel scales and (asymmetric codes) column sums of the tile
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + SCALE_BYTES;
 };
 
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
     float* sx_s = reinterpret_cast<float*>(lds + STAGES * STAGE_BYTES);  // [BM] row scales of the tile
     float* sw_s = sx_s + BM;                                             // [BN] channel scales, packed order
+    int32_t* cs_s = reinterpret_cast<int32_t*>(sw_s + BN);               // [BN] column sums of the weight codes, packed order (ASYM)
 
     const TileCoord tc = decode_tile<BM, BN>(a);
     if (!tc.valid) return;
@@ -163,15 +164,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     for (int i = tid; i < BN; i += S::THREADS) {
         const int pc = tc.n0 + i;
         float v = 0.0f;
+        int cs = 0;
         if (pc < a.N) {
             if (SWIGLU) {
                 const int col = (pc / 64) * 32 + (pc % 32);
                 v = ((pc / 32) & 1) ? sw_b[col] : sw_a[col];
+                if (ASYM) cs = ((pc / 32) & 1) ? cs_b[col] : cs_a[col];
             } else {
                 v = sw_a[pc];
+                if (ASYM) cs = cs_a[pc];
             }
         }
         sw_s[i] = v;
+        if (ASYM) cs_s[i] = cs;
     }
 
     // direct-to-LDS load descriptors: group g = wave + i*NW covers 64 rows of one 16-byte chunk
@@ -339,14 +344,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
                     const int nloc = j * 32 + 8 * q + n_l;
                     const float4 sw = *reinterpret_cast<const float4*>(sw_s + wn * WN + nloc);
                     const float swv[4] = {sw.x, sw.y, sw.z, sw.w};
+                    int csv[4] = {0, 0, 0, 0};
+                    if (ASYM) {
+                        const int4 c4 = *reinterpret_cast<const int4*>(cs_s + wn * WN + nloc);
+                        csv[0] = c4.x, csv[1] = c4.y, csv[2] = c4.z, csv[3] = c4.w;
+                    }
                     __half hv[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         int v = acc[i][j][4 * q + e];
-                        if (ASYM) {
-                            const int col = tc.n0 + wn * WN + nloc + e;
-                            if (col < a.N) v += zshift * cs_a[col];
-                        }
+                        if (ASYM) v += zshift * csv[e];  // channels past N hold column sum 0
                         if (DBG) {
                             const int row = tc.m0 + rloc, col = tc.n0 + wn * WN + nloc + e;
                             if (row < tc.m_end && col < a.N) a.acc_dbg[(size_t)row * a.N + col] = v;
@@ -366,17 +373,21 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
                     const float4 s1 = *reinterpret_cast<const float4*>(sw_s + wn * WN + nloc);
                     const float4 s3 = *reinterpret_cast<const float4*>(sw_s + wn * WN + nloc + 32);
                     const float s1v[4] = {s1.x, s1.y, s1.z, s1.w}, s3v[4] = {s3.x, s3.y, s3.z, s3.w};
+                    int c1v[4] = {0, 0, 0, 0}, c3v[4] = {0, 0, 0, 0};
+                    if (ASYM) {
+                        const int4 c1 = *reinterpret_cast<const int4*>(cs_s + wn * WN + nloc);
+                        const int4 c3 = *reinterpret_cast<const int4*>(cs_s + wn * WN + nloc + 32);
+                        c1v[0] = c1.x, c1v[1] = c1.y, c1v[2] = c1.z, c1v[3] = c1.w;
+                        c3v[0] = c3.x, c3v[1] = c3.y, c3v[2] = c3.z, c3v[3] = c3.w;
+                    }
                     __half hv[4];
                     const int oloc = (j / 2) * 32 + 8 * q + n_l;  // output channel inside the wave tile
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         int ag = acc[i][j][4 * q + e], au = acc[i][j + 1][4 * q + e];
                         if (ASYM) {
-                            const int col = out_n0 + oloc + e;
-                            if (col < out_n) {
-                                ag += zshift * cs_a[col];
-                                au += zshift * cs_b[col];
-                            }
+                            ag += zshift * c1v[e];
+                            au += zshift * c3v[e];
                         }
                         const float g = dequant(ag, sx, s1v[e]);
                         const float u = dequant(au, sx, s3v[e]);

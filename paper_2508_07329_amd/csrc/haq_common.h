@@ -105,7 +105,11 @@ struct QuantArgs {
     int n_sel;         // with tab: the experts whose row groups this launch covers
     int sel[32];
     int max_rows;      // with tab: upper bound of the rows of the selected groups (grid sizing)
-
+    // Asymmetric codes (zp_dest set): zero points by output row and (optional) by input row; q_rm then holds the
+    // unsigned codes and q_cm code - 128.  Only the pipelined kernel has this variant: launch_quant returns
+    // HAQ_ERR_UNSUPPORTED (no error message) when the batch is too short for it or K > 16384.
+    int32_t* zp_dest;
+    int32_t* zp;
 };
 int launch_quant(const QuantArgs& a, hipStream_t st);
 

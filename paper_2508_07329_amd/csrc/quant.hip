@@ -318,7 +318,10 @@ __host__ __device__ inline int qstage_rows(int slab) { return slab > QSTAGE ? sl
 // reads of eight rows x eight chunks spread evenly over the banks
 __host__ __device__ inline int qstage_pitch(int nchunk) { return (nchunk + ((24 - nchunk % 16) % 16)) * 16; }
 
-template <int RS>
+//
+// ASYM: unsigned codes with a zero point per row (range of the row widened to contain 0, scale = range / 255,
+// zero point = rne(-min / scale)); the packed operand holds code - 128, the optional row-major output the codes.
+template <int RS, bool ASYM>
 __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArgs a, int CL) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t qlds[];
     const int nthr = blockDim.x;
@@ -330,7 +333,8 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
     const int nchunk = a.K / 16;
     const int slab = G * RS;
     const int srows = qstage_rows(slab), pitch = qstage_pitch(nchunk);
-    float* red = reinterpret_cast<float*>(qlds + (size_t)srows * pitch);  // [2][QMAX_THREADS / 64][RS]
+    float* red = reinterpret_cast<float*>(qlds + (size_t)srows * pitch);  // [2][QMAX_THREADS / 64][RS] maxima (ASYM: then minima)
+    constexpr int RED_HALF = 2 * (QMAX_THREADS / 64) * RS;
     // Slabs per work-group: the grid is fixed (one work-group per CU); every group (expert)
     // is cut into runs of `nit` slabs, so no work-group does more than nit slabs whatever the
     // group sizes are, and sum_e ceil(slabs_e / nit) <= total / nit + groups <= grid.
@@ -409,10 +413,10 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
         fetch(src_nxt, raw_nxt);  // arrives while this slab is reduced and rounded
         // quotients x / s of the slab stay in registers from the reduction to the rounding
         float y[RS][16];
-        float amax[RS];
+        float amax[RS], amin[RS];
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
-            float m = 0.0f;
+            float m = 0.0f, mlo = 0.0f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) y[r][i] = 0.0f;
             if (src[r] >= 0) {
@@ -435,41 +439,79 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
 #pragma unroll
                     for (int i = 0; i < 16; ++i) y[r][i] = x[i] / sv[i];
                 }
+                if constexpr (ASYM) {  // the range always contains 0
 #pragma unroll
-                for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(y[r][i]));
+                    for (int i = 0; i < 16; ++i) {
+                        m = fmaxf(m, y[r][i]);
+                        mlo = fminf(mlo, y[r][i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(y[r][i]));
+                }
             }
             amax[r] = m;
+            amin[r] = mlo;
         }
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) amax[r] = fmaxf(amax[r], __shfl_xor(amax[r], o));
+            for (int o = 32; o > 0; o >>= 1) {
+                amax[r] = fmaxf(amax[r], __shfl_xor(amax[r], o));
+                if constexpr (ASYM) amin[r] = fminf(amin[r], __shfl_xor(amin[r], o));
+            }
         }
         float* redp = red + (size_t)(it & 1) * (QMAX_THREADS / 64) * RS;
         if (lane == 0) {
 #pragma unroll
-            for (int r = 0; r < RS; ++r) redp[wave * RS + r] = amax[r];
+            for (int r = 0; r < RS; ++r) {
+                redp[wave * RS + r] = amax[r];
+                if constexpr (ASYM) redp[RED_HALF + wave * RS + r] = amin[r];
+            }
         }
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
             if (src[r] >= 0) {
                 uint32_t w[4] = {0, 0, 0, 0};
-                float m = 0.0f;
-                for (int w2 = 0; w2 < waves_per_group; ++w2) m = fmaxf(m, redp[(g * waves_per_group + w2) * RS + r]);
-                const float scale = m / 127.0f;
-                const float rscale = 1.0f / scale;
-                const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
-                if (m != 0.0f) {
-                    if (sfast) {  // the common case: the division through the reciprocal
+                float m = 0.0f, mlo = 0.0f;
+                for (int w2 = 0; w2 < waves_per_group; ++w2) {
+                    m = fmaxf(m, redp[(g * waves_per_group + w2) * RS + r]);
+                    if constexpr (ASYM) mlo = fminf(mlo, redp[RED_HALF + (g * waves_per_group + w2) * RS + r]);
+                }
+                float scale, z = 0.0f;
+                if constexpr (ASYM) {
+                    const float range = m - mlo;
+                    scale = 0.0f;
+                    if (range != 0.0f) {
+                        scale = range / 255.0f;
+                        z = fminf(fmaxf(rintf(-mlo / scale), 0.0f), 255.0f);
+                        const float rscale = 1.0f / scale;
+                        const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
                         float q[16];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) q[i] = div_by(y[r][i], scale, rscale, true);
+                        for (int i = 0; i < 16; ++i) {
+                            const float qv = sfast ? div_by(y[r][i], scale, rscale, true) : y[r][i] / scale;
+                            q[i] = fminf(fmaxf(rintf(qv) + z, 0.0f), 255.0f);  // an integer in [0, 255]
+                        }
 #pragma unroll
                         for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
-                    } else {
+                    }
+                } else {
+                    scale = m / 127.0f;
+                    const float rscale = 1.0f / scale;
+                    const bool sfast = scale >= 0x1p-100f && scale <= 0x1p100f;
+                    if (m != 0.0f) {
+                        if (sfast) {  // the common case: the division through the reciprocal
+                            float q[16];
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[r][i], scale) & 0xff) << (8 * (i % 4));
+                            for (int i = 0; i < 16; ++i) q[i] = div_by(y[r][i], scale, rscale, true);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) w[i] = round_pack4(q[4 * i], q[4 * i + 1], q[4 * i + 2], q[4 * i + 3]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) w[i / 4] |= (uint32_t)(code_of(y[r][i], scale) & 0xff) << (8 * (i % 4));
+                        }
                     }
                 }
                 const uint4 code = make_uint4(w[0], w[1], w[2], w[3]);
@@ -477,9 +519,15 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
                 if (c == r) {
                     if (a.scale_dest) a.scale_dest[t] = scale;
                     if (a.scale) a.scale[src[r]] = scale;
+                    if constexpr (ASYM) {
+                        if (a.zp_dest) a.zp_dest[t] = (int32_t)z;
+                        if (a.zp) a.zp[src[r]] = (int32_t)z;
+                    }
                 }
                 if (a.q_rm) *reinterpret_cast<uint4*>(a.q_rm + (size_t)src[r] * a.ldq + c * 16) = code;
-                *reinterpret_cast<uint4*>(qlds + (size_t)(staged + g * RS + r) * pitch + c * 16) = code;
+                // the operand of the signed matrix instruction: code - 128
+                const uint4 packed = ASYM ? make_uint4(w[0] ^ 0x80808080u, w[1] ^ 0x80808080u, w[2] ^ 0x80808080u, w[3] ^ 0x80808080u) : code;
+                *reinterpret_cast<uint4*>(qlds + (size_t)(staged + g * RS + r) * pitch + c * 16) = packed;
             }
         }
         staged += slab;
@@ -843,19 +891,25 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
             n_cu = v > 64 ? v : 256;
         }
         if (rows / (LRS * G) >= n_cu) {
-            const size_t red_bytes = 2 * (QMAX_THREADS / 64) * LRS * sizeof(float);
+            const size_t red_bytes = 4 * (QMAX_THREADS / 64) * LRS * sizeof(float);  // maxima and (asymmetric codes) minima
             const size_t lds = (size_t)qstage_rows(LRS * G) * qstage_pitch(nchunk) + red_bytes;
             static std::once_flag once;
             static hipError_t attr_err = hipSuccess;
             std::call_once(once, [&] {  // the largest case: one row group, QMAX_THREADS chunks
-                attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               QSTAGE * qstage_pitch(QMAX_THREADS) + (int)red_bytes);
+                const int most = QSTAGE * qstage_pitch(QMAX_THREADS) + (int)red_bytes;
+                attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS, false>, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+                if (attr_err == hipSuccess)
+                    attr_err = hipFuncSetAttribute((const void*)smooth_quant_lds_kernel<LRS, true>, hipFuncAttributeMaxDynamicSharedMemorySize, most);
             });
             HAQ_CHECK_HIP(attr_err);
-            hipLaunchKernelGGL(smooth_quant_lds_kernel<LRS>, dim3(n_cu), dim3(threads), lds, st, a, CL);
+            if (a.zp_dest)
+                hipLaunchKernelGGL((smooth_quant_lds_kernel<LRS, true>), dim3(n_cu), dim3(threads), lds, st, a, CL);
+            else
+                hipLaunchKernelGGL((smooth_quant_lds_kernel<LRS, false>), dim3(n_cu), dim3(threads), lds, st, a, CL);
             HAQ_CHECK_HIP(hipGetLastError());
             return HAQ_OK;
         }
+        if (a.zp_dest) return HAQ_ERR_UNSUPPORTED;  // asymmetric codes: only the pipelined kernel; the caller has a row kernel
         // otherwise the register-resident single pass, at most 4 rows per thread
         const int RS = QBLOCK_ROWS / G > 4 ? 4 : QBLOCK_ROWS / G;
         const int brows = RS * G;
@@ -868,6 +922,7 @@ int launch_quant(const QuantArgs& a, hipStream_t st) {
         HAQ_CHECK_HIP(hipGetLastError());
         return HAQ_OK;
     }
+    if (a.zp_dest) return HAQ_ERR_UNSUPPORTED;
     switch (QBLOCK_ROWS / G) {
         case 8: hipLaunchKernelGGL(smooth_quant_kernel<8>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
         case 4: hipLaunchKernelGGL(smooth_quant_kernel<4>, dim3(blocks), dim3(threads), 0, st, a, CL); break;
