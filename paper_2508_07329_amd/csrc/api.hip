@@ -336,7 +336,21 @@ int32_t haq_w8a8_linear_asym(const void* x_fp16, int64_t ldx, const float* s, co
     hipStream_t st = (hipStream_t)stream;
     const LinearWs w = carve_linear(workspace, T, K);
     int32_t* zp = reinterpret_cast<int32_t*>((uint8_t*)workspace + w.bytes);
-    int rc = launch_asym_quant((const __half*)x_fp16, ldx, s, T, K, w.q_cm, w.R, q_dbg, K, w.sx, zp, st);
+    // long batches: the pipelined quantiser; short ones: the register-resident kernel
+    QuantArgs pa{};
+    pa.x = (const __half*)x_fp16;
+    pa.ldx = ldx;
+    pa.s = s;
+    pa.T = T;
+    pa.K = K;
+    pa.q_rm = (int8_t*)q_dbg;
+    pa.ldq = K;
+    pa.q_cm = w.q_cm;
+    pa.R = w.R;
+    pa.scale_dest = w.sx;
+    pa.zp_dest = zp;
+    int rc = launch_quant(pa, st);
+    if (rc == HAQ_ERR_UNSUPPORTED) rc = launch_asym_quant((const __half*)x_fp16, ldx, s, T, K, w.q_cm, w.R, q_dbg, K, w.sx, zp, st);
     if (rc == HAQ_ERR_UNSUPPORTED) HAQ_FAIL(HAQ_ERR_UNSUPPORTED, "haq_w8a8_linear_asym: K=%d not supported", K);
     if (rc != HAQ_OK) return rc;
     if (sx_dbg) HAQ_CHECK_HIP(hipMemcpyAsync(sx_dbg, w.sx, (size_t)T * sizeof(float), hipMemcpyDeviceToDevice, st));

@@ -621,7 +621,8 @@ def test_hessian_quantiser_rejects_an_indefinite_matrix():
 
 # ------------------------------------------------------------------ asymmetric activation codes (dense linear)
 @pytest.mark.parametrize("T,K,N,act,relu_in", [(16, 768, 3072, "relu", False), (203, 320, 208, "none", True),
-                                                (1, 64, 16, "none", False), (2048, 4096, 1024, "relu", True)])
+                                                (1, 64, 16, "none", False), (2048, 4096, 1024, "relu", True),
+                                                (4101, 128, 32, "relu", False), (2051, 4096, 64, "none", False)])
 def test_linear_asym_bit_exact(T, K, N, act, relu_in):
     X, _, _ = hi.hidden_states(90 + T, T, K, n_outlier=max(1, K // 200))
     if relu_in:
