@@ -793,6 +793,27 @@ def test_moe_asym_mixtral(layer, name):
     _check_moe_asym(_mixtral_case(wl, layer), layer["dev_experts"], layer["colsums"], np.arange(wl.T))
 
 
+def test_zero_token_calls_return_empty_outputs_on_every_block_level_entry_point():
+    """T = 0 is a valid batch: every call returns an empty output and launches nothing."""
+    m = offline.small_moe(seed=240, T=4, H=128, I=256, E=4)
+    ex = upload_experts(m["experts"])
+    X0 = torch.empty((0, 128), dtype=torch.float16, device="cuda:0")
+    L0 = torch.empty((0, 4), dtype=torch.float16, device="cuda:0")
+    s_in = dev(m["s_in"])
+    assert haq.haq_moe_w8a8_ffn(X0, L0, s_in, ex, 256).shape == (0, 128)
+    assert haq.haq_moe_w8a8_ffn_asym(X0, L0, s_in, ex, _colsums(m["experts"]), 256).shape == (0, 128)
+    out0 = torch.empty((0, 128), dtype=torch.float16, device="cuda:0")
+    assert haq.haq_moe_w8a8_ffn_static(X0, L0, s_in, ex, 256, out=out0).shape == (0, 128)
+    e0 = m["experts"][0]
+    w1, sw1 = dev(e0.w1), dev(e0.sw1)
+    assert haq.haq_w8a8_linear(X0, s_in, haq.haq_pack_weight(w1), sw1, 256).shape == (0, 256)
+    assert haq.haq_w8a8_linear_kn(X0, s_in, w1, sw1).shape == (0, 256)
+    assert haq.haq_w8a8_linear_asym(X0, s_in, haq.haq_pack_weight(w1), sw1, haq.haq_weight_colsum(w1), 256).shape == (0, 256)
+    assert haq.haq_w8a8_ffn(X0, s_in, haq.haq_pack_weight(w1), sw1, 256, haq.HAQ_ACT_RELU, dev(e0.s_mid), haq.haq_pack_weight(dev(e0.w2)),
+                            dev(e0.sw2), 128).shape == (0, 128)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ offload policy: Eq. 7-8 decision and CPU experts
 def _cpu_handles(experts, ids):
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
