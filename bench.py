@@ -117,11 +117,15 @@ def _quant_record(name, rows, cols, ms):
                     "lane_instr_per_element": QUANT_VALU_PER_ELEMENT}}
 
 
-def _mfma_ceiling(torch, haq, data, work_groups, seconds):
-    """Sustained rate of the pure-MFMA loop (operands in registers, no memory traffic) on `data`."""
+def _mfma_ceiling(torch, haq, data, work_groups, seconds, level=0):
+    """Sustained rate of the pure-MFMA loop (operands in registers, no memory traffic) on `data`; level 1-3: the
+    same loop with the GEMM kernel's K-loop ingredients added (LDS fragment reads; + barrier; + direct-to-LDS loads)."""
     iters = 20000
     out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)
-    launch = lambda: haq.haq_probe_mfma_i8(data, iters, work_groups, out=out)
+    if level == 0:
+        launch = lambda: haq.haq_probe_mfma_i8(data, iters, work_groups, out=out)
+    else:
+        launch = lambda: haq.haq_probe_kloop_i8(data, level, iters, work_groups, out=out)
     ev = _events(torch, 2)
     launch()
     torch.cuda.synchronize()
@@ -281,6 +285,14 @@ def bench_ffn(args, torch, haq, hi, cpu_seconds=10.0):
         roof["sustained_mfma_ceiling"] = ceil
         roof["peak_sustained"] = best
         roof["frac_sustained"] = achieved / best
+        # the same loop (two work-groups per CU, workload codes) with the K loop's ingredients added one at a time:
+        # what each of them costs the matrix pipes; the GEMM's own K-loop rate follows from gemm_sweep's K sweep
+        ladder = {"0_mfma_only_registers": ceil["workload_codes/2_waves_per_simd"]["TOPs"]}
+        for level, label in ((1, "1_plus_lds_fragment_reads"), (2, "2_plus_barrier_per_k_step"), (3, "3_plus_direct_to_lds_loads_from_l2")):
+            v, dur, clk = _mfma_ceiling(torch, haq, data_wl, 512, 0.3, level=level)
+            ladder[label] = v
+            ladder[label + "_clock_mhz"] = clk
+        roof["k_loop_ladder_TOPs"] = ladder
 
     cpu = None
     if not args.no_cpu_baseline:

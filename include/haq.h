@@ -510,6 +510,15 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
  * out: int32 [256 * 128] device, the accumulators of work-group 0 (thread t,
  * tile (i, j), register r at ((t * 8 + i * 4 + j) * 16 + r), int32 wrap-around).
  *
+ * haq_probe_kloop_i8: the same operands, register tile, work-group shape, `out`
+ * and accumulators as haq_probe_mfma_i8, with the ingredients of the GEMM
+ * kernel's K loop added one level at a time: 1 = the operand fragments are
+ * re-read from LDS for every K-step; 2 = plus one work-group barrier per K-step;
+ * 3 = plus the direct-to-LDS loads that refill the ring (six 1 KiB loads per
+ * wave and K-step, all work-groups from the same 24 KiB).  One iteration is two
+ * K-steps (32 matrix instructions per wave).  The rate lost from one level to the
+ * next is what that ingredient costs the matrix pipes.
+ *
  * haq_probe_clock: one wave spins for ticks_100mhz periods of the constant 100 MHz
  * counter; out[0] = shader clock cycles elapsed, out[1] = 100 MHz periods elapsed
  * (uint64, device).  Launched on a second stream it reads the shader clock while
@@ -517,6 +526,7 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
 int32_t haq_profile_enable(int32_t on);
 int32_t haq_profile_read(int32_t max_stages, int32_t* n_stages, const char** names, float* ms);
 int32_t haq_probe_mfma_i8(const int8_t* data, int32_t iters, int32_t work_groups, int32_t* out, void* stream);
+int32_t haq_probe_kloop_i8(const int8_t* data, int32_t level, int32_t iters, int32_t work_groups, int32_t* out, void* stream);
 int32_t haq_probe_clock(uint64_t* out, int64_t ticks_100mhz, void* stream);
 
 /* ------------------------------------------------------------------------

@@ -24,7 +24,7 @@ __all__ = [
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
     "haq_linear_kn_workspace_bytes", "haq_w8a8_linear_kn",
-    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
+    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_kloop_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -49,7 +49,7 @@ EXPORTED_SYMBOLS = [
     "haq_ctx_cache_stats", "haq_ctx_cache_invalidate", "haq_offload_n_critical", "haq_select_experts", "haq_lru_plan",
     "haq_cpu_expert_create", "haq_cpu_expert_destroy", "haq_cpu_expert_ffn", "haq_ctx_set_offload_policy", "haq_ctx_register_cpu_expert", "haq_ctx_last_decisions",
     "haq_linear_kn_workspace_bytes", "haq_w8a8_linear_kn",
-    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_clock",
+    "haq_moe_w8a8_ffn_static", "haq_moe_asym_workspace_bytes", "haq_moe_w8a8_ffn_asym", "haq_ctx_last_call_timing", "haq_profile_enable", "haq_profile_read", "haq_probe_mfma_i8", "haq_probe_kloop_i8", "haq_probe_clock",
     "haq_hessian_quant_workspace_bytes", "haq_inverse_cholesky_workspace_bytes", "haq_hessian_f64",
     "haq_inverse_cholesky_upper_f64", "haq_hessian_quant_weight",
     "haq_weight_colsum", "haq_linear_asym_workspace_bytes", "haq_w8a8_linear_asym",
@@ -466,6 +466,16 @@ def haq_probe_mfma_i8(data, iters: int, work_groups: int, *, out=None):
     if out is None:
         out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)
     _check(lib().haq_probe_mfma_i8(_ptr(data), iters, work_groups, _ptr(out), _stream()))
+    return out
+
+
+def haq_probe_kloop_i8(data, level: int, iters: int, work_groups: int, *, out=None):
+    """The K loop of the GEMM kernel rebuilt on the probe's operands: level 1 adds the LDS fragment reads, 2 the barrier
+    per K-step, 3 the direct-to-LDS loads.  Same accumulators as haq_probe_mfma_i8 for the same iters."""
+    assert data.numel() >= 24576
+    if out is None:
+        out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)
+    _check(lib().haq_probe_kloop_i8(_ptr(data), level, iters, work_groups, _ptr(out), _stream()))
     return out
 
 

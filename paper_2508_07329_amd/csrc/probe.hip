@@ -55,6 +55,117 @@ __global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(const int8_t* dat
     if (blockIdx.x != 0 && fold == 0x5a5a5a5a && iters < 0) out[0] = fold;
 }
 
+// The K loop of the GEMM kernel rebuilt one ingredient at a time, on the same operand sets and with the same
+// register tile, so that what each ingredient costs the matrix pipes can be read off as a rate.  A work-group is
+// four waves; LDS holds a ring of three stages of 24 KB, each stage = the 24 fragments of `data` (one K-step of a
+// 128 x 256 tile has exactly this size).  One iteration = two K-steps = 32 MFMAs per wave that use every operand
+// set once, so the accumulators equal those of mfma_i8_probe_kernel for the same `iters`.
+//   LEVEL 1: the 12 fragments of each K-step are re-read from LDS (ds_read_b128, one behind each of the first MFMAs
+//            of a half step, as in the GEMM kernel) instead of staying in registers;
+//   LEVEL 2: plus one s_barrier per K-step;
+//   LEVEL 3: plus six direct-to-LDS loads of 1 KB per wave and K-step that refill the stage just vacated (with the
+//            bytes it already holds: all work-groups fetch the same 24 KB, which stay in L2).
+constexpr int LD_STAGES = 3, LD_STAGE_BYTES = 24 * 1024, LD_LPW = 6;
+#define PR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+#define PR_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
+#define PR_CFENCE() asm volatile("" ::: "memory")
+
+template <int LEVEL>
+__global__ __launch_bounds__(256, 2) void mfma_i8_ladder_kernel(const int8_t* data, int iters, int32_t* out) {
+    extern __shared__ __attribute__((aligned(1024))) int8_t ring[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    auto load_stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LD_LPW; ++i) {
+            const int g = wave + i * 4;  // 24 groups of 1 KB, six per wave
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(uintptr_t)(data + (size_t)g * 1024 + lane * 16),
+                                             (__attribute__((address_space(3))) void*)(ring + buf * LD_STAGE_BYTES + g * 1024), 16, 0, 0);
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < LD_STAGES; ++st) load_stage(st);
+    PR_WAIT_VMCNT(0);
+    PR_CFENCE();
+    __builtin_amdgcn_s_barrier();
+    PR_CFENCE();
+
+    v16i acc[PR_MI][PR_NI];
+#pragma unroll
+    for (int i = 0; i < PR_MI; ++i)
+#pragma unroll
+        for (int j = 0; j < PR_NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // fragments of operand set s in stage buf: token fragments first (groups 6s, 6s+1), then the four weight fragments
+    auto read_frags = [&](int buf, int set, v4i(&xa)[PR_MI], v4i(&xb)[PR_NI]) {
+        const int8_t* sb = ring + buf * LD_STAGE_BYTES + (set * 6) * 1024 + lane * 16;
+#pragma unroll
+        for (int i = 0; i < PR_MI; ++i) xa[i] = *reinterpret_cast<const v4i*>(sb + i * 1024);
+#pragma unroll
+        for (int j = 0; j < PR_NI; ++j) xb[j] = *reinterpret_cast<const v4i*>(sb + (PR_MI + j) * 1024);
+    };
+    auto mfmas = [&](v4i(&xa)[PR_MI], v4i(&xb)[PR_NI]) {
+#pragma unroll
+        for (int j = 0; j < PR_NI; ++j)
+#pragma unroll
+            for (int i = 0; i < PR_MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xb[j], xa[i], acc[i][j], 0, 0, 0);
+    };
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < PR_MI + PR_NI; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, PR_MI * PR_NI - (PR_MI + PR_NI), 0);
+    };
+    v4i fa[2][2][PR_MI], fb[2][2][PR_NI];  // [register buffer][half step][tile]
+    read_frags(0, 0, fa[0][0], fb[0][0]);
+    read_frags(0, 1, fa[0][1], fb[0][1]);
+    // K-step kt: MFMAs on its fragments (registers), LDS reads of the next K-step's, refill of its stage
+    auto body = [&](int cur, int set0, v4i(&ca)[2][PR_MI], v4i(&cb)[2][PR_NI], v4i(&na)[2][PR_MI], v4i(&nb)[2][PR_NI]) {
+        int nxt = cur + 1;
+        if (nxt >= LD_STAGES) nxt -= LD_STAGES;
+        if (LEVEL >= 3) PR_WAIT_VMCNT(LD_LPW * (LD_STAGES - 2));
+        PR_WAIT_LGKM0();
+        if (LEVEL >= 2) {
+            PR_CFENCE();
+            __builtin_amdgcn_s_barrier();
+            PR_CFENCE();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (LEVEL >= 3) load_stage(cur);
+        read_frags(nxt, set0, na[0], nb[0]);
+        mfmas(ca[0], cb[0]);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(nxt, set0 + 1, na[1], nb[1]);
+        mfmas(ca[1], cb[1]);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int st = 0;
+    for (int it = 0; it < iters; ++it) {
+        // the registers hold sets 0, 1; the next K-step reads sets 2, 3, the one after it 0, 1 again
+        body(st, 2, fa[0], fb[0], fa[1], fb[1]);
+        st = st + 1 >= LD_STAGES ? 0 : st + 1;
+        body(st, 0, fa[1], fb[1], fa[0], fb[0]);
+        st = st + 1 >= LD_STAGES ? 0 : st + 1;
+    }
+    PR_WAIT_VMCNT(0);
+    int fold = 0;
+#pragma unroll
+    for (int i = 0; i < PR_MI; ++i)
+#pragma unroll
+        for (int j = 0; j < PR_NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (blockIdx.x == 0) out[((size_t)threadIdx.x * 8 + i * 4 + j) * 16 + r] = acc[i][j][r];
+                fold ^= acc[i][j][r];
+            }
+    if (blockIdx.x != 0 && fold == 0x5a5a5a5a && iters < 0) out[0] = fold;
+}
+
 // One wave spins for `ticks` periods of the constant 100 MHz counter and reports how far the shader
 // clock counter moved meanwhile: out[0] = shader clock ticks, out[1] = 100 MHz ticks.
 __global__ void clock_probe_kernel(unsigned long long* out, unsigned long long ticks) {
@@ -79,6 +190,27 @@ int32_t haq_probe_mfma_i8(const int8_t* data, int32_t iters, int32_t work_groups
     if (iters < 1 || iters > (1 << 24) || work_groups < 1 || work_groups > 65535)
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_probe_mfma_i8: iters=%d work_groups=%d", iters, work_groups);
     hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(work_groups), dim3(256), 0, (hipStream_t)stream, data, iters, out);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int32_t haq_probe_kloop_i8(const int8_t* data, int32_t level, int32_t iters, int32_t work_groups, int32_t* out, void* stream) {
+    if (!data || !out || !aligned16(data)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_probe_kloop_i8: null or misaligned buffer");
+    if (level < 1 || level > 3 || iters < 1 || iters > (1 << 24) || work_groups < 1 || work_groups > 65535)
+        HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_probe_kloop_i8: level=%d iters=%d work_groups=%d", level, iters, work_groups);
+    const size_t lds = (size_t)LD_STAGES * LD_STAGE_BYTES;
+    static hipError_t attr_err[3] = {hipErrorUnknown, hipErrorUnknown, hipErrorUnknown};
+    const void* kern = level == 1 ? (const void*)mfma_i8_ladder_kernel<1> : level == 2 ? (const void*)mfma_i8_ladder_kernel<2>
+                                                                                         : (const void*)mfma_i8_ladder_kernel<3>;
+    if (attr_err[level - 1] != hipSuccess) attr_err[level - 1] = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    HAQ_CHECK_HIP(attr_err[level - 1]);
+    hipStream_t st = (hipStream_t)stream;
+    if (level == 1)
+        hipLaunchKernelGGL(mfma_i8_ladder_kernel<1>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
+    else if (level == 2)
+        hipLaunchKernelGGL(mfma_i8_ladder_kernel<2>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
+    else
+        hipLaunchKernelGGL(mfma_i8_ladder_kernel<3>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -682,6 +682,10 @@ def test_mfma_probe_computes_the_stated_dot_products():
             wrow = 8 * (r // 4) + 4 * (l // 32) + r % 4
             ref[t, :, r] = prod[:, :, wrow, l % 32].reshape(8)
     assert np.array_equal(out.astype(np.int64), ref)
+    # the K-loop probes (fragments re-read from LDS; + barrier; + direct-to-LDS refills) compute the same sums
+    for level in (1, 2, 3):
+        got = host(haq.haq_probe_kloop_i8(dev(data), level, iters, 5))
+        assert np.array_equal(got.astype(np.int64), ref), f"level {level}"
 
 
 def test_stage_profile_and_clock_probe_report():
