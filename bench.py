@@ -288,7 +288,8 @@ def bench_ffn(args, torch, haq, hi, cpu_seconds=10.0):
         # the same loop (two work-groups per CU, workload codes) with the K loop's ingredients added one at a time:
         # what each of them costs the matrix pipes; the GEMM's own K-loop rate follows from gemm_sweep's K sweep
         ladder = {"0_mfma_only_registers": ceil["workload_codes/2_waves_per_simd"]["TOPs"]}
-        for level, label in ((1, "1_plus_lds_fragment_reads"), (2, "2_plus_barrier_per_k_step"), (3, "3_plus_direct_to_lds_loads_from_l2")):
+        for level, label in ((1, "1_plus_lds_fragment_reads"), (2, "2_plus_barrier_per_k_step"), (3, "3_plus_direct_to_lds_loads_from_l2"),
+                             (4, "4_as_3_but_refill_through_registers")):
             v, dur, clk = _mfma_ceiling(torch, haq, data_wl, 512, 0.3, level=level)
             ladder[label] = v
             ladder[label + "_clock_mhz"] = clk

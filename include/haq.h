@@ -515,7 +515,8 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
  * kernel's K loop added one level at a time: 1 = the operand fragments are
  * re-read from LDS for every K-step; 2 = plus one work-group barrier per K-step;
  * 3 = plus the direct-to-LDS loads that refill the ring (six 1 KiB loads per
- * wave and K-step, all work-groups from the same 24 KiB).  One iteration is two
+ * wave and K-step, all work-groups from the same 24 KiB); 4 = as 3 with the
+ * refill through registers (vector loads, LDS writes a K-step later).  One iteration is two
  * K-steps (32 matrix instructions per wave).  The rate lost from one level to the
  * next is what that ingredient costs the matrix pipes.
  *

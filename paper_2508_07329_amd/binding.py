@@ -471,7 +471,7 @@ def haq_probe_mfma_i8(data, iters: int, work_groups: int, *, out=None):
 
 def haq_probe_kloop_i8(data, level: int, iters: int, work_groups: int, *, out=None):
     """The K loop of the GEMM kernel rebuilt on the probe's operands: level 1 adds the LDS fragment reads, 2 the barrier
-    per K-step, 3 the direct-to-LDS loads.  Same accumulators as haq_probe_mfma_i8 for the same iters."""
+    per K-step, 3 the direct-to-LDS loads (4: the same refill through registers).  Same accumulators as haq_probe_mfma_i8 for the same iters."""
     assert data.numel() >= 24576
     if out is None:
         out = torch.empty((256, 8, 16), dtype=torch.int32, device=data.device)

@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(const int8_t* dat
 //            of a half step, as in the GEMM kernel) instead of staying in registers;
 //   LEVEL 2: plus one s_barrier per K-step;
 //   LEVEL 3: plus six direct-to-LDS loads of 1 KB per wave and K-step that refill the stage just vacated (with the
-//            bytes it already holds: all work-groups fetch the same 24 KB, which stay in L2).
+//            bytes it already holds: all work-groups fetch the same 24 KB, which stay in L2);
+//   LEVEL 4: as 3, but the refill goes through registers (global_load_dwordx4, ds_write_b128 one K-step later).
 constexpr int LD_STAGES = 3, LD_STAGE_BYTES = 24 * 1024, LD_LPW = 6;
 #define PR_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define PR_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
@@ -120,13 +121,17 @@ __global__ __launch_bounds__(256, 2) void mfma_i8_ladder_kernel(const int8_t* da
         __builtin_amdgcn_sched_group_barrier(0x008, PR_MI * PR_NI - (PR_MI + PR_NI), 0);
     };
     v4i fa[2][2][PR_MI], fb[2][2][PR_NI];  // [register buffer][half step][tile]
+    v4i tmp[LD_LPW];
+#pragma unroll
+    for (int i = 0; i < LD_LPW; ++i) tmp[i] = *reinterpret_cast<const v4i*>(data + (size_t)(wave + i * 4) * 1024 + lane * 16);
     read_frags(0, 0, fa[0][0], fb[0][0]);
     read_frags(0, 1, fa[0][1], fb[0][1]);
     // K-step kt: MFMAs on its fragments (registers), LDS reads of the next K-step's, refill of its stage
     auto body = [&](int cur, int set0, v4i(&ca)[2][PR_MI], v4i(&cb)[2][PR_NI], v4i(&na)[2][PR_MI], v4i(&nb)[2][PR_NI]) {
         int nxt = cur + 1;
         if (nxt >= LD_STAGES) nxt -= LD_STAGES;
-        if (LEVEL >= 3) PR_WAIT_VMCNT(LD_LPW * (LD_STAGES - 2));
+        if (LEVEL == 3) PR_WAIT_VMCNT(LD_LPW * (LD_STAGES - 2));
+        if (LEVEL == 4) PR_WAIT_VMCNT(0);
         PR_WAIT_LGKM0();
         if (LEVEL >= 2) {
             PR_CFENCE();
@@ -134,7 +139,17 @@ __global__ __launch_bounds__(256, 2) void mfma_i8_ladder_kernel(const int8_t* da
             PR_CFENCE();
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (LEVEL >= 3) load_stage(cur);
+        if (LEVEL == 3) load_stage(cur);
+        if (LEVEL == 4) {
+            // the stage refill through registers: last K-step's loads go to LDS (into the stage vacated one K-step
+            // ago, read again in the next K-step, behind its barrier), this K-step's loads start
+            int prv = cur == 0 ? LD_STAGES - 1 : cur - 1;
+#pragma unroll
+            for (int i = 0; i < LD_LPW; ++i) *reinterpret_cast<v4i*>(ring + prv * LD_STAGE_BYTES + (wave + i * 4) * 1024 + lane * 16) = tmp[i];
+#pragma unroll
+            for (int i = 0; i < LD_LPW; ++i)
+                tmp[i] = *reinterpret_cast<const __attribute__((address_space(1))) v4i*>((uintptr_t)(data + (size_t)(wave + i * 4) * 1024 + lane * 16));
+        }
         read_frags(nxt, set0, na[0], nb[0]);
         mfmas(ca[0], cb[0]);
         interleave();
@@ -196,12 +211,14 @@ int32_t haq_probe_mfma_i8(const int8_t* data, int32_t iters, int32_t work_groups
 
 int32_t haq_probe_kloop_i8(const int8_t* data, int32_t level, int32_t iters, int32_t work_groups, int32_t* out, void* stream) {
     if (!data || !out || !aligned16(data)) HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_probe_kloop_i8: null or misaligned buffer");
-    if (level < 1 || level > 3 || iters < 1 || iters > (1 << 24) || work_groups < 1 || work_groups > 65535)
+    if (level < 1 || level > 4 || iters < 1 || iters > (1 << 24) || work_groups < 1 || work_groups > 65535)
         HAQ_FAIL(HAQ_ERR_INVALID_ARG, "haq_probe_kloop_i8: level=%d iters=%d work_groups=%d", level, iters, work_groups);
     const size_t lds = (size_t)LD_STAGES * LD_STAGE_BYTES;
-    static hipError_t attr_err[3] = {hipErrorUnknown, hipErrorUnknown, hipErrorUnknown};
-    const void* kern = level == 1 ? (const void*)mfma_i8_ladder_kernel<1> : level == 2 ? (const void*)mfma_i8_ladder_kernel<2>
-                                                                                         : (const void*)mfma_i8_ladder_kernel<3>;
+    static hipError_t attr_err[4] = {hipErrorUnknown, hipErrorUnknown, hipErrorUnknown, hipErrorUnknown};
+    const void* kern = level == 1   ? (const void*)mfma_i8_ladder_kernel<1>
+                       : level == 2 ? (const void*)mfma_i8_ladder_kernel<2>
+                       : level == 3 ? (const void*)mfma_i8_ladder_kernel<3>
+                                    : (const void*)mfma_i8_ladder_kernel<4>;
     if (attr_err[level - 1] != hipSuccess) attr_err[level - 1] = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     HAQ_CHECK_HIP(attr_err[level - 1]);
     hipStream_t st = (hipStream_t)stream;
@@ -209,8 +226,10 @@ int32_t haq_probe_kloop_i8(const int8_t* data, int32_t level, int32_t iters, int
         hipLaunchKernelGGL(mfma_i8_ladder_kernel<1>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
     else if (level == 2)
         hipLaunchKernelGGL(mfma_i8_ladder_kernel<2>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
-    else
+    else if (level == 3)
         hipLaunchKernelGGL(mfma_i8_ladder_kernel<3>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
+    else
+        hipLaunchKernelGGL(mfma_i8_ladder_kernel<4>, dim3(work_groups), dim3(256), lds, st, data, iters, out);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }

@@ -683,7 +683,7 @@ def test_mfma_probe_computes_the_stated_dot_products():
             ref[t, :, r] = prod[:, :, wrow, l % 32].reshape(8)
     assert np.array_equal(out.astype(np.int64), ref)
     # the K-loop probes (fragments re-read from LDS; + barrier; + direct-to-LDS refills) compute the same sums
-    for level in (1, 2, 3):
+    for level in (1, 2, 3, 4):
         got = host(haq.haq_probe_kloop_i8(dev(data), level, iters, 5))
         assert np.array_equal(got.astype(np.int64), ref), f"level {level}"
 
