@@ -17,7 +17,10 @@ namespace {
 #define HAQ_MINB 2
 #define HAQ_STAGES 3
 #endif
-constexpr int BM = HAQ_BM, BN = HAQ_BN, WAVES_M = 2, WAVES_N = 2, STAGES = HAQ_STAGES, MINB = HAQ_MINB;
+#ifndef HAQ_WAVES_M
+#define HAQ_WAVES_M 2
+#endif
+constexpr int BM = HAQ_BM, BN = HAQ_BN, WAVES_M = HAQ_WAVES_M, WAVES_N = 2, STAGES = HAQ_STAGES, MINB = HAQ_MINB;
 using Shape = GemmShape<BM, BN, WAVES_M, WAVES_N, STAGES>;
 
 template <int EPI, bool DBG>
@@ -38,9 +41,9 @@ int launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
 // work-group slots empty: twice the tiles, 49 KB of LDS, three work-groups per CU.
 constexpr int SMALL_TILE_LIMIT = 256;  // 128 x 256 tiles that would not even give every CU one work-group
 constexpr int BN_S = 128, MINB_S = 3;
-using ShapeS = GemmShape<128, BN_S, WAVES_M, WAVES_N, 3>;
+using ShapeS = GemmShape<128, BN_S, 2, 2, 3>;
 int launch_small(const GemmArgs& a, dim3 grid, hipStream_t st) {
-    auto kern = gemm_i8_kernel<128, BN_S, WAVES_M, WAVES_N, 3, MINB_S, EPI_LINEAR, false>;
+    auto kern = gemm_i8_kernel<128, BN_S, 2, 2, 3, MINB_S, EPI_LINEAR, false>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -52,6 +55,25 @@ int launch_small(const GemmArgs& a, dim3 grid, hipStream_t st) {
     return HAQ_OK;
 }
 
+// 256 x 256 tiles, 8 waves (4 x 2, the same 64 x 128 wave tile and per-wave code as the main shape), one
+// work-group per CU: a third fewer direct-to-LDS bytes per matrix instruction, which is what limits the K loop.
+// For dense problems with at least two full rounds of such tiles (one per CU and round); measured +3 % on
+// 2048..8192 x 4096 x 16384, -8 % on a single round, and slower on ragged expert groups (more padding rows).
+constexpr int LARGE_TILE_MIN = 512;
+using ShapeL = GemmShape<256, 256, 4, 2, 3>;
+int launch_large(const GemmArgs& a, dim3 grid, hipStream_t st) {
+    auto kern = gemm_i8_kernel<256, 256, 4, 2, 3, 1, EPI_LINEAR, false>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ShapeL::LDS_BYTES);
+    });
+    HAQ_CHECK_HIP(attr_err);
+    hipLaunchKernelGGL(kern, grid, dim3(ShapeL::THREADS), ShapeL::LDS_BYTES, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
 }  // namespace
 
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
@@ -59,6 +81,10 @@ int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
     // upper bound on the M tiles: exact for one matrix; rows/BM plus one partial tile per group otherwise
     const int mt = a.offsets ? a.max_rows / BM + a.n_sel : cdiv(a.M, BM);
     if (mt <= 0 || ntn <= 0) return HAQ_OK;
+    if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg) {
+        const int64_t tiles_l = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 256);
+        if (tiles_l >= LARGE_TILE_MIN) return launch_large(a, dim3((unsigned)round_up(tiles_l, 8)), st);
+    }
     if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg && mt * ntn <= SMALL_TILE_LIMIT) {
         const int ntn_s = cdiv(a.N, BN_S), mt_s = cdiv(a.M, 128);
         return launch_small(a, dim3((unsigned)round_up((int64_t)mt_s * ntn_s, 8)), st);
