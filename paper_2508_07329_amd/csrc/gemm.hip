@@ -20,7 +20,10 @@ namespace {
 #ifndef HAQ_WAVES_M
 #define HAQ_WAVES_M 2
 #endif
-constexpr int BM = HAQ_BM, BN = HAQ_BN, WAVES_M = HAQ_WAVES_M, WAVES_N = 2, STAGES = HAQ_STAGES, MINB = HAQ_MINB;
+#ifndef HAQ_WAVES_N
+#define HAQ_WAVES_N 2
+#endif
+constexpr int BM = HAQ_BM, BN = HAQ_BN, WAVES_M = HAQ_WAVES_M, WAVES_N = HAQ_WAVES_N, STAGES = HAQ_STAGES, MINB = HAQ_MINB;
 using Shape = GemmShape<BM, BN, WAVES_M, WAVES_N, STAGES>;
 
 template <int EPI, bool DBG>

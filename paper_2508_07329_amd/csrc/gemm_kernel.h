@@ -114,6 +114,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
     constexpr int GA = 4 * BM / 64, GB = 4 * BN / 64;  // 1 KB (64 rows x 16 B) load groups per K-step
     constexpr int LPW = (GA + GB) / NW;                // direct-to-LDS loads per wave per K-step
     static_assert((GA + GB) % NW == 0, "load groups must divide among the waves");
+    // a tile's loads cover BM rows and BN channels whatever the problem size: the packed operands are padded for that
+    static_assert(NPAD % BN == 0, "a channel tile must not reach past the padded width of the packed weights");
+    static_assert(BM <= 256, "packed activations carry 256 rows of padding");
     constexpr bool SWIGLU = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_ASYM;
     constexpr bool ASYM = EPI == EPI_LINEAR_ASYM || EPI == EPI_SWIGLU_ASYM;
     static_assert(!SWIGLU || NI % 2 == 0, "gate/up blocks come in pairs");
