@@ -536,8 +536,10 @@ __global__ __launch_bounds__(QMAX_THREADS) void smooth_quant_lds_kernel(QuantArg
             __syncthreads();  // the staged codes are complete
             if (a.q_cm) {
                 const int nrow = min(staged, row_end - stage_t0);
+                // srows is a power of two (8 or 16): shifts instead of a division by a run-time value
+                const int sh = srows == 8 ? 3 : 4;
                 for (int i = tid; i < nchunk * srows; i += nthr) {
-                    const int row = i % srows, ch = i / srows;
+                    const int row = i & (srows - 1), ch = i >> sh;
                     if (row < nrow)
                         *reinterpret_cast<uint4*>(a.q_cm + ((size_t)ch * a.R + stage_t0 + row) * 16) =
                             *reinterpret_cast<const uint4*>(qlds + (size_t)row * pitch + ch * 16);
