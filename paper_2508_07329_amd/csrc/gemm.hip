@@ -42,7 +42,10 @@ int launch_one(const GemmArgs& a, dim3 grid, hipStream_t st) {
 
 // 128 x 128 tiles (wave tile 64 x 64) for problems whose 128 x 256 tiling would leave half of the
 // work-group slots empty: twice the tiles, 49 KB of LDS, three work-groups per CU.
-constexpr int SMALL_TILE_LIMIT = 256;  // 128 x 256 tiles that would not even give every CU one work-group
+#ifndef HAQ_SMALL_TILE_LIMIT
+#define HAQ_SMALL_TILE_LIMIT 256
+#endif
+constexpr int SMALL_TILE_LIMIT = HAQ_SMALL_TILE_LIMIT;  // 128 x 256 tiles that would not even give every CU one work-group
 constexpr int BN_S = 128, MINB_S = 3;
 using ShapeS = GemmShape<128, BN_S, 2, 2, 3>;
 int launch_small(const GemmArgs& a, dim3 grid, hipStream_t st) {
