@@ -631,6 +631,9 @@ def test_linear_asym_bit_exact(T, K, N, act, relu_in):
         X = np.maximum(X, 0).astype(np.float16)   # one-sided rows: zero point 0
     if T > 4:
         X[3] = 0
+    if T > 8:
+        X[5] = -np.abs(X[5])                       # all negative: zero point 255
+        X[7] = np.float16(0.75)                    # a constant row
     W = hi.gaussian_weight(90 + T, 0, K, N)
     s, Wq, sw = offline.quantize_linear(X, W)
     y_ref, acc_ref, q_ref, sx_ref, zp_ref = oracle.w8a8_linear_asym(X, s, Wq, sw, act, full=True)
