@@ -446,7 +446,8 @@ size_t haq_moe_workspace_bytes(int32_t T, int32_t H, int32_t I, int32_t E);
  * and, when the offload policy sends experts to the CPU, for their computation;
  * everything else of the call is enqueued as usual.
  * Launch shapes (same results on every path): more than 64 tokens or any
- * host-resident expert -> grouped tiled GEMMs; up to 64 tokens, all experts
+ * host-resident expert -> grouped tiled GEMMs (a streamed expert with at most 64
+ * rows runs on the weight-streaming kernels when H and I allow); up to 64 tokens, all experts
  * resident, H % 128 == 0 and I % 256 == 0 -> weight-streaming kernels (five
  * launches); one or two tokens with H <= 8192, I <= 16384 and none of q, sx, hq,
  * sh asked for in dbg -> three launches (those four stay on chip on that path). */
@@ -469,8 +470,9 @@ int32_t haq_moe_w8a8_ffn(haq_ctx* ctx, const void* x_fp16, int64_t ldx, const vo
  * GEMM epilogues add (128 - zero point) * column sum of the expert's weight codes:
  * colsums_host [E] (HOST array) points at int32 device vectors cs1 [I], cs3 [I]
  * (of the w1 and w3 codes) and cs2 [H] (of the w2 codes) from haq_weight_colsum.
- * Every expert must be device resident; every batch size takes the grouped tiled
- * GEMMs.  2 <= E <= 32, top_k = 2, H % 64 == 0, I % 64 == 0, both <= 16384.
+ * Every expert must be device resident.  More than 64 tokens -> grouped tiled
+ * GEMMs; up to 64 tokens with H % 128 == 0 and I % 256 == 0 -> the
+ * weight-streaming kernels for the two projections.  2 <= E <= 32, top_k = 2, H % 64 == 0, I % 64 == 0, both <= 16384.
  * dbg: the fields of haq_moe_debug (q and hq receive the uint8 codes) plus the zero
  * points zx [T] and zh [2T] (sorted order); every field optional.               */
 typedef struct haq_expert_colsum {
