@@ -404,14 +404,14 @@ def haq_moe_w8a8_ffn_asym(x, logits, s_in, experts, colsums, I: int, *, out=None
 
 
 # ---- the CPU side of the offload runtime (Section III.B.3, III.C.1a-b) ----------------------------
-def haq_cpu_expert_create(w1q, w3q, w2q, sw1, sw3, sw2, s_mid):
+def haq_cpu_expert_create(w1q, w3q, w2q, sw1, sw3, sw2, s_mid, keep_codes: bool = False):
     """CPU tensors: canonical int8 matrices w1q, w3q [H,I], w2q [I,H], their scales and s_mid.  Returns an opaque handle
     to the expert's dequantised floating-point copy (free it with haq_cpu_expert_destroy)."""
     H, I = w1q.shape
     for t in (w1q, w3q, w2q, sw1, sw3, sw2, s_mid):
         assert t.device.type == "cpu" and t.is_contiguous()
     h = C.c_void_p()
-    _check(lib().haq_cpu_expert_create(_ptr(w1q), _ptr(w3q), _ptr(w2q), _ptr(sw1), _ptr(sw3), _ptr(sw2), _ptr(s_mid), H, I, C.byref(h)))
+    _check(lib().haq_cpu_expert_create(_ptr(w1q), _ptr(w3q), _ptr(w2q), _ptr(sw1), _ptr(sw3), _ptr(sw2), _ptr(s_mid), H, I, int(bool(keep_codes)), C.byref(h)))
     return h
 
 

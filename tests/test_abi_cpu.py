@@ -195,12 +195,13 @@ def test_cpu_expert_matches_the_oracle_bit_for_bit_for_any_thread_count():
         ex = m["experts"][1]
         ref, mid_ref = oracle.cpu_expert_ffn(m["X"], m["s_in"], oracle.cpu_expert(ex), dumps=True)
         t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
-        h = haq.haq_cpu_expert_create(t(ex.w1), t(ex.w3), t(ex.w2), t(ex.sw1), t(ex.sw3), t(ex.sw2), t(ex.s_mid))
-        try:
-            for nt in (1, 3, 0):
-                y = haq.haq_cpu_expert_ffn(h, t(m["X"]), t(m["s_in"]), H, nt).numpy()
-                assert np.array_equal(y.view(np.uint16), ref.view(np.uint16)), (seed, nt)
-            y0 = haq.haq_cpu_expert_ffn(h, t(m["X"]), None, H, 2).numpy()
-            assert np.array_equal(y0.view(np.uint16), oracle.cpu_expert_ffn(m["X"], np.ones(H, np.float32), oracle.cpu_expert(ex)).view(np.uint16))
-        finally:
-            haq.haq_cpu_expert_destroy(h)
+        for keep_codes in (False, True):   # the binary32 copy made at load time; the codes dequantised in the inner loop
+            h = haq.haq_cpu_expert_create(t(ex.w1), t(ex.w3), t(ex.w2), t(ex.sw1), t(ex.sw3), t(ex.sw2), t(ex.s_mid), keep_codes)
+            try:
+                for nt in (1, 3, 0):
+                    y = haq.haq_cpu_expert_ffn(h, t(m["X"]), t(m["s_in"]), H, nt).numpy()
+                    assert np.array_equal(y.view(np.uint16), ref.view(np.uint16)), (seed, nt, keep_codes)
+                y0 = haq.haq_cpu_expert_ffn(h, t(m["X"]), None, H, 2).numpy()
+                assert np.array_equal(y0.view(np.uint16), oracle.cpu_expert_ffn(m["X"], np.ones(H, np.float32), oracle.cpu_expert(ex)).view(np.uint16))
+            finally:
+                haq.haq_cpu_expert_destroy(h)

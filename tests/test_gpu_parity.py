@@ -825,9 +825,10 @@ def test_zero_token_calls_return_empty_outputs_on_every_block_level_entry_point(
 
 # ------------------------------------------------------------------ offload policy: Eq. 7-8 decision and CPU experts
 def _cpu_handles(experts, ids):
+    """CPU copies of the experts, alternately as binary32 copies and as kept int8 codes (same results)."""
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a))
     return {e: haq.haq_cpu_expert_create(t(experts[e].w1), t(experts[e].w3), t(experts[e].w2), t(experts[e].sw1), t(experts[e].sw3),
-                                         t(experts[e].sw2), t(experts[e].s_mid)) for e in ids}
+                                         t(experts[e].sw2), t(experts[e].s_mid), keep_codes=bool(e & 1)) for e in ids}
 
 
 @pytest.mark.parametrize("t_e,lat_cpu,lat_gpu", [(10.0, 1.0, 0.5), (3.0, 1.0, 0.9), (0.4, 1.0, 0.1), (5.0, 0.2, 0.5)])
