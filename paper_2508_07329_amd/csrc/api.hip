@@ -1096,9 +1096,8 @@ int32_t haq_moe_w8a8_ffn_asym(const void* x_fp16, int64_t ldx, const void* logit
 
     int rc;
     if ((rc = launch_route_permute((const __half*)logits_fp16, ldl, T, E, tab, w.tab, idx, gw, counts, offsets, perm, inv, w.blk_counts,
-                                   st)) != HAQ_OK)
+                                   st, cst, cstab)) != HAQ_OK)
         return rc;
-    if ((rc = launch_set_cstab(cst, E, cstab, st)) != HAQ_OK) return rc;
     // tokens: one row of codes per (token, expert) pair in sorted order, zero point and scale with it
     AsymRowArgs qa{};
     qa.x = (const __half*)x_fp16;

@@ -10,6 +10,10 @@ namespace haq {
 
 namespace {
 
+struct ColsumAll {
+    ColsumTab e[32];
+};
+
 // One work-group does the whole routing side: router top-2 for every token, then a stable
 // counting sort of the P = 2T pairs by expert (thread i owns a contiguous run of pair ids, so
 // ranks inside an expert follow pair id), and it drops the expert table into device memory
@@ -19,13 +23,16 @@ constexpr int ROUTE_SINGLE_MAX = 256;  // longer batches take the multi-work-gro
 __global__ __launch_bounds__(PERM_THREADS) void route_permute_kernel(const __half* logits, int64_t ldl, int T, int E,
                                                                      TabAll tab, ExpertTab* tab_dev, int32_t* idx,
                                                                      float* gw, int32_t* counts, int32_t* offsets,
-                                                                     int32_t* perm, int32_t* inv) {
+                                                                     int32_t* perm, int32_t* inv, ColsumAll cs, ColsumTab* cs_dev) {
     extern __shared__ int32_t sm[];  // cnt[E][PERM_THREADS], then off[E + 1]
     int32_t* cnt = sm;
     int32_t* off = sm + E * PERM_THREADS;
     const int tid = threadIdx.x;
     const int P = 2 * T;
-    if (tid < E) tab_dev[tid] = tab.e[tid];
+    if (tid < E) {
+        tab_dev[tid] = tab.e[tid];
+        if (cs_dev) cs_dev[tid] = cs.e[tid];  // asymmetric codes: the experts' column-sum table travels the same way
+    }
     for (int t = tid; t < T; t += PERM_THREADS) route_token(logits + (size_t)t * ldl, E, idx + 2 * t, gw + 2 * t);
     __syncthreads();  // idx is re-read below by other threads (global memory, same work-group)
     const int seg = (P + PERM_THREADS - 1) / PERM_THREADS;
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_count_kernel(const __half* l
 __global__ __launch_bounds__(RT_THREADS) void permute_kernel(int T, int E, TabAll tab, ExpertTab* tab_dev,
                                                              const int32_t* idx, const int32_t* blk_counts, int nblk,
                                                              int32_t* counts, int32_t* offsets, int32_t* perm,
-                                                             int32_t* inv) {
+                                                             int32_t* inv, ColsumAll cs, ColsumTab* cs_dev) {
     __shared__ int32_t total[32], before[32], base[32];
     __shared__ int32_t wave_cnt[RT_THREADS / 64][32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -126,6 +133,7 @@ __global__ __launch_bounds__(RT_THREADS) void permute_kernel(int T, int E, TabAl
         before[tid] = bef;
         if (blockIdx.x == 0) {
             tab_dev[tid] = tab.e[tid];
+            if (cs_dev) cs_dev[tid] = cs.e[tid];
             counts[tid] = tot;
         }
     }
@@ -259,19 +267,24 @@ int route_blocks(int T) { return T > ROUTE_SINGLE_MAX ? cdiv(T, RT_THREADS) : 0;
 
 int launch_route_permute(const __half* logits, int64_t ldl, int T, int E, const ExpertTab* tab_host, ExpertTab* tab_dev,
                          int32_t* idx, float* gw, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                         int32_t* blk_counts, hipStream_t st) {
+                         int32_t* blk_counts, hipStream_t st, const ColsumTab* cs_host, ColsumTab* cs_dev) {
     TabAll tab{};
     for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
+    ColsumAll cs{};
+    if (cs_host && cs_dev)
+        for (int e = 0; e < E; ++e) cs.e[e] = cs_host[e];
+    else
+        cs_dev = nullptr;
     if (const int nblk = route_blocks(T)) {
         hipLaunchKernelGGL(route_count_kernel, dim3(nblk), dim3(RT_THREADS), 0, st, logits, ldl, T, E, idx, gw, blk_counts);
         hipLaunchKernelGGL(permute_kernel, dim3(nblk), dim3(RT_THREADS), 0, st, T, E, tab, tab_dev, (const int32_t*)idx,
-                           (const int32_t*)blk_counts, nblk, counts, offsets, perm, inv);
+                           (const int32_t*)blk_counts, nblk, counts, offsets, perm, inv, cs, cs_dev);
         HAQ_CHECK_HIP(hipGetLastError());
         return HAQ_OK;
     }
     const size_t sm = ((size_t)E * PERM_THREADS + E + 1) * sizeof(int32_t);
     hipLaunchKernelGGL(route_permute_kernel, dim3(1), dim3(PERM_THREADS), sm, st, logits, ldl, T, E, tab, tab_dev, idx, gw,
-                       counts, offsets, perm, inv);
+                       counts, offsets, perm, inv, cs, cs_dev);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
@@ -297,23 +310,6 @@ int launch_set_tab(const ExpertTab* tab_host, int E, ExpertTab* tab_dev, hipStre
     TabAll tab{};
     for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
     hipLaunchKernelGGL(set_tab_kernel, dim3(1), dim3(64), 0, st, tab, E, tab_dev);
-    HAQ_CHECK_HIP(hipGetLastError());
-    return HAQ_OK;
-}
-
-namespace {
-struct ColsumAll {
-    ColsumTab e[32];
-};
-__global__ void set_cstab_kernel(ColsumAll tab, int E, ColsumTab* tab_dev) {
-    if ((int)threadIdx.x < E) tab_dev[threadIdx.x] = tab.e[threadIdx.x];
-}
-}  // namespace
-
-int launch_set_cstab(const ColsumTab* tab_host, int E, ColsumTab* tab_dev, hipStream_t st) {
-    ColsumAll tab{};
-    for (int e = 0; e < E; ++e) tab.e[e] = tab_host[e];
-    hipLaunchKernelGGL(set_cstab_kernel, dim3(1), dim3(64), 0, st, tab, E, tab_dev);
     HAQ_CHECK_HIP(hipGetLastError());
     return HAQ_OK;
 }
