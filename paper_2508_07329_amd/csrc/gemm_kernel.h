@@ -182,7 +182,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
         if (ASYM) cs_s[i] = cs;
     }
 
-    // direct-to-LDS load descriptors: group g = wave + i*NW covers 64 rows of one 16-byte chunk
+    // direct-to-LDS load descriptors: group g = wave + i*NW covers 64 rows of one 16-byte chunk.  The base of a
+    // group is the same for all lanes of the wave (scalar registers; the tile origin and the expert's matrix come
+    // out of memory and are made wave-uniform explicitly), the lane adds 16 bytes per row: the loads then use the
+    // scalar-base + 32-bit lane-offset form and their addresses cost no vector instructions in the K loop.
+    auto uniform_ptr = [](const int8_t* p) {
+        const uint64_t v = (uint64_t)(uintptr_t)p;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return (const int8_t*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+    };
+    const int m0u = __builtin_amdgcn_readfirstlane(tc.m0), n0u = __builtin_amdgcn_readfirstlane(tc.n0);
+    const int8_t* Au = uniform_ptr(a.A);
+    const int8_t* Bu = uniform_ptr(Bmat);
+    const uint32_t lane_off = (uint32_t)lane * 16u;
     const int8_t* gsrc[LPW];
     size_t gstep[LPW];
 #pragma unroll
@@ -190,19 +202,23 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64, MINB) void gemm_i8_kernel(G
         const int g = wave + i * NW;
         if (g < GA) {
             const int c = g / (BM / 64), rg = g % (BM / 64);
-            gsrc[i] = a.A + ((size_t)c * a.R + tc.m0 + rg * 64 + lane) * 16;
+            gsrc[i] = Au + ((size_t)c * a.R + m0u + rg * 64) * 16;
             gstep[i] = (size_t)4 * a.R * 16;
         } else {
             const int g2 = g - GA;
             const int c = g2 / (BN / 64), rg = g2 % (BN / 64);
-            gsrc[i] = Bmat + ((size_t)c * a.Npad + tc.n0 + rg * 64 + lane) * 16;
+            gsrc[i] = Bu + ((size_t)c * a.Npad + n0u + rg * 64) * 16;
             gstep[i] = (size_t)4 * a.Npad * 16;
         }
     }
     auto load_stage = [&](int buf, int kt) {
+        // (the empty asm keeps the widening of the lane offset next to its use: hoisted out of the loop as a 64-bit
+        // vector value it would turn every address back into a vector add)
+        uint32_t lo = lane_off;
+        asm volatile("" : "+v"(lo));
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int8_t* src = gsrc[i] + (size_t)kt * gstep[i];
+            const int8_t* src = gsrc[i] + (size_t)kt * gstep[i] + lo;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(uintptr_t)src,
                                              (__attribute__((address_space(3))) void*)(lds + buf * STAGE_BYTES + (wave + i * NW) * 1024),
                                              16, 0, 0);
