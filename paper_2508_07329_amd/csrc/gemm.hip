@@ -80,6 +80,35 @@ int launch_large(const GemmArgs& a, dim3 grid, hipStream_t st) {
     return HAQ_OK;
 }
 
+// 256 x 128 tiles, 8 waves (4 x 2 of 64 x 64), one work-group per CU: for dense problems that this tiling covers in
+// one round with most CUs busy (fc2 of the OPT-6.7B block: 8 x 32 tiles on 256 CUs).  A quarter fewer
+// direct-to-LDS bytes per matrix instruction than the 128 x 128 shape such problems would otherwise take: -2 %.
+using ShapeT = GemmShape<256, 128, 4, 2, 3>;
+int launch_tall(const GemmArgs& a, dim3 grid, hipStream_t st) {
+    auto kern = gemm_i8_kernel<256, 128, 4, 2, 3, 1, EPI_LINEAR, false>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ShapeT::LDS_BYTES);
+    });
+    HAQ_CHECK_HIP(attr_err);
+    hipLaunchKernelGGL(kern, grid, dim3(ShapeT::THREADS), ShapeT::LDS_BYTES, st, a);
+    HAQ_CHECK_HIP(hipGetLastError());
+    return HAQ_OK;
+}
+
+int cu_count() {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int devid = 0, v = 0;
+        if (hipGetDevice(&devid) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, devid) == hipSuccess && v > 0)
+            n_cu = v;
+        else
+            n_cu = 256;
+    }
+    return n_cu;
+}
+
 }  // namespace
 
 int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
@@ -90,6 +119,9 @@ int launch_gemm(const GemmArgs& a, int epi, hipStream_t st) {
     if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg) {
         const int64_t tiles_l = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 256);
         if (tiles_l >= LARGE_TILE_MIN) return launch_large(a, dim3((unsigned)round_up(tiles_l, 8)), st);
+        const int64_t tiles_t = (int64_t)cdiv(a.M, 256) * cdiv(a.N, 128);
+        const int n_cu = cu_count();
+        if (tiles_t <= n_cu && 4 * tiles_t > 3 * n_cu) return launch_tall(a, dim3((unsigned)round_up(tiles_t, 8)), st);
     }
     if (!a.offsets && epi == EPI_LINEAR && !a.acc_dbg && mt * ntn <= SMALL_TILE_LIMIT) {
         const int ntn_s = cdiv(a.N, BN_S), mt_s = cdiv(a.M, 128);

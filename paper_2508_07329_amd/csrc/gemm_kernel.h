@@ -69,9 +69,11 @@ __device__ __forceinline__ TileCoord decode_tile(const GemmArgs& a) {
     // work-groups resident on one XCD at a time then form a compact block of the tile grid
     // (a row tile's activations and a channel tile's weights are each shared by ~8 of them
     // in L2) instead of one channel tile across every row tile of every expert
-    const int band = id / (TILE_BAND * ntn), rem = id % (TILE_BAND * ntn);
-    const int band_rows = min(TILE_BAND, total_mt - band * TILE_BAND);
-    int mi = band * TILE_BAND + rem % band_rows;
+    // (256-row tiles: bands of 4, the same 1024 rows; with one work-group per CU an XCD then holds 4 x 8 tiles)
+    constexpr int BAND = BM >= 256 ? TILE_BAND / 2 : TILE_BAND;
+    const int band = id / (BAND * ntn), rem = id % (BAND * ntn);
+    const int band_rows = min(BAND, total_mt - band * BAND);
+    int mi = band * BAND + rem % band_rows;
     tc.n0 = (rem / band_rows) * BN;
     if (!a.offsets) {
         tc.m0 = mi * BM;

@@ -133,11 +133,13 @@ def test_linear_opt125m_config():
 @pytest.mark.parametrize("T,K,N,act", [(300, 832, 1040, "relu"), (1, 64, 16, "none"), (257, 1024, 272, "none"),
                                         (513, 2048, 768, "relu"), (5, 32768, 48, "none"), (130, 65536, 16, "relu"),
                                         (4101, 128, 32, "relu"), (2051, 4096, 64, "none"),
-                                        (4100, 128, 7696, "relu"), (8200, 64, 4112, "none")])
+                                        (4100, 128, 7696, "relu"), (8200, 64, 4112, "none"),
+                                        (2000, 64, 3984, "relu"), (1600, 128, 4000, "none")])
 def test_linear_ragged_shapes(T, K, N, act):
     """Two are long enough for the pipelined quantisation kernel (its transposed write-out of the packed codes ends
-    in a partial block of rows); the last two have at least 512 tiles of 256 x 256 and take the large-tile
-    instantiation of the GEMM (ragged last row and channel tiles) on the call without debug outputs."""
+    in a partial block of rows); two have at least 512 tiles of 256 x 256 and take the large-tile instantiation of
+    the GEMM, the last two fill one round of 256 x 128 tiles and take that instantiation (ragged last row and
+    channel tiles), each on the call without debug outputs."""
     X, _, _ = hi.hidden_states(T + K, T, K, n_outlier=3)
     _linear_case(X, hi.gaussian_weight(T + K, 0, K, N), act)
 
